@@ -1,0 +1,164 @@
+"""ctypes front end of the CPU oracle (freeze_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg, never by the library's product path.  It takes
+and returns numpy arrays; all arithmetic is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "freeze_oracle.c")
+_LIB = os.path.join(_HERE, "libfreeze_oracle.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (no fast-math, no BLAS)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-pthread", "-Wall",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        c_p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.fz_oracle_host_threads.restype = i32
+        L.fz_oracle_knn.restype = i32
+        L.fz_oracle_knn.argtypes = [c_p, i64, c_p, i32, i64, i64, i32, c_p, c_p, i32]
+        L.fz_oracle_vote.restype = i32
+        L.fz_oracle_vote.argtypes = [c_p, c_p, i64, i32, i32, i32, c_p, c_p, c_p]
+        L.fz_oracle_confidence.restype = i32
+        L.fz_oracle_confidence.argtypes = [c_p, c_p, c_p, i64, i32, i32, c_p, c_p]
+        L.fz_oracle_compact.restype = i64
+        L.fz_oracle_compact.argtypes = [c_p, c_p, i64, c_p]
+        L.fz_oracle_cascade.restype = i32
+        L.fz_oracle_cascade.argtypes = [i32, c_p, i64, c_p, c_p, c_p, c_p, c_p, c_p, i32, c_p, c_p, c_p,
+                                        c_p, i32]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _entries(entries: np.ndarray) -> Tuple[np.ndarray, int]:
+    if entries.dtype == np.float32:
+        return np.ascontiguousarray(entries), F32
+    if entries.dtype == np.uint16:
+        return np.ascontiguousarray(entries), BF16
+    raise TypeError("entries must be float32 or uint16 (bf16 bit patterns)")
+
+
+def host_threads() -> int:
+    return int(lib().fz_oracle_host_threads())
+
+
+def knn(queries: np.ndarray, entries: np.ndarray, k: int, nthreads: int = 0):
+    """Exact k-NN.  Returns (idx [b,k] int32, sqdist [b,k] float64, threads used)."""
+    q = np.ascontiguousarray(queries, dtype=np.float32)
+    e, kind = _entries(entries)
+    b, d = q.shape
+    n, d2 = e.shape
+    assert d == d2
+    idx = np.empty((b, k), dtype=np.int32)
+    dist = np.empty((b, k), dtype=np.float64)
+    used = lib().fz_oracle_knn(_ptr(q), b, _ptr(e), kind, n, d, k, _ptr(idx), _ptr(dist), nthreads)
+    if used < 0:
+        raise ValueError("fz_oracle_knn: invalid arguments")
+    return idx, dist, used
+
+
+def vote(labels: np.ndarray, nbr_idx: np.ndarray, num_classes: int, vote_threshold: int):
+    """Returns (label [b] int32, votes [b] int32, hit [b] uint8)."""
+    lab = np.ascontiguousarray(labels, dtype=np.int32)
+    nbr = np.ascontiguousarray(nbr_idx, dtype=np.int32)
+    b, k = nbr.shape
+    out_l = np.empty(b, dtype=np.int32)
+    out_v = np.empty(b, dtype=np.int32)
+    out_h = np.empty(b, dtype=np.uint8)
+    rc = lib().fz_oracle_vote(_ptr(lab), _ptr(nbr), b, k, num_classes, vote_threshold, _ptr(out_l),
+                              _ptr(out_v), _ptr(out_h))
+    if rc != 0:
+        raise ValueError("fz_oracle_vote: invalid arguments")
+    return out_l, out_v, out_h
+
+
+def confidence(labels: np.ndarray, nbr_idx: np.ndarray, nbr_sqdist: np.ndarray, num_classes: int):
+    """Paper's distance-weighted confidence.  Returns (label [b] int32, confidence [b] float64)."""
+    lab = np.ascontiguousarray(labels, dtype=np.int32)
+    nbr = np.ascontiguousarray(nbr_idx, dtype=np.int32)
+    dist = np.ascontiguousarray(nbr_sqdist, dtype=np.float64)
+    b, k = nbr.shape
+    out_l = np.empty(b, dtype=np.int32)
+    out_c = np.empty(b, dtype=np.float64)
+    rc = lib().fz_oracle_confidence(_ptr(lab), _ptr(nbr), _ptr(dist), b, k, num_classes, _ptr(out_l),
+                                    _ptr(out_c))
+    if rc != 0:
+        raise ValueError("fz_oracle_confidence: invalid arguments")
+    return out_l, out_c
+
+
+def lookup(queries, entries, labels, num_classes, k, vote_threshold, nthreads: int = 0):
+    """k-NN + vote.  Returns dict(idx, sqdist, label, votes, hit, threads)."""
+    idx, dist, used = knn(queries, entries, k, nthreads)
+    lab, votes, hit = vote(labels, idx, num_classes, vote_threshold)
+    return dict(idx=idx, sqdist=dist, label=lab, votes=votes, hit=hit, threads=used)
+
+
+def compact(hit: np.ndarray, sel_in: np.ndarray) -> np.ndarray:
+    h = np.ascontiguousarray(hit, dtype=np.uint8)
+    s = np.ascontiguousarray(sel_in, dtype=np.int32)
+    out = np.empty_like(s)
+    m = lib().fz_oracle_compact(_ptr(h), _ptr(s), s.shape[0], _ptr(out))
+    return out[:m].copy()
+
+
+def cascade(queries: Sequence[np.ndarray], entries: Sequence[np.ndarray], labels: Sequence[np.ndarray],
+            num_classes: Sequence[int], k: int, thresholds: Sequence[int], nthreads: int = 0):
+    """Cascaded lookup.  Returns (label [b], exit_layer [b], hits_per_layer [L], threads used)."""
+    L = len(queries)
+    qs = [np.ascontiguousarray(q, dtype=np.float32) for q in queries]
+    es: List[np.ndarray] = []
+    kinds = np.empty(L, dtype=np.int32)
+    for l, e in enumerate(entries):
+        ee, kind = _entries(e)
+        es.append(ee)
+        kinds[l] = kind
+    labs = [np.ascontiguousarray(x, dtype=np.int32) for x in labels]
+    b = qs[0].shape[0]
+    ns = np.array([e.shape[0] for e in es], dtype=np.int64)
+    ds = np.array([e.shape[1] for e in es], dtype=np.int64)
+    for l in range(L):
+        assert qs[l].shape == (b, ds[l])
+    ncls = np.array(list(num_classes), dtype=np.int32)
+    thr = np.array(list(thresholds), dtype=np.int32)
+    vp = ctypes.c_void_p * L
+    qp = vp(*[q.ctypes.data for q in qs])
+    ep = vp(*[e.ctypes.data for e in es])
+    lp = vp(*[x.ctypes.data for x in labs])
+    out_l = np.empty(b, dtype=np.int32)
+    out_x = np.empty(b, dtype=np.int32)
+    hits = np.zeros(L, dtype=np.int64)
+    used = lib().fz_oracle_cascade(L, qp, b, ep, _ptr(kinds), _ptr(ns), _ptr(ds), lp, _ptr(ncls), k,
+                                   _ptr(thr), _ptr(out_l), _ptr(out_x), _ptr(hits), nthreads)
+    if used < 0:
+        raise ValueError("fz_oracle_cascade: invalid arguments")
+    return out_l, out_x, hits, used
