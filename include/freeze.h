@@ -1,0 +1,150 @@
+/*
+ * freeze.h - C ABI of the MI355X (gfx950) Freeze Inference cache-lookup library.
+ *
+ * The library implements the per-layer approximate cache of the paper
+ * "Accelerating Deep Learning Inference via Freezing" (Sec. 2.1 and Sec. 3):
+ * a layer's cache is a list of <intermediate output, label> pairs
+ * (Pseudocode 1, ConstructCache); a look-up finds the k cached outputs nearest
+ * to a query activation, takes a vote over their labels and reports a hit when
+ * the agreement reaches the layer's threshold (Sec. 3, the cache look-up API;
+ * Pseudocode 1, FreezeInference); a cascade tries the layers in order and
+ * forwards only the requests that missed (Pseudocode 1; Sec. 5, "Freeze
+ * Inference on GPUs": the batch is rebuilt without the frozen items).
+ *
+ * Conventions for every entry point
+ *  - All data pointers are DEVICE pointers on the current HIP device unless the
+ *    parameter comment says "host".  The caller owns every buffer; the library
+ *    allocates no device memory and frees nothing it is given.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on it and return; they never synchronise.
+ *    Buffers must stay alive until the enqueued work has finished.
+ *  - Return value: FREEZE_OK or a negative error code.  Arguments are checked
+ *    on the host before anything is enqueued; on an argument error nothing is
+ *    launched and no output is written.  Errors never abort or throw.
+ *  - Distances are SQUARED Euclidean distances in fp32.
+ *  - Neighbour order is (distance, entry index) ascending: equal distances rank
+ *    the lower entry index first.
+ *  - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
+ */
+#ifndef FREEZE_H
+#define FREEZE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct freeze_ctx freeze_ctx; /* opaque; host memory; holds per-layer descriptors only */
+
+enum {
+    FREEZE_OK = 0,
+    FREEZE_EINVAL = -1,     /* null pointer, size or parameter out of range */
+    FREEZE_ELAYER = -2,     /* layer index out of range */
+    FREEZE_ENOTBUILT = -3,  /* layer has no cache yet */
+    FREEZE_EWORKSPACE = -4, /* storage / workspace buffer too small or misaligned */
+    FREEZE_EHIP = -5        /* a HIP runtime call failed (launch error) */
+};
+
+enum { FREEZE_F32 = 0, FREEZE_BF16 = 1 }; /* element type of the entries handed to freeze_cache_build */
+
+/* Largest k and largest re-scoring width accepted by the look-ups. */
+#define FREEZE_MAX_K 64
+#define FREEZE_MAX_RESCORE 64
+
+/* Create / destroy a context with `num_layers` empty layer slots (host-only state). */
+int freeze_create(freeze_ctx **out, int num_layers);
+int freeze_destroy(freeze_ctx *ctx);
+
+/* Bytes of device memory freeze_cache_build needs in `storage` for an n x d cache
+ * (bf16 rows padded for the matrix cores, fp32 squared norms, labels, and the fp32
+ * rows when the entries are given in fp32).  0 on invalid arguments. */
+size_t freeze_cache_storage_bytes(int64_t n, int64_t d, int entries_dtype);
+
+/*
+ * Ingest one layer's cache (Pseudocode 1, ConstructCache: the list of
+ * <intermediate output, predicted label> pairs of a layer).
+ *   entries  [n, d] row-major, fp32 or bf16 (entries_dtype); the stored values ARE the
+ *            cache: distances are measured to exactly these values.
+ *   labels   [n] int32, each in [0, num_classes).
+ *   storage  caller-owned device buffer of >= freeze_cache_storage_bytes() bytes,
+ *            256-byte aligned; everything the look-ups need is copied into it, so
+ *            `entries` and `labels` may be released once the stream has run the call.
+ *            It must outlive every look-up on this layer.
+ * Rebuilding a layer replaces its cache.  Limits: 1 <= n < 2^31 - 512, 1 <= d <= 2^24.
+ */
+int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entries_dtype, int64_t n,
+                       int64_t d, const int32_t *labels, int32_t num_classes, void *storage,
+                       size_t storage_bytes, void *stream);
+
+/* Bytes of workspace freeze_lookup needs for a batch of b queries. 0 on invalid arguments. */
+size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b, int k, int rescore_r);
+
+/*
+ * Look up a batch of activations in one layer's cache (Sec. 3, cache look-up
+ * API: k nearest neighbours -> k (label, distance) tuples -> label with the most
+ * occurrences m_i among the k -> hit decision; Pseudocode 1, FreezeInference).
+ *   queries        [b, d] fp32 row-major.
+ *   k              neighbours per query, 1 <= k <= min(n, FREEZE_MAX_K).
+ *   vote_threshold hit iff the winning label holds >= vote_threshold of the k
+ *                  neighbours; 1 <= vote_threshold <= k.
+ *   rescore_r      candidates per query kept by the bf16 matrix-core pass and
+ *                  re-scored exactly in fp32; 0 = library default, else
+ *                  k <= rescore_r <= FREEZE_MAX_RESCORE (clamped to n).
+ *   out_labels     [b] int32  winning label (equal counts -> smaller label id).
+ *   out_hit        [b] uint8  1 = cache hit.
+ *   out_votes      [b] int32  occurrences m of the winning label.
+ *   out_nbr_idx    [b, k] int32  entry indices, nearest first.
+ *   out_nbr_dist   [b, k] fp32   squared distances, computed as sum (q_i - c_i)^2
+ *                  in fp32 (exactly 0 for an entry identical to the query).
+ *   workspace      >= freeze_lookup_workspace_bytes() bytes, 256-byte aligned;
+ *                  scratch only, contents undefined afterwards.
+ * b == 0 is a no-op.  Calls that share a workspace must be ordered on one stream.
+ */
+int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k, int vote_threshold,
+                  int rescore_r, int32_t *out_labels, uint8_t *out_hit, int32_t *out_votes,
+                  int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
+/* Bytes of workspace freeze_lookup_cascade needs. `layers` is a host array. 0 on invalid arguments. */
+size_t freeze_cascade_workspace_bytes(const freeze_ctx *ctx, int num_layers, const int *layers, int64_t b,
+                                      int k, int rescore_r);
+
+/*
+ * Cascaded look-up (Pseudocode 1, FreezeInference; Sec. 5, batch reconstruction):
+ * every request is looked up in layers[0]; the requests that miss are compacted
+ * (order preserved) and looked up in layers[1], and so on.  No host
+ * synchronisation: the number of surviving requests stays on the device.
+ *   layers             host array [num_layers] of layer indices, tried in order.
+ *   queries_per_layer  host array [num_layers] of device pointers; entry l is
+ *                      [b, d_l] fp32; row i of every entry belongs to request i.
+ *   vote_thresholds    host array [num_layers].
+ *   out_labels         [b] int32  label of the first layer that hit, -1 if none.
+ *   out_exit_layer     [b] int32  position (0-based, in `layers`) of that layer, -1 if none
+ *                      (the model's own output layer decides; outside this library).
+ *   out_hits_per_layer [num_layers] int64  requests frozen at each position.
+ */
+int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers,
+                          const float *const *queries_per_layer, int64_t b, int k,
+                          const int *vote_thresholds, int rescore_r, int32_t *out_labels,
+                          int32_t *out_exit_layer, int64_t *out_hits_per_layer, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
+ * Batch reconstruction on its own (Sec. 5): writes to sel_out the entries
+ * sel_in[j] (or j itself when sel_in is NULL) with hit[j] == 0, j < count, in
+ * order, and their number to *out_count.
+ *   hit       [count] uint8;  sel_in [count] int32 or NULL;  sel_out [count] int32;
+ *   out_count [1] int32.
+ */
+int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t count, int32_t *sel_out,
+                          int32_t *out_count, void *stream);
+
+/* Static description of an error code (host string, never NULL). */
+const char *freeze_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREEZE_H */

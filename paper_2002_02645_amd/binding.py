@@ -1,0 +1,219 @@
+"""Thin ctypes binding of the C ABI declared in include/freeze.h.
+
+Argument marshalling only: every step of a look-up runs in the HIP kernels of
+libfreeze_hip.so.  PyTorch supplies device memory (tensors) and the stream.
+There is no fallback: if the library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "_lib", "libfreeze_hip.so")
+
+FREEZE_OK, FREEZE_EINVAL, FREEZE_ELAYER, FREEZE_ENOTBUILT, FREEZE_EWORKSPACE, FREEZE_EHIP = 0, -1, -2, -3, -4, -5
+FREEZE_F32, FREEZE_BF16 = 0, 1
+
+_lib = None
+
+
+class FreezeError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().freeze_strerror(code).decode() if _lib is not None else str(code)
+        super().__init__(f"{where}: {msg} ({code})")
+
+
+def lib():
+    """Load libfreeze_hip.so (built by `python -m paper_2002_02645_amd.build` / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build the HIP library first "
+                           "(python -m paper_2002_02645_amd.build); there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    p, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    L.freeze_create.restype = i32
+    L.freeze_create.argtypes = [ctypes.POINTER(p), i32]
+    L.freeze_destroy.restype = i32
+    L.freeze_destroy.argtypes = [p]
+    L.freeze_cache_storage_bytes.restype = sz
+    L.freeze_cache_storage_bytes.argtypes = [i64, i64, i32]
+    L.freeze_cache_build.restype = i32
+    L.freeze_cache_build.argtypes = [p, i32, p, i32, i64, i64, p, ctypes.c_int32, p, sz, p]
+    L.freeze_lookup_workspace_bytes.restype = sz
+    L.freeze_lookup_workspace_bytes.argtypes = [p, i32, i64, i32, i32]
+    L.freeze_lookup.restype = i32
+    L.freeze_lookup.argtypes = [p, i32, p, i64, i32, i32, i32, p, p, p, p, p, p, sz, p]
+    L.freeze_cascade_workspace_bytes.restype = sz
+    L.freeze_cascade_workspace_bytes.argtypes = [p, i32, p, i64, i32, i32]
+    L.freeze_lookup_cascade.restype = i32
+    L.freeze_lookup_cascade.argtypes = [p, i32, p, p, i64, i32, p, i32, p, p, p, p, sz, p]
+    L.freeze_compact_misses.restype = i32
+    L.freeze_compact_misses.argtypes = [p, p, i64, p, p, p]
+    L.freeze_strerror.restype = ctypes.c_char_p
+    L.freeze_strerror.argtypes = [i32]
+    _lib = L
+    return L
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(rc: int, where: str):
+    if rc != FREEZE_OK:
+        raise FreezeError(rc, where)
+
+
+# ---- functions with the names of the C entry points ---------------------------------------------
+
+def freeze_strerror(code: int) -> str:
+    return lib().freeze_strerror(code).decode()
+
+
+def freeze_create(num_layers: int) -> ctypes.c_void_p:
+    h = ctypes.c_void_p()
+    _check(lib().freeze_create(ctypes.byref(h), num_layers), "freeze_create")
+    return h
+
+
+def freeze_destroy(ctx) -> None:
+    _check(lib().freeze_destroy(ctx), "freeze_destroy")
+
+
+def freeze_cache_storage_bytes(n: int, d: int, entries_dtype: int) -> int:
+    return int(lib().freeze_cache_storage_bytes(n, d, entries_dtype))
+
+
+def freeze_cache_build(ctx, layer: int, entries: torch.Tensor, labels: torch.Tensor, num_classes: int,
+                       storage: torch.Tensor, stream=None) -> None:
+    assert entries.is_cuda and entries.is_contiguous() and entries.dim() == 2
+    assert labels.is_cuda and labels.dtype == torch.int32 and labels.is_contiguous()
+    dt = {torch.float32: FREEZE_F32, torch.bfloat16: FREEZE_BF16}[entries.dtype]
+    n, d = entries.shape
+    assert labels.numel() == n
+    _check(lib().freeze_cache_build(ctx, layer, _ptr(entries), dt, n, d, _ptr(labels), num_classes, _ptr(storage),
+                                    storage.numel() * storage.element_size(), _stream(stream)), "freeze_cache_build")
+
+
+def freeze_lookup_workspace_bytes(ctx, layer: int, b: int, k: int, rescore_r: int = 0) -> int:
+    return int(lib().freeze_lookup_workspace_bytes(ctx, layer, b, k, rescore_r))
+
+
+def freeze_lookup(ctx, layer: int, queries: torch.Tensor, k: int, vote_threshold: int, rescore_r: int,
+                  out_labels: torch.Tensor, out_hit: torch.Tensor, out_votes: torch.Tensor,
+                  out_nbr_idx: torch.Tensor, out_nbr_dist: torch.Tensor, workspace: torch.Tensor,
+                  stream=None) -> None:
+    assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous() and queries.dim() == 2
+    b = queries.shape[0]
+    _check(lib().freeze_lookup(ctx, layer, _ptr(queries), b, k, vote_threshold, rescore_r, _ptr(out_labels),
+                               _ptr(out_hit), _ptr(out_votes), _ptr(out_nbr_idx), _ptr(out_nbr_dist),
+                               _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "freeze_lookup")
+
+
+def freeze_cascade_workspace_bytes(ctx, layers: Sequence[int], b: int, k: int, rescore_r: int = 0) -> int:
+    arr = (ctypes.c_int * len(layers))(*layers)
+    return int(lib().freeze_cascade_workspace_bytes(ctx, len(layers), arr, b, k, rescore_r))
+
+
+def freeze_lookup_cascade(ctx, layers: Sequence[int], queries_per_layer: Sequence[torch.Tensor], k: int,
+                          vote_thresholds: Sequence[int], rescore_r: int, out_labels: torch.Tensor,
+                          out_exit_layer: torch.Tensor, out_hits_per_layer: torch.Tensor, workspace: torch.Tensor,
+                          stream=None) -> None:
+    nl = len(layers)
+    assert len(queries_per_layer) == nl and len(vote_thresholds) == nl
+    b = queries_per_layer[0].shape[0]
+    for q in queries_per_layer:
+        assert q.is_cuda and q.dtype == torch.float32 and q.is_contiguous() and q.shape[0] == b
+    larr = (ctypes.c_int * nl)(*layers)
+    tarr = (ctypes.c_int * nl)(*vote_thresholds)
+    qarr = (ctypes.c_void_p * nl)(*[q.data_ptr() for q in queries_per_layer])
+    _check(lib().freeze_lookup_cascade(ctx, nl, larr, qarr, b, k, tarr, rescore_r, _ptr(out_labels),
+                                       _ptr(out_exit_layer), _ptr(out_hits_per_layer), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)),
+           "freeze_lookup_cascade")
+
+
+def freeze_compact_misses(hit: torch.Tensor, sel_in: Optional[torch.Tensor], sel_out: torch.Tensor,
+                          out_count: torch.Tensor, stream=None) -> None:
+    assert hit.is_cuda and hit.dtype == torch.uint8
+    _check(lib().freeze_compact_misses(_ptr(hit), _ptr(sel_in), hit.numel(), _ptr(sel_out), _ptr(out_count),
+                                       _stream(stream)), "freeze_compact_misses")
+
+
+# ---- convenience holder: owns the context, the per-layer storage and a reusable workspace ---------
+
+class FreezeCache:
+    def __init__(self, num_layers: int, device="cuda:0"):
+        self.device = torch.device(device)
+        self.ctx = freeze_create(num_layers)
+        self.storage: Dict[int, torch.Tensor] = {}
+        self.meta: Dict[int, tuple] = {}
+        self._ws: Optional[torch.Tensor] = None
+
+    def close(self):
+        if self.ctx is not None:
+            freeze_destroy(self.ctx)
+            self.ctx = None
+
+    def _workspace(self, nbytes: int) -> torch.Tensor:
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def build_layer(self, layer: int, entries: torch.Tensor, labels: torch.Tensor, num_classes: int):
+        n, d = entries.shape
+        dt = FREEZE_F32 if entries.dtype == torch.float32 else FREEZE_BF16
+        nbytes = freeze_cache_storage_bytes(n, d, dt)
+        if nbytes == 0:
+            raise FreezeError(FREEZE_EINVAL, "freeze_cache_storage_bytes")
+        st = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        freeze_cache_build(self.ctx, layer, entries, labels, num_classes, st)
+        self.storage[layer] = st
+        self.meta[layer] = (n, d, num_classes)
+
+    def alloc_outputs(self, b: int, k: int):
+        dev = self.device
+        return dict(label=torch.empty(b, dtype=torch.int32, device=dev),
+                    hit=torch.empty(b, dtype=torch.uint8, device=dev),
+                    votes=torch.empty(b, dtype=torch.int32, device=dev),
+                    idx=torch.empty((b, k), dtype=torch.int32, device=dev),
+                    dist=torch.empty((b, k), dtype=torch.float32, device=dev))
+
+    def lookup(self, layer: int, queries: torch.Tensor, k: int, vote_threshold: int, rescore_r: int = 0,
+               out: Optional[dict] = None) -> dict:
+        b = queries.shape[0]
+        if out is None:
+            out = self.alloc_outputs(b, k)
+        nbytes = freeze_lookup_workspace_bytes(self.ctx, layer, b, k, rescore_r)
+        ws = self._workspace(nbytes)
+        freeze_lookup(self.ctx, layer, queries, k, vote_threshold, rescore_r, out["label"], out["hit"], out["votes"],
+                      out["idx"], out["dist"], ws)
+        return out
+
+    def lookup_cascade(self, layers: Sequence[int], queries_per_layer: List[torch.Tensor], k: int,
+                       vote_thresholds: Sequence[int], rescore_r: int = 0, out: Optional[dict] = None) -> dict:
+        b = queries_per_layer[0].shape[0]
+        if out is None:
+            out = dict(label=torch.empty(b, dtype=torch.int32, device=self.device),
+                       exit_layer=torch.empty(b, dtype=torch.int32, device=self.device),
+                       hits_per_layer=torch.empty(len(layers), dtype=torch.int64, device=self.device))
+        nbytes = freeze_cascade_workspace_bytes(self.ctx, layers, b, k, rescore_r)
+        if nbytes == 0:
+            raise FreezeError(FREEZE_EINVAL, "freeze_cascade_workspace_bytes")
+        ws = self._workspace(nbytes)
+        freeze_lookup_cascade(self.ctx, layers, queries_per_layer, k, vote_thresholds, rescore_r, out["label"],
+                              out["exit_layer"], out["hits_per_layer"], ws)
+        return out

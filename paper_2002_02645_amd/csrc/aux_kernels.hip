@@ -1,0 +1,380 @@
+// Kernels around the distance pass: cache ingest, query preparation, the finishing
+// kernel (merge of per-split candidate lists, exact fp32 re-scoring, final top-k, label
+// vote, hit decision), miss compaction and the cascade's scatter.  gfx950 only.
+#include "freeze_internal.h"
+
+namespace fz {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// fp32 -> bf16, round to nearest even (inputs are finite by contract; NaN stays NaN)
+__device__ __forceinline__ uint16_t bf16_rne(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// Sum over the 256 threads of a block in a fixed order; result valid in every thread.
+__device__ __forceinline__ float block_sum_256(float v, float *scratch4)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch4[w] = v;
+    __syncthreads();
+    return (scratch4[0] + scratch4[1]) + (scratch4[2] + scratch4[3]);
+}
+
+// ---------------------------------------------------------------------------------------
+// Cache ingest (Pseudocode 1, ConstructCache: the layer's list of <output, label>).
+// One block per padded cache row: bf16 copy (round to nearest even when given fp32), zero
+// padding, |c|^2 of the bf16 row in fp32, optional fp32 copy for exact re-scoring.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, int dtype, int64_t n, int64_t d,
+                                                          int64_t d_pad, uint16_t *c_bf, float *norm, float *c_f32)
+{
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    uint16_t *dst = c_bf + row * d_pad;
+    float ss = 0.f;
+    if (row < n) {
+        for (int64_t i = threadIdx.x; i < d_pad; i += 256) {
+            uint16_t h = 0;
+            float f = 0.f;
+            if (i < d) {
+                if (dtype == 0) {
+                    f = reinterpret_cast<const float *>(entries)[row * d + i];
+                    h = bf16_rne(f);
+                } else {
+                    h = reinterpret_cast<const uint16_t *>(entries)[row * d + i];
+                }
+            }
+            dst[i] = h;
+            if (c_f32) c_f32[row * d_pad + i] = f;
+            const float x = bf16_to_f32(h);
+            ss = __builtin_fmaf(x, x, ss);
+        }
+    } else {
+        for (int64_t i = threadIdx.x; i < d_pad; i += 256) dst[i] = 0;
+    }
+    const float tot = block_sum_256(ss, red);
+    if (threadIdx.x == 0) norm[row] = (row < n) ? tot : __builtin_inff();
+}
+
+__global__ void copy_i32_kernel(const int32_t *src, int32_t *dst, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t d, int64_t n_pad, int64_t d_pad,
+                              uint16_t *c_bf, float *norm, float *c_f32, const int32_t *labels_in,
+                              int32_t *labels_out, hipStream_t s)
+{
+    hipLaunchKernelGGL(cache_build_kernel, dim3((unsigned)n_pad), dim3(256), 0, s, entries, dtype, n, d, d_pad, c_bf,
+                       norm, c_f32);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(copy_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, labels_in, labels_out, n);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Query preparation: bf16 copy (round to nearest even) of the live queries for the matrix
+// cores, gathered through the miss list when there is one; rows up to the next tile
+// boundary are zero filled.  One block per row.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, const int32_t *sel, const int32_t *count,
+                                                         int b, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf)
+{
+    const int nq = count ? *count : b;
+    const int row = blockIdx.x;
+    const int live_pad = ((nq + bm - 1) / bm) * bm;
+    if (row >= live_pad) return;
+    uint16_t *dst = q_bf + (int64_t)row * d_pad;
+    if (row < nq) {
+        const float *src = queries + (int64_t)(sel ? sel[row] : row) * d;
+        for (int64_t i = threadIdx.x; i < d_pad; i += 256) dst[i] = (i < d) ? bf16_rne(src[i]) : (uint16_t)0;
+    } else {
+        for (int64_t i = threadIdx.x; i < d_pad; i += 256) dst[i] = 0;
+    }
+}
+
+hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
+                             int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, hipStream_t s)
+{
+    hipLaunchKernelGGL(query_prep_kernel, dim3((unsigned)b_pad), dim3(256), 0, s, queries, sel, count, (int)b, bm, d,
+                       d_pad, q_bf);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Finishing kernel, one block per live query:
+//  1. gather the query's n_splits * r packed (ordered key, index) candidates and sort them
+//     (bitonic, in LDS); the first r are the coarse candidates;
+//  2. exact re-scoring: dist = sum_i (q_i - c_i)^2 in fp32 against the stored cache values
+//     (bf16 rows widen exactly; fp32 rows when the cache was given in fp32);
+//  3. rank the r candidates by (dist, index), emit the first k (Sec. 3: the k (label,
+//     distance) tuples);
+//  4. vote: occurrences m of each label among the k, winner = most occurrences, smaller
+//     label id on equal counts; hit iff m >= vote_threshold (Sec. 2.1 / Sec. 3).
+// ---------------------------------------------------------------------------------------
+struct FinishKernelArgs {
+    FinishArgs a;
+    int sort_n;   // power of two >= n_splits * r
+};
+
+__global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
+{
+    const FinishArgs &a = fa.a;
+    __shared__ uint64_t ent[kMaxMergeEntries];
+    __shared__ float red[4][8];
+    __shared__ float dist_s[kMaxRescore];
+    __shared__ int32_t idx_s[kMaxRescore];
+    __shared__ int32_t lab_s[kMaxK];
+    __shared__ int32_t cnt_s[kMaxK];
+
+    const int nq = a.count ? *a.count : a.b;
+    const int q = blockIdx.x;
+    if (q >= nq) return;
+    const int tid = threadIdx.x;
+    const int r = a.r;
+
+    // 1. merge the per-split lists
+    const int total = a.n_splits * r;
+    const uint64_t *src = a.part + (size_t)q * total;
+    for (int i = tid; i < fa.sort_n; i += 256) ent[i] = (i < total) ? src[i] : kSentinel;
+    __syncthreads();
+    {
+        for (int size = 2; size <= fa.sort_n; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                for (int i = tid; i < (fa.sort_n >> 1); i += 256) {
+                    const int lo = ((i / stride) * stride * 2) + (i % stride);
+                    const int hi = lo + stride;
+                    const bool up = ((lo & size) == 0);
+                    const uint64_t x = ent[lo], y = ent[hi];
+                    if ((x > y) == up) {
+                        ent[lo] = y;
+                        ent[hi] = x;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+    if (tid < r) idx_s[tid] = (int32_t)(uint32_t)(ent[tid] & 0xffffffffu);
+    __syncthreads();
+
+    // 2. exact fp32 re-scoring, 8 candidates at a time
+    const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
+    const bool vec = (a.d % 8) == 0;
+    for (int r0 = 0; r0 < r; r0 += 8) {
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        int64_t cand[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cand[j] = idx_s[(r0 + j < r) ? r0 + j : r - 1];
+        if (vec) {
+            for (int64_t i = (int64_t)tid * 8; i < a.d; i += 256 * 8) {
+                const f32x4 q0 = *reinterpret_cast<const f32x4 *>(qrow + i);
+                const f32x4 q1 = *reinterpret_cast<const f32x4 *>(qrow + i + 4);
+                const float qv[8] = {q0[0], q0[1], q0[2], q0[3], q1[0], q1[1], q1[2], q1[3]};
+                if (a.c_f32) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float *c = a.c_f32 + cand[j] * a.d_pad + i;
+                        const f32x4 c0 = *reinterpret_cast<const f32x4 *>(c);
+                        const f32x4 c1 = *reinterpret_cast<const f32x4 *>(c + 4);
+                        const float cv[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float df = qv[e] - cv[e];
+                            acc[j] = __builtin_fmaf(df, df, acc[j]);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const uint4 cb = *reinterpret_cast<const uint4 *>(a.c_bf + cand[j] * a.d_pad + i);
+                        const uint32_t wv[4] = {cb.x, cb.y, cb.z, cb.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float c_lo = __uint_as_float(wv[e] << 16);
+                            const float c_hi = __uint_as_float(wv[e] & 0xffff0000u);
+                            const float d0 = qv[2 * e] - c_lo;
+                            acc[j] = __builtin_fmaf(d0, d0, acc[j]);
+                            const float d1 = qv[2 * e + 1] - c_hi;
+                            acc[j] = __builtin_fmaf(d1, d1, acc[j]);
+                        }
+                    }
+                }
+            }
+        } else {
+            for (int64_t i = tid; i < a.d; i += 256) {
+                const float qv = qrow[i];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float cv = a.c_f32 ? a.c_f32[cand[j] * a.d_pad + i] : bf16_to_f32(a.c_bf[cand[j] * a.d_pad + i]);
+                    const float df = qv - cv;
+                    acc[j] = __builtin_fmaf(df, df, acc[j]);
+                }
+            }
+        }
+        // block reduction in a fixed order
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float v = acc[j];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            if ((tid & 63) == 0) red[tid >> 6][j] = v;
+        }
+        __syncthreads();
+        if (tid < 8 && r0 + tid < r) dist_s[r0 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+        __syncthreads();
+    }
+
+    // 3. final order (dist, index) and the first k
+    if (tid < r) {
+        const float dm = dist_s[tid];
+        const int32_t im = idx_s[tid];
+        int rank = 0;
+        for (int j = 0; j < r; ++j) {
+            const float dj = dist_s[j];
+            const int32_t ij = idx_s[j];
+            rank += (dj < dm) || (dj == dm && ij < im);
+        }
+        if (rank < a.k) {
+            a.out_nbr_idx[(int64_t)q * a.k + rank] = im;
+            a.out_nbr_dist[(int64_t)q * a.k + rank] = dm;
+            lab_s[rank] = a.labels[im];
+        }
+    }
+    __syncthreads();
+
+    // 4. vote and hit decision
+    if (tid < a.k) {
+        const int32_t lm = lab_s[tid];
+        int c = 0;
+        for (int j = 0; j < a.k; ++j) c += (lab_s[j] == lm);
+        cnt_s[tid] = c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int best_c = 0;
+        int32_t best_l = 0;
+        for (int j = 0; j < a.k; ++j) {
+            const int c = cnt_s[j];
+            const int32_t l = lab_s[j];
+            if (c > best_c || (c == best_c && l < best_l)) {
+                best_c = c;
+                best_l = l;
+            }
+        }
+        a.out_labels[q] = best_l;
+        a.out_votes[q] = best_c;
+        a.out_hit[q] = (uint8_t)(best_c >= a.vote_threshold);
+    }
+}
+
+hipError_t launch_finish(const FinishArgs &a, hipStream_t s)
+{
+    const int total = a.n_splits * a.r;
+    if (total > kMaxMergeEntries || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r) return hipErrorInvalidValue;
+    FinishKernelArgs fa{a, 2};
+    while (fa.sort_n < total) fa.sort_n <<= 1;
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)a.b), dim3(256), 0, s, fa);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Miss compaction (Sec. 5, "Freeze Inference on GPUs": the batch is rebuilt without the
+// frozen items).  Stable: misses keep their order.  One block; ballot-based scan.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void compact_kernel(const uint8_t *hit, const int32_t *sel_in, const int32_t *count_in,
+                                                       int count_max, int32_t *sel_out, int32_t *count_out,
+                                                       int64_t *hits_out)
+{
+    __shared__ int wave_tot[16];
+    __shared__ int base_s;
+    const int cnt = count_in ? *count_in : count_max;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (tid == 0) base_s = 0;
+    __syncthreads();
+    for (int start = 0; start < cnt; start += 1024) {
+        const int j = start + tid;
+        const bool miss = (j < cnt) && (hit[j] == 0);
+        const uint64_t bal = __ballot(miss);
+        const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[w] = __builtin_popcountll(bal);
+        __syncthreads();
+        int off = base_s;
+        for (int i = 0; i < w; ++i) off += wave_tot[i];
+        if (miss) sel_out[off + before] = sel_in ? sel_in[j] : j;
+        __syncthreads();
+        if (tid == 0) {
+            int t = 0;
+            for (int i = 0; i < 16; ++i) t += wave_tot[i];
+            base_s += t;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        *count_out = base_s;
+        if (hits_out) *hits_out = (int64_t)cnt - (int64_t)base_s;
+    }
+}
+
+hipError_t launch_compact(const uint8_t *hit, const int32_t *sel_in, const int32_t *count_in, int64_t count_max,
+                          int32_t *sel_out, int32_t *count_out, int64_t *hits_out, hipStream_t s)
+{
+    hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, s, hit, sel_in, count_in, (int)count_max, sel_out,
+                       count_out, hits_out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Cascade bookkeeping (Pseudocode 1, FreezeInference): start with "no layer hit", then
+// after each layer record (label, layer position) for the requests that hit there.
+// ---------------------------------------------------------------------------------------
+__global__ void cascade_init_kernel(int32_t *out_labels, int32_t *out_exit, int64_t b)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < b) {
+        out_labels[i] = -1;
+        out_exit[i] = -1;
+    }
+}
+
+hipError_t launch_cascade_init(int32_t *out_labels, int32_t *out_exit, int64_t b, hipStream_t s)
+{
+    hipLaunchKernelGGL(cascade_init_kernel, dim3((unsigned)((b + 255) / 256)), dim3(256), 0, s, out_labels, out_exit, b);
+    return hipGetLastError();
+}
+
+__global__ void cascade_scatter_kernel(const int32_t *labels, const uint8_t *hit, const int32_t *sel, const int32_t *count,
+                                       int b, int layer_pos, int32_t *out_labels, int32_t *out_exit)
+{
+    const int nq = count ? *count : b;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < nq && hit[j]) {
+        const int orig = sel ? sel[j] : j;
+        out_labels[orig] = labels[j];
+        out_exit[orig] = layer_pos;
+    }
+}
+
+hipError_t launch_cascade_scatter(const int32_t *labels, const uint8_t *hit, const int32_t *sel,
+                                  const int32_t *count, int64_t b, int layer_pos, int32_t *out_labels,
+                                  int32_t *out_exit, hipStream_t s)
+{
+    hipLaunchKernelGGL(cascade_scatter_kernel, dim3((unsigned)((b + 255) / 256)), dim3(256), 0, s, labels, hit, sel,
+                       count, (int)b, layer_pos, out_labels, out_exit);
+    return hipGetLastError();
+}
+
+}  // namespace fz

@@ -1,0 +1,353 @@
+// Distance pass of the cache look-up on the matrix cores (gfx950 / CDNA4).
+//
+// For every query row b and cache entry n it forms the ranking key of the squared
+// Euclidean distance  |q - c|^2 = |q|^2 + |c|^2 - 2 q.c  without the per-query
+// constant:  key(b, n) = |c_n|^2 - 2 * sum_i Q_bf[b,i] * C_bf[n,i]   (bf16 inputs,
+// fp32 accumulation on MFMA), and keeps, per query and per range of cache tiles, the
+// R entries with the smallest (key, index).  The score matrix never reaches memory:
+// a workgroup owns a 256- (or 128-) query tile, walks a range of 256-entry cache
+// tiles, and folds each finished tile into a per-query top-R list held in LDS.
+// The exact fp32 distances of these candidates are computed by the finishing kernel.
+//
+// Paper: Sec. 3 (the look-up computes the k nearest neighbours of the layer output)
+// and Sec. 4 "Computational Complexity" (the scan over all cached points is the cost).
+//
+// Work decomposition: unit = (query tile, split); a split is a contiguous range of
+// cache tiles.  Units are numbered so that the workgroups resident on one XCD (block
+// id modulo 8) hold neighbouring units, which share query tiles and walk the same
+// cache tiles, so that operand re-reads are served by that XCD's L2.
+//
+// Main loop: 8 waves (2 x 4), each owning a (TM*32) x 64 block of the tile as
+// 32x32x16 bf16 MFMA accumulators.  Operands are streamed global -> LDS with
+// LDS-direct 16-byte loads (no VGPR staging) into two stages; 16-byte chunks are
+// XOR-swizzled inside each row so the ds_read_b128 fragment reads are bank-conflict
+// free.  The loads are issued with inline asm: the compiler would otherwise order
+// every LDS read behind the outstanding direct loads, serialising load and compute.
+//
+// Epilogue (per tile, in column slabs that reuse the operand LDS): waves write their
+// keys to the slab; thread t scans row t, collecting a bit mask of keys not above the
+// row's current R-th best, then inserts the survivors into the row's list under the
+// total order (key, index).
+#include "freeze_internal.h"
+
+namespace fz {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+__device__ __forceinline__ void load16_global_to_lds(const void *g, uint32_t lds_byte_addr)
+{
+    // M0 carries the wave-uniform LDS destination; lane i lands at +16*i.
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(g)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ void wait_all_global_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// fp32 -> unsigned with the same order (so that (key, index) packs into one u64)
+__device__ __forceinline__ uint32_t ordered_bits(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float from_ordered_bits(uint32_t u)
+{
+    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
+}
+
+template <int BM_, int BK_, int RMAX_>
+struct DistCfg {
+    static constexpr int BM = BM_, BN = kTileN, BK = BK_, RMAX = RMAX_;
+    static constexpr int NS = 2;                    // operand stages in LDS
+    static constexpr int WM = 2, WN = 4;            // wave grid
+    static constexpr int NWAVES = WM * WN, THREADS = 64 * NWAVES;
+    static constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
+    static constexpr int CPR = BK / 8;              // 16-byte chunks per operand row
+    static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+    static constexpr int A_BYTES = BM * BK * 2;
+    static constexpr int OP_BYTES = NS * STAGE_BYTES;
+    static constexpr int NI_A = BM * CPR / 64 / NWAVES;   // direct-load instructions per wave and stage
+    static constexpr int NI_B = BN * CPR / 64 / NWAVES;
+    // slab pass: WNS wave columns at a time
+    static constexpr int WNS = (BM * 4 * 32 * 4 <= OP_BYTES) ? 4 : ((BM * 2 * 32 * 4 <= OP_BYTES) ? 2 : 1);
+    static constexpr int SLABW = WNS * 32;          // keys per row in one slab
+    static constexpr int TOP_BYTES = RMAX * BM * 8;
+    static constexpr int LDS_BYTES = OP_BYTES + TOP_BYTES;
+    static_assert(BM * SLABW * 4 <= OP_BYTES, "slab must fit in the operand area");
+    static_assert(LDS_BYTES <= 163840, "LDS budget");
+    static_assert(NI_A >= 1 && NI_B >= 1, "load split");
+    static_assert(BM <= THREADS, "one scanning thread per row");
+};
+
+// chunk swizzle: physical chunk = logical chunk ^ swz(row); conflict-free for 8- and 16-lane groups
+template <int CPR>
+__device__ __forceinline__ int swz(int row)
+{
+    if constexpr (CPR == 8)
+        return ((row ^ (row >> 3)) & 1) | (row & 6);
+    else
+        return (((row >> 1) ^ (row >> 3)) & 1) | ((row >> 1) & 2);
+}
+
+struct DistKernelArgs {
+    const uint16_t *q_bf;
+    const uint16_t *c_bf;
+    const float *norm;
+    uint64_t *part;
+    const int32_t *count;
+    int b, n, d_pad;
+    int n_tiles, n_splits, r;
+    int units;   // m_tiles * n_splits
+};
+
+template <class C>
+__global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
+{
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, CPR = C::CPR, TM = C::TM, TN = C::TN;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[C::LDS_BYTES];
+    uint64_t *top = reinterpret_cast<uint64_t *>(smem + C::OP_BYTES);   // [RMAX][BM]
+    float *slab = reinterpret_cast<float *>(smem);                      // [BM][SLABW], aliases operands
+    const bf16x8 *smem16 = reinterpret_cast<const bf16x8 *>(smem);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w / C::WN, wn = w % C::WN;
+
+    // XCD-aware unit numbering: blocks with equal (id % 8) run on one XCD; give them a contiguous
+    // range of units.  units = 8a + rem: XCD x owns a (+1 if x < rem) consecutive units.
+    int unit;
+    {
+        const int g = p.units, a = g >> 3, rem = g & 7;
+        const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+        unit = x * a + (x < rem ? x : rem) + j;
+    }
+    const int mt = unit / p.n_splits, sp = unit % p.n_splits;
+    const int nq = p.count ? *p.count : p.b;
+    if (mt * BM >= nq) return;   // uniform per workgroup, before any barrier
+    const int nt0 = (int)(((int64_t)sp * p.n_tiles) / p.n_splits);
+    const int nt1 = (int)(((int64_t)(sp + 1) * p.n_tiles) / p.n_splits);
+    const int r = p.r;
+
+    // per-row selection state lives with thread t (< BM)
+    uint64_t curmax = kSentinel;
+    int maxpos = 0;
+    float tau = __builtin_inff();
+    if (tid < BM) {
+#pragma unroll
+        for (int i = 0; i < C::RMAX; ++i) top[i * BM + tid] = kSentinel;
+    }
+
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
+    const size_t row_bytes = (size_t)p.d_pad * 2;
+
+    // global source pointers of this thread's direct loads (k offset 0)
+    const unsigned char *srcA[C::NI_A];
+    const unsigned char *srcB[C::NI_B];
+#pragma unroll
+    for (int i = 0; i < C::NI_A; ++i) {
+        const int ch = (i * C::NWAVES + w) * 64 + lane;
+        const int row = ch / CPR, pc = ch % CPR, c = pc ^ swz<CPR>(row);
+        srcA[i] = reinterpret_cast<const unsigned char *>(p.q_bf) + ((size_t)mt * BM + row) * row_bytes + c * 16;
+    }
+    // fragment read addresses (in 16-byte units, relative to the stage's A / B area)
+    const int g = lane >> 5;
+    const int rowA = wm * TM * 32 + (lane & 31);
+    const int rowB = wn * TN * 32 + (lane & 31);
+    const int rdA = rowA * CPR, pcxA = g ^ swz<CPR>(rowA);
+    const int rdB = rowB * CPR, pcxB = g ^ swz<CPR>(rowB);
+    const int nk = p.d_pad / BK;
+
+    for (int nt = nt0; nt < nt1; ++nt) {
+        const int n0 = nt * BN;
+#pragma unroll
+        for (int i = 0; i < C::NI_B; ++i) {
+            const int ch = (i * C::NWAVES + w) * 64 + lane;
+            const int row = ch / CPR, pc = ch % CPR, c = pc ^ swz<CPR>(row);
+            srcB[i] = reinterpret_cast<const unsigned char *>(p.c_bf) + ((size_t)n0 + row) * row_bytes + c * 16;
+        }
+        auto issue = [&](int stage, int kt) {
+            const uint32_t sbase = smem_base + stage * C::STAGE_BYTES;
+            const size_t koff = (size_t)kt * (BK * 2);
+#pragma unroll
+            for (int i = 0; i < C::NI_A; ++i)
+                load16_global_to_lds(srcA[i] + koff, sbase + (i * C::NWAVES + w) * 1024);
+#pragma unroll
+            for (int i = 0; i < C::NI_B; ++i)
+                load16_global_to_lds(srcB[i] + koff, sbase + C::A_BYTES + (i * C::NWAVES + w) * 1024);
+        };
+
+        f32x16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        issue(0, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const int st = kt & 1;
+            wait_all_global_loads();   // stage `st` has landed
+            __syncthreads();           // ... for every wave; and all reads of the other stage are done
+            if (kt + 1 < nk) issue(st ^ 1, kt + 1);
+            const int baseA = st * (C::STAGE_BYTES / 16) + rdA;
+            const int baseB = st * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB;
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                bf16x8 af[TM], bfr[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[i] = smem16[baseA + i * 32 * CPR + ((kk << 1) ^ pcxA)];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bfr[j] = smem16[baseB + j * 32 * CPR + ((kk << 1) ^ pcxB)];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            }
+        }
+        __syncthreads();   // operand LDS is free: the slab may overwrite it
+
+        // ---- epilogue: fold this tile into the per-row top-R lists ----
+#pragma unroll
+        for (int bj = 0; bj < TN; ++bj) {
+#pragma unroll 1
+            for (int wg = 0; wg < C::WN / C::WNS; ++wg) {
+                if (wn / C::WNS == wg) {
+                    const int col = n0 + wn * TN * 32 + bj * 32 + (lane & 31);
+                    const float nrm = p.norm[col];   // col < n_pad always
+                    const int sc = (wn % C::WNS) * 32 + (lane & 31);
+#pragma unroll
+                    for (int bi = 0; bi < TM; ++bi) {
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                            const float key = __builtin_fmaf(-2.f, acc[bi][bj][e], nrm);
+                            slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = key;
+                        }
+                    }
+                }
+                __syncthreads();
+                if (tid < BM) {
+                    const int t = tid;
+                    // which of the slab's columns are real cache entries
+                    uint64_t mask[(C::SLABW + 63) / 64];
+                    const f32x4 *srow = reinterpret_cast<const f32x4 *>(slab + t * C::SLABW);
+                    constexpr int CGM = (C::SLABW < 64 ? C::SLABW : 64) / 4;   // column groups per mask word
+#pragma unroll
+                    for (int m = 0; m < (C::SLABW + 63) / 64; ++m) {
+                        uint64_t mk = 0;
+#pragma unroll 4
+                        for (int cgi = 0; cgi < CGM; ++cgi) {
+                            const int cg = m * 16 + cgi;
+                            const f32x4 v = srow[(cg ^ t) & (C::SLABW / 4 - 1)];
+                            // the four keys share a 32-column segment: one validity limit for all
+                            const int seg0 = (wg * C::WNS + (cg >> 3)) * TN * 32 + bj * 32 + ((cg & 7) << 2);
+                            const int lim = p.n - n0 - seg0;   // columns seg0 .. seg0+3 are valid iff index < lim
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const bool pass = (v[e] <= tau) && (e < lim);
+                                mk |= (uint64_t)pass << (cgi * 4 + e);
+                            }
+                        }
+                        mask[m] = mk;
+                    }
+#pragma unroll
+                    for (int m = 0; m < (C::SLABW + 63) / 64; ++m) {
+                        uint64_t mk = mask[m];
+                        while (mk) {
+                            const int sc = m * 64 + __builtin_ctzll(mk);
+                            mk &= mk - 1;
+                            const float key = slab[t * C::SLABW + ((((sc >> 2) ^ t) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)];
+                            const int tilecol = (wg * C::WNS + sc / 32) * TN * 32 + bj * 32 + (sc & 31);
+                            const uint64_t ent = ((uint64_t)ordered_bits(key) << 32) | (uint32_t)(n0 + tilecol);
+                            if (ent < curmax) {
+                                top[maxpos * BM + t] = ent;
+                                curmax = 0;
+#pragma unroll
+                                for (int i = 0; i < C::RMAX; ++i) {
+                                    if (i < r) {
+                                        const uint64_t v = top[i * BM + t];
+                                        if (v >= curmax) { curmax = v; maxpos = i; }
+                                    }
+                                }
+                                tau = (curmax == kSentinel) ? __builtin_inff() : from_ordered_bits((uint32_t)(curmax >> 32));
+                            }
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+
+    if (tid < BM) {
+        uint64_t *dst = p.part + (((size_t)mt * BM + tid) * p.n_splits + sp) * r;
+#pragma unroll
+        for (int i = 0; i < C::RMAX; ++i)
+            if (i < r) dst[i] = top[i * BM + tid];
+    }
+}
+
+DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus)
+{
+    DistPlan pl{};
+    pl.variant = r <= 16 ? 0 : (r <= 32 ? 1 : 2);
+    pl.bm = pl.variant == 2 ? 128 : 256;
+    pl.r = r;
+    pl.m_tiles = (int)((b + pl.bm - 1) / pl.bm);
+    if (pl.m_tiles < 1) pl.m_tiles = 1;
+    pl.n_tiles = (int)((n + kTileN - 1) / kTileN);
+    pl.b_pad = (int64_t)pl.m_tiles * pl.bm;
+    // Choose the number of splits: best fill of the CUs over whole rounds, fewest splits on ties.
+    const int max_splits = pl.n_tiles < kMaxMergeEntries / r ? pl.n_tiles : kMaxMergeEntries / r;
+    double best_eff = -1.0;
+    int best_s = 1;
+    const double total = (double)pl.m_tiles * pl.n_tiles;
+    for (int s = 1; s <= max_splits; ++s) {
+        const int64_t units = (int64_t)pl.m_tiles * s;
+        const int64_t rounds = (units + num_cus - 1) / num_cus;
+        const int tiles_per_unit = (pl.n_tiles + s - 1) / s;
+        const double eff = total / ((double)rounds * num_cus * tiles_per_unit);
+        if (eff > best_eff * 1.02) {   // a later (larger) s must win by 2% to be taken
+            best_eff = eff;
+            best_s = s;
+        }
+    }
+    pl.n_splits = best_s;
+    return pl;
+}
+
+template <class C>
+static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStream_t s)
+{
+    DistKernelArgs k{};
+    k.q_bf = a.q_bf;
+    k.c_bf = a.c_bf;
+    k.norm = a.norm;
+    k.part = a.part;
+    k.count = a.count;
+    k.b = a.b;
+    k.n = a.n;
+    k.d_pad = a.d_pad;
+    k.n_tiles = plan.n_tiles;
+    k.n_splits = plan.n_splits;
+    k.r = plan.r;
+    k.units = plan.m_tiles * plan.n_splits;
+    hipLaunchKernelGGL((dist_topr_kernel<C>), dim3(k.units), dim3(C::THREADS), 0, s, k);
+    return hipGetLastError();
+}
+
+hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t s)
+{
+    if (plan.r < 1 || plan.r > kMaxRescore || a.d_pad % kPadD != 0) return hipErrorInvalidValue;
+    switch (plan.variant) {
+    case 0: return launch_variant<DistCfg<256, 64, 16>>(plan, a, s);
+    case 1: return launch_variant<DistCfg<256, 32, 32>>(plan, a, s);
+    default: return launch_variant<DistCfg<128, 64, 64>>(plan, a, s);
+    }
+}
+
+}  // namespace fz

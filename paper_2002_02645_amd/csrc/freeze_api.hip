@@ -1,0 +1,367 @@
+// C ABI of the library: argument checking, carving of the caller's storage / workspace
+// buffers, and the launch sequences of the look-up and of the cascade.  Host code only;
+// every step of the look-up itself runs in the HIP kernels.
+#include "../../include/freeze.h"
+
+#include <new>
+#include <vector>
+
+#include "freeze_internal.h"
+
+using namespace fz;
+
+struct freeze_ctx {
+    std::vector<LayerCache> layers;
+    int num_cus = 256;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// bump allocator over a caller-provided buffer
+struct Carver {
+    unsigned char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base(static_cast<unsigned char *>(p)) {}
+    template <class T>
+    T *take(size_t count)
+    {
+        T *p = reinterpret_cast<T *>(base + off);
+        off += align_up(count * sizeof(T));
+        return p;
+    }
+};
+
+struct CacheLayout {
+    int64_t n_pad, d_pad;
+    size_t bytes;
+};
+
+bool cache_layout(int64_t n, int64_t d, int dtype, CacheLayout *out)
+{
+    if (n < 1 || n >= (int64_t)2147483647 - 512 || d < 1 || d > (1 << 24)) return false;
+    if (dtype != FREEZE_F32 && dtype != FREEZE_BF16) return false;
+    out->n_pad = round_up(n, kTileN);
+    out->d_pad = round_up(d, kPadD);
+    size_t bytes = align_up((size_t)out->n_pad * out->d_pad * 2) + align_up((size_t)out->n_pad * 4) +
+                   align_up((size_t)n * 4);
+    if (dtype == FREEZE_F32) bytes += align_up((size_t)n * out->d_pad * 4);
+    out->bytes = bytes;
+    return true;
+}
+
+int default_rescore(int k) { return k <= 10 ? 16 : (k <= 24 ? 32 : 64); }
+
+// Validated parameters of one look-up on one layer.
+struct LookupShape {
+    int r;
+    DistPlan plan;
+    size_t ws_bytes;
+};
+
+bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, int rescore_r, LookupShape *out)
+{
+    if (b < 0 || b > (int64_t)1 << 30 || k < 1 || k > FREEZE_MAX_K || k > L.n) return false;
+    int r = rescore_r == 0 ? default_rescore(k) : rescore_r;
+    if (rescore_r != 0 && (rescore_r < k || rescore_r > FREEZE_MAX_RESCORE)) return false;
+    if (r < k) r = k;
+    if ((int64_t)r > L.n) r = (int)L.n;
+    out->r = r;
+    out->plan = plan_dist(b, L.n, r, ctx->num_cus);
+    out->ws_bytes = align_up((size_t)out->plan.b_pad * L.d_pad * 2) +
+                    align_up((size_t)out->plan.b_pad * out->plan.n_splits * r * 8);
+    return true;
+}
+
+const LayerCache *get_layer(const freeze_ctx *ctx, int layer, int *err)
+{
+    if (!ctx) {
+        *err = FREEZE_EINVAL;
+        return nullptr;
+    }
+    if (layer < 0 || layer >= (int)ctx->layers.size()) {
+        *err = FREEZE_ELAYER;
+        return nullptr;
+    }
+    if (!ctx->layers[layer].built) {
+        *err = FREEZE_ENOTBUILT;
+        return nullptr;
+    }
+    *err = FREEZE_OK;
+    return &ctx->layers[layer];
+}
+
+// Enqueue one look-up.  `sel` / `count` (device) restrict it to the live requests of a cascade.
+int enqueue_lookup(const LayerCache &L, const LookupShape &sh, const float *queries, const int32_t *sel,
+                   const int32_t *count, int64_t b, int k, int vote_threshold, int32_t *out_labels, uint8_t *out_hit,
+                   int32_t *out_votes, int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace, hipStream_t s)
+{
+    Carver ws(workspace);
+    uint16_t *q_bf = ws.take<uint16_t>((size_t)sh.plan.b_pad * L.d_pad);
+    uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * sh.plan.n_splits * sh.r);
+
+    if (launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf, s) != hipSuccess)
+        return FREEZE_EHIP;
+
+    DistArgs da{};
+    da.q_bf = q_bf;
+    da.c_bf = L.c_bf;
+    da.norm = L.norm;
+    da.part = part;
+    da.count = count;
+    da.b = (int)b;
+    da.n = (int)L.n;
+    da.d_pad = (int)L.d_pad;
+    if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
+
+    FinishArgs fa{};
+    fa.part = part;
+    fa.n_splits = sh.plan.n_splits;
+    fa.r = sh.r;
+    fa.queries = queries;
+    fa.sel = sel;
+    fa.count = count;
+    fa.b = (int)b;
+    fa.d = L.d;
+    fa.d_pad = L.d_pad;
+    fa.c_bf = L.c_bf;
+    fa.c_f32 = L.c_f32;
+    fa.labels = L.labels;
+    fa.k = k;
+    fa.vote_threshold = vote_threshold;
+    fa.out_labels = out_labels;
+    fa.out_hit = out_hit;
+    fa.out_votes = out_votes;
+    fa.out_nbr_idx = out_nbr_idx;
+    fa.out_nbr_dist = out_nbr_dist;
+    if (launch_finish(fa, s) != hipSuccess) return FREEZE_EHIP;
+    return FREEZE_OK;
+}
+
+struct CascadeLayout {
+    size_t lookup_ws;   // largest per-layer look-up workspace
+    size_t bytes;
+};
+
+bool cascade_layout(const freeze_ctx *ctx, int num_layers, const int *layers, int64_t b, int k, int rescore_r,
+                    CascadeLayout *out, int *err)
+{
+    if (!ctx || !layers || num_layers < 1 || num_layers > 1024) {
+        *err = FREEZE_EINVAL;
+        return false;
+    }
+    size_t mx = 0;
+    for (int l = 0; l < num_layers; ++l) {
+        const LayerCache *L = get_layer(ctx, layers[l], err);
+        if (!L) return false;
+        LookupShape sh;
+        if (!lookup_shape(ctx, *L, b, k, rescore_r, &sh)) {
+            *err = FREEZE_EINVAL;
+            return false;
+        }
+        if (sh.ws_bytes > mx) mx = sh.ws_bytes;
+    }
+    out->lookup_ws = mx;
+    const size_t bb = (size_t)(b > 0 ? b : 1);
+    // per-layer outputs in compact order + two miss lists + two counters
+    out->bytes = mx + 3 * align_up(bb * 4) + align_up(bb) + 2 * align_up(bb * k * 4) + 2 * align_up(bb * 4) +
+                 2 * align_up(4);
+    *err = FREEZE_OK;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+int freeze_create(freeze_ctx **out, int num_layers)
+{
+    if (!out || num_layers < 1 || num_layers > 65536) return FREEZE_EINVAL;
+    freeze_ctx *c = new (std::nothrow) freeze_ctx;
+    if (!c) return FREEZE_EINVAL;
+    c->layers.resize((size_t)num_layers);
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+        c->num_cus = prop.multiProcessorCount;
+    else
+        (void)hipGetLastError();   // no device: keep the MI355X default; launches will report the error
+    *out = c;
+    return FREEZE_OK;
+}
+
+int freeze_destroy(freeze_ctx *ctx)
+{
+    if (!ctx) return FREEZE_EINVAL;
+    delete ctx;
+    return FREEZE_OK;
+}
+
+size_t freeze_cache_storage_bytes(int64_t n, int64_t d, int entries_dtype)
+{
+    CacheLayout cl;
+    return cache_layout(n, d, entries_dtype, &cl) ? cl.bytes : 0;
+}
+
+int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entries_dtype, int64_t n, int64_t d,
+                       const int32_t *labels, int32_t num_classes, void *storage, size_t storage_bytes, void *stream)
+{
+    if (!ctx || !entries || !labels || !storage || num_classes < 1) return FREEZE_EINVAL;
+    if (layer < 0 || layer >= (int)ctx->layers.size()) return FREEZE_ELAYER;
+    CacheLayout cl;
+    if (!cache_layout(n, d, entries_dtype, &cl)) return FREEZE_EINVAL;
+    if (storage_bytes < cl.bytes || (reinterpret_cast<uintptr_t>(storage) % kAlign) != 0) return FREEZE_EWORKSPACE;
+
+    Carver st(storage);
+    uint16_t *c_bf = st.take<uint16_t>((size_t)cl.n_pad * cl.d_pad);
+    float *norm = st.take<float>((size_t)cl.n_pad);
+    int32_t *lab = st.take<int32_t>((size_t)n);
+    float *c_f32 = entries_dtype == FREEZE_F32 ? st.take<float>((size_t)n * cl.d_pad) : nullptr;
+
+    LayerCache &L = ctx->layers[layer];
+    L.built = false;
+    if (launch_cache_build(entries, entries_dtype, n, d, cl.n_pad, cl.d_pad, c_bf, norm, c_f32, labels, lab,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+        return FREEZE_EHIP;
+    L.n = n;
+    L.d = d;
+    L.n_pad = cl.n_pad;
+    L.d_pad = cl.d_pad;
+    L.num_classes = num_classes;
+    L.entries_dtype = entries_dtype;
+    L.c_bf = c_bf;
+    L.norm = norm;
+    L.labels = lab;
+    L.c_f32 = c_f32;
+    L.built = true;
+    return FREEZE_OK;
+}
+
+size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b, int k, int rescore_r)
+{
+    int err;
+    const LayerCache *L = get_layer(ctx, layer, &err);
+    LookupShape sh;
+    if (!L || !lookup_shape(ctx, *L, b, k, rescore_r, &sh)) return 0;
+    return sh.ws_bytes;
+}
+
+int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k, int vote_threshold,
+                  int rescore_r, int32_t *out_labels, uint8_t *out_hit, int32_t *out_votes, int32_t *out_nbr_idx,
+                  float *out_nbr_dist, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int err;
+    const LayerCache *L = get_layer(ctx, layer, &err);
+    if (!L) return err;
+    if (!queries || !out_labels || !out_hit || !out_votes || !out_nbr_idx || !out_nbr_dist || !workspace)
+        return FREEZE_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(queries) % 16) != 0) return FREEZE_EINVAL;
+    LookupShape sh;
+    if (!lookup_shape(ctx, *L, b, k, rescore_r, &sh)) return FREEZE_EINVAL;
+    if (vote_threshold < 1 || vote_threshold > k) return FREEZE_EINVAL;
+    if (workspace_bytes < sh.ws_bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return FREEZE_EWORKSPACE;
+    if (b == 0) return FREEZE_OK;
+    return enqueue_lookup(*L, sh, queries, nullptr, nullptr, b, k, vote_threshold, out_labels, out_hit, out_votes,
+                          out_nbr_idx, out_nbr_dist, workspace, static_cast<hipStream_t>(stream));
+}
+
+size_t freeze_cascade_workspace_bytes(const freeze_ctx *ctx, int num_layers, const int *layers, int64_t b, int k,
+                                      int rescore_r)
+{
+    CascadeLayout cl;
+    int err;
+    return cascade_layout(ctx, num_layers, layers, b, k, rescore_r, &cl, &err) ? cl.bytes : 0;
+}
+
+int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers, const float *const *queries_per_layer,
+                          int64_t b, int k, const int *vote_thresholds, int rescore_r, int32_t *out_labels,
+                          int32_t *out_exit_layer, int64_t *out_hits_per_layer, void *workspace,
+                          size_t workspace_bytes, void *stream)
+{
+    CascadeLayout cl;
+    int err;
+    if (!cascade_layout(ctx, num_layers, layers, b, k, rescore_r, &cl, &err)) return err;
+    if (!queries_per_layer || !vote_thresholds || !out_labels || !out_exit_layer || !out_hits_per_layer || !workspace)
+        return FREEZE_EINVAL;
+    for (int l = 0; l < num_layers; ++l) {
+        if (!queries_per_layer[l] || (reinterpret_cast<uintptr_t>(queries_per_layer[l]) % 16) != 0)
+            return FREEZE_EINVAL;
+        if (vote_thresholds[l] < 1 || vote_thresholds[l] > k) return FREEZE_EINVAL;
+    }
+    if (workspace_bytes < cl.bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return FREEZE_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    Carver ws(workspace);
+    unsigned char *lookup_ws = ws.take<unsigned char>(cl.lookup_ws);
+    const size_t bb = (size_t)(b > 0 ? b : 1);
+    int32_t *t_labels = ws.take<int32_t>(bb);
+    int32_t *t_votes = ws.take<int32_t>(bb);
+    int32_t *t_spare = ws.take<int32_t>(bb);
+    (void)t_spare;
+    uint8_t *t_hit = ws.take<uint8_t>(bb);
+    int32_t *t_idx = ws.take<int32_t>(bb * k);
+    float *t_dist = ws.take<float>(bb * k);
+    int32_t *sel_buf[2] = {ws.take<int32_t>(bb), ws.take<int32_t>(bb)};
+    int32_t *cnt_buf[2] = {ws.take<int32_t>(1), ws.take<int32_t>(1)};
+
+    if (b == 0) {
+        // nothing to look up: every layer froze zero requests
+        for (int l = 0; l < num_layers; ++l)
+            if (launch_compact(t_hit, nullptr, nullptr, 0, sel_buf[0], cnt_buf[0], out_hits_per_layer + l, s) !=
+                hipSuccess)
+                return FREEZE_EHIP;
+        return FREEZE_OK;
+    }
+    if (launch_cascade_init(out_labels, out_exit_layer, b, s) != hipSuccess) return FREEZE_EHIP;
+
+    const int32_t *sel = nullptr;     // layer 0: every request, identity order
+    const int32_t *count = nullptr;
+    for (int l = 0; l < num_layers; ++l) {
+        const LayerCache &L = ctx->layers[layers[l]];
+        LookupShape sh;
+        lookup_shape(ctx, L, b, k, rescore_r, &sh);
+        int rc = enqueue_lookup(L, sh, queries_per_layer[l], sel, count, b, k, vote_thresholds[l], t_labels, t_hit,
+                                t_votes, t_idx, t_dist, lookup_ws, s);
+        if (rc != FREEZE_OK) return rc;
+        if (launch_cascade_scatter(t_labels, t_hit, sel, count, b, l, out_labels, out_exit_layer, s) != hipSuccess)
+            return FREEZE_EHIP;
+        int32_t *sel_next = sel_buf[l & 1];
+        int32_t *cnt_next = cnt_buf[l & 1];
+        if (launch_compact(t_hit, sel, count, b, sel_next, cnt_next, out_hits_per_layer + l, s) != hipSuccess)
+            return FREEZE_EHIP;
+        sel = sel_next;
+        count = cnt_next;
+    }
+    return FREEZE_OK;
+}
+
+int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t count, int32_t *sel_out,
+                          int32_t *out_count, void *stream)
+{
+    if (!hit || !sel_out || !out_count || count < 0 || count > (int64_t)1 << 30) return FREEZE_EINVAL;
+    if (launch_compact(hit, sel_in, nullptr, count, sel_out, out_count, nullptr, static_cast<hipStream_t>(stream)) !=
+        hipSuccess)
+        return FREEZE_EHIP;
+    return FREEZE_OK;
+}
+
+const char *freeze_strerror(int code)
+{
+    switch (code) {
+    case FREEZE_OK: return "ok";
+    case FREEZE_EINVAL: return "invalid argument";
+    case FREEZE_ELAYER: return "layer index out of range";
+    case FREEZE_ENOTBUILT: return "layer cache not built";
+    case FREEZE_EWORKSPACE: return "storage or workspace too small or misaligned";
+    case FREEZE_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+    }
+}
+
+}  // extern "C"

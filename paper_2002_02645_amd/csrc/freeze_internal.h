@@ -1,0 +1,94 @@
+// Internal declarations shared by the translation units of the library
+// (host dispatcher <-> kernel launchers).  Not part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fz {
+
+constexpr int kTileN = 256;      // cache entries per matrix-core tile; cache rows are padded to it
+constexpr int kPadD = 64;        // activation length is padded to a multiple of this (bf16 copies)
+constexpr int kMaxRescore = 64;  // largest re-scoring width R
+constexpr int kMaxK = 64;
+constexpr int kMaxMergeEntries = 8192;  // n_splits * R gathered per query in the finishing kernel
+constexpr uint64_t kSentinel = ~0ull;   // "no entry" in (key, index) lists; larger than every real entry
+
+// One layer's cache inside the caller's storage buffer.
+struct LayerCache {
+    bool built = false;
+    int64_t n = 0, d = 0;
+    int64_t n_pad = 0, d_pad = 0;
+    int32_t num_classes = 0;
+    int entries_dtype = 0;
+    const uint16_t *c_bf = nullptr;   // [n_pad, d_pad] bf16, zero padded
+    const float *norm = nullptr;      // [n_pad] sum of squares of the bf16 row, fp32
+    const int32_t *labels = nullptr;  // [n]
+    const float *c_f32 = nullptr;     // [n, d_pad] fp32 rows when the cache was given in fp32, else null
+};
+
+// Which distance kernel variant serves a re-scoring width.
+struct DistPlan {
+    int variant;    // 0: R<=16, 1: R<=32, 2: R<=64
+    int bm;         // queries per tile
+    int r;          // entries kept per (query, split)
+    int m_tiles;    // ceil(b / bm)
+    int n_tiles;    // ceil(n / kTileN)
+    int n_splits;   // ranges of cache tiles scanned by separate workgroups
+    int64_t b_pad;  // m_tiles * bm
+};
+
+DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus);
+
+struct DistArgs {
+    const uint16_t *q_bf;   // [b_pad, d_pad]
+    const uint16_t *c_bf;   // [n_pad, d_pad]
+    const float *norm;      // [n_pad]
+    uint64_t *part;         // [b_pad, n_splits, r] packed (ordered key, index)
+    const int32_t *count;   // device: number of live queries, or null (= b)
+    int b;
+    int n;
+    int d_pad;
+};
+
+hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t d, int64_t n_pad, int64_t d_pad,
+                              uint16_t *c_bf, float *norm, float *c_f32, const int32_t *labels_in,
+                              int32_t *labels_out, hipStream_t s);
+
+hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
+                             int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, hipStream_t s);
+
+hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t s);
+
+struct FinishArgs {
+    const uint64_t *part;   // [b_pad, n_splits, r]
+    int n_splits, r;
+    const float *queries;   // [*, d] fp32 (original batch)
+    const int32_t *sel;     // compact position -> row of `queries`, or null
+    const int32_t *count;   // device live-query count or null
+    int b;
+    int64_t d, d_pad;
+    const uint16_t *c_bf;
+    const float *c_f32;     // non-null: re-score against the fp32 rows
+    const int32_t *labels;
+    int k, vote_threshold;
+    int32_t *out_labels;    // [b] (compact order)
+    uint8_t *out_hit;
+    int32_t *out_votes;
+    int32_t *out_nbr_idx;   // [b, k]
+    float *out_nbr_dist;    // [b, k]
+};
+
+hipError_t launch_finish(const FinishArgs &a, hipStream_t s);
+
+hipError_t launch_compact(const uint8_t *hit, const int32_t *sel_in, const int32_t *count_in, int64_t count_max,
+                          int32_t *sel_out, int32_t *count_out, int64_t *hits_out, hipStream_t s);
+
+hipError_t launch_cascade_init(int32_t *out_labels, int32_t *out_exit, int64_t b, hipStream_t s);
+
+hipError_t launch_cascade_scatter(const int32_t *labels, const uint8_t *hit, const int32_t *sel,
+                                  const int32_t *count, int64_t b, int layer_pos, int32_t *out_labels,
+                                  int32_t *out_exit, hipStream_t s);
+
+}  // namespace fz

@@ -1,0 +1,215 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Sizes span several tiles, several splits and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import freeze_oracle as fo
+from paper_2002_02645_amd import binding, synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+TIGHT = 1e-5   # tighter than the contract's 1e-4: the fp32 re-scoring is good to ~1e-6
+
+
+def _host_entries(t: torch.Tensor) -> np.ndarray:
+    return synth.bf16_bits(t) if t.dtype == torch.bfloat16 else t.detach().cpu().numpy()
+
+
+def run_lookup(entries, labels, queries, num_classes, k, thr, r=0):
+    fc = binding.FreezeCache(1)
+    try:
+        fc.build_layer(0, entries.cuda().contiguous(), labels.cuda().contiguous(), num_classes)
+        out = fc.lookup(0, queries.cuda().contiguous(), k, thr, r)
+        torch.cuda.synchronize()
+        return {key: v.cpu().numpy() for key, v in out.items()}
+    finally:
+        fc.close()
+
+
+def check_case(entries, labels, queries, num_classes, k, thr, r=0, rel=TIGHT):
+    got = run_lookup(entries, labels, queries, num_classes, k, thr, r)
+    e_h, l_h, q_h = _host_entries(entries), labels.cpu().numpy(), queries.cpu().numpy()
+    ref = parity.oracle_reference(q_h, e_h, l_h, num_classes, k, thr)
+    near = parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, num_classes, k, thr, rel=rel, dist_rel=TIGHT)
+    # the contract's own tolerance must hold as well
+    parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, num_classes, k, thr)
+    return got, ref, near
+
+
+def test_config1_tiny_full_batch():
+    wl = synth.WORKLOADS["c1_tiny"]
+    data = synth.make_workload(wl)
+    L = data.layers[0]
+    got, ref, near = check_case(L.entries, L.labels, data.queries[0], 10, wl.k, wl.vote_thresholds[0])
+    assert got["hit"].all() and (got["votes"] == 5).all()
+    assert near < 64
+
+
+def test_hand_example_on_gpu():
+    ent = torch.tensor([[0, 0], [1, 0], [0, 2], [3, 0], [1, 0], [4, 4]], dtype=torch.float32)
+    lab = torch.tensor([0, 0, 1, 1, 1, 0], dtype=torch.int32)
+    q = torch.tensor([[1, 1], [1, 0]], dtype=torch.float32)
+    for dt in (torch.float32, torch.bfloat16):
+        got = run_lookup(ent.to(dt), lab, q, 2, 3, 2)
+        assert got["idx"][0].tolist() == [1, 4, 0] and got["dist"][0].tolist() == [1.0, 1.0, 2.0]
+        assert (got["label"][0], got["votes"][0], got["hit"][0]) == (0, 2, 1)
+        got = run_lookup(ent.to(dt), lab, q, 2, 5, 4)
+        assert got["idx"][0].tolist() == [1, 4, 0, 2, 3] and (got["label"][0], got["votes"][0], got["hit"][0]) == (1, 3, 0)
+        got = run_lookup(ent.to(dt), lab, q, 2, 2, 1)
+        assert got["idx"][1].tolist() == [1, 4] and got["dist"][1].tolist() == [0.0, 0.0]
+        assert (got["label"][1], got["votes"][1]) == (0, 1)
+        got = run_lookup(ent.to(dt), lab, q, 2, 6, 3)   # k = N
+        assert got["idx"][0].tolist() == [1, 4, 0, 2, 3, 5] and (got["label"][0], got["votes"][0]) == (0, 3)
+
+
+@pytest.mark.parametrize("n,d,b,k,r,dtype", [
+    (777, 100, 37, 7, 0, torch.float32),      # nothing a multiple of a tile; d not a multiple of 8
+    (777, 100, 37, 7, 0, torch.bfloat16),
+    (5000, 1024, 600, 10, 0, torch.bfloat16),  # 3 query tiles (ragged), 20 cache tiles, several splits
+    (3000, 256, 300, 10, 32, torch.bfloat16),  # R = 32 kernel variant
+    (3000, 320, 130, 20, 64, torch.float32),   # R = 64 kernel variant (128-query tiles), k = 20
+    (40, 64, 5, 40, 0, torch.bfloat16),        # k = N
+    (300, 64, 1, 1, 0, torch.float32),         # batch 1, k = 1
+    (1500, 192, 9, 33, 0, torch.bfloat16),     # k > 24 -> default R = 64
+])
+def test_shapes_against_oracle(n, d, b, k, r, dtype):
+    wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
+    spec = wl.layers[0]
+    spec = type(spec)(n, d, 10, spec.sigma, relu=True, store_bf16=(dtype == torch.bfloat16))
+    data = synth.make_workload(type(wl)(wl.name, (spec,), b, k, (max(1, k - 2),), r, 77 + n + d))
+    L = data.layers[0]
+    check_case(L.entries, L.labels, data.queries[0], 10, k, max(1, k - 2), r)
+
+
+def test_random_labels_and_duplicates():
+    # labels independent of geometry: votes span 1..k and label ties occur; duplicate rows: exact ties
+    wl = synth.scaled(synth.WORKLOADS["c1_tiny"], n=900, batch=120)
+    data = synth.make_workload(wl)
+    L = data.layers[0]
+    ent = L.entries.clone()
+    ent[500:520] = ent[100:120]            # exact duplicates: lower index must come first
+    lab = synth.random_labels(900, 4, 5)
+    q = data.queries[0].clone()
+    q[:20] = ent[100:120]                  # queries identical to cached rows: distance exactly 0
+    got, ref, _ = check_case(ent, lab, q, 4, 7, 4)
+    assert (got["dist"][:20, 0] == 0.0).all() and (got["dist"][:20, 1] == 0.0).all()
+    assert got["idx"][:20, 0].tolist() == list(range(100, 120))
+    assert got["idx"][:20, 1].tolist() == list(range(500, 520))
+    assert len(set(got["votes"].tolist())) >= 3
+    assert (got["dist"] >= 0).all()
+
+
+def test_threshold_monotone_and_extremes():
+    wl = synth.scaled(synth.WORKLOADS["c1_tiny"], n=600, batch=64)
+    data = synth.make_workload(wl)
+    L = data.layers[0]
+    lab = synth.random_labels(600, 3, 9)
+    prev = None
+    for thr in range(1, 6):
+        got = run_lookup(L.entries, lab, data.queries[0], 3, 5, thr)
+        if prev is not None:
+            assert (got["hit"] <= prev).all()
+        prev = got["hit"]
+        assert np.array_equal(got["hit"], (got["votes"] >= thr).astype(np.uint8))
+        if thr == 1:
+            assert got["hit"].all()
+
+
+def test_results_are_deterministic():
+    wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=4000, d_div=16, batch=300)
+    data = synth.make_workload(wl)
+    L = data.layers[0]
+    a = run_lookup(L.entries, L.labels, data.queries[0], 10, 10, 8)
+    b = run_lookup(L.entries, L.labels, data.queries[0], 10, 10, 8)
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_compact_misses_against_oracle():
+    rng = np.random.default_rng(3)
+    for count in (0, 1, 63, 64, 1023, 1024, 1025, 10000):
+        hit = (rng.random(count) < 0.37).astype(np.uint8)
+        sel = rng.permutation(max(count, 1) * 3)[:count].astype(np.int32)
+        for use_sel in (True, False):
+            hit_d = torch.from_numpy(hit).cuda()
+            sel_d = torch.from_numpy(sel).cuda() if use_sel else None
+            out = torch.full((max(count, 1),), -7, dtype=torch.int32, device="cuda")
+            cnt = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+            binding.freeze_compact_misses(hit_d, sel_d, out, cnt)
+            torch.cuda.synchronize()
+            exp = fo.compact(hit, sel if use_sel else np.arange(count, dtype=np.int32))
+            assert int(cnt.item()) == exp.size
+            assert np.array_equal(out.cpu().numpy()[:exp.size], exp)
+
+
+def _cascade_case(wl_name, n, d_div, batch):
+    wl = synth.scaled(synth.WORKLOADS[wl_name], n=n, d_div=d_div, batch=batch)
+    data = synth.make_workload(wl)
+    nl = len(wl.layers)
+    fc = binding.FreezeCache(nl)
+    try:
+        for l, L in enumerate(data.layers):
+            fc.build_layer(l, L.entries.cuda(), L.labels.cuda(), L.spec.num_classes)
+        qs = [q.cuda() for q in data.queries]
+        out = fc.lookup_cascade(list(range(nl)), qs, wl.k, list(wl.vote_thresholds), wl.rescore_r)
+        torch.cuda.synchronize()
+        got = {key: v.cpu().numpy() for key, v in out.items()}
+    finally:
+        fc.close()
+    exp_l, exp_x, exp_h, _ = fo.cascade([q.numpy() for q in data.queries],
+                                        [_host_entries(L.entries) for L in data.layers],
+                                        [L.labels.numpy() for L in data.layers],
+                                        [L.spec.num_classes for L in data.layers], wl.k, wl.vote_thresholds)
+    return got, exp_l, exp_x, exp_h
+
+
+def test_cascade_against_oracle_noisy():
+    got, exp_l, exp_x, exp_h = _cascade_case("c4_cascade_noisy", 2000, 64, 700)
+    assert np.array_equal(got["exit_layer"], exp_x)
+    assert np.array_equal(got["label"], exp_l)
+    assert got["hits_per_layer"].tolist() == exp_h.tolist()
+    assert (exp_x == -1).any() and (exp_x > 0).any() and (exp_x == 0).any()   # every branch exercised
+    assert got["hits_per_layer"].sum() + (got["exit_layer"] == -1).sum() == 700
+
+
+def test_cascade_against_oracle_clean():
+    got, exp_l, exp_x, exp_h = _cascade_case("c4_cascade", 1500, 64, 300)
+    assert np.array_equal(got["exit_layer"], exp_x) and np.array_equal(got["label"], exp_l)
+    assert got["hits_per_layer"].tolist() == exp_h.tolist()
+
+
+def test_argument_errors_launch_nothing():
+    fc = binding.FreezeCache(2)
+    try:
+        ent = torch.randn(100, 32, device="cuda")
+        lab = torch.zeros(100, dtype=torch.int32, device="cuda")
+        fc.build_layer(0, ent, lab, 3)
+        q = torch.randn(4, 32, device="cuda")
+        out = fc.alloc_outputs(4, 5)
+        for key in out:
+            out[key].fill_(42)
+        ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+
+        def call(layer=0, k=5, thr=3, r=0, wsz=None):
+            return binding.lib().freeze_lookup(fc.ctx, layer, q.data_ptr(), 4, k, thr, r, out["label"].data_ptr(),
+                                               out["hit"].data_ptr(), out["votes"].data_ptr(), out["idx"].data_ptr(),
+                                               out["dist"].data_ptr(), ws.data_ptr(),
+                                               ws.numel() if wsz is None else wsz, None)
+        assert call(layer=5) == binding.FREEZE_ELAYER
+        assert call(layer=1) == binding.FREEZE_ENOTBUILT
+        assert call(k=0) == binding.FREEZE_EINVAL
+        assert call(k=101) == binding.FREEZE_EINVAL
+        assert call(thr=0) == binding.FREEZE_EINVAL
+        assert call(thr=6) == binding.FREEZE_EINVAL
+        assert call(r=3) == binding.FREEZE_EINVAL
+        assert call(r=65) == binding.FREEZE_EINVAL
+        assert call(wsz=16) == binding.FREEZE_EWORKSPACE
+        torch.cuda.synchronize()
+        for key in out:
+            assert (out[key] == 42).all()    # nothing was written
+        assert call() == binding.FREEZE_OK
+        torch.cuda.synchronize()
+    finally:
+        fc.close()
