@@ -135,11 +135,26 @@ int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers,
  * Batch reconstruction on its own (Sec. 5): writes to sel_out the entries
  * sel_in[j] (or j itself when sel_in is NULL) with hit[j] == 0, j < count, in
  * order, and their number to *out_count.
- *   hit       [count] uint8;  sel_in [count] int32 or NULL;  sel_out [count] int32;
+ *   hit       [count] uint8;  sel_in [count] int32 or NULL;  sel_out [count] int32
+ *             (hit and sel_out may be NULL when count == 0);
  *   out_count [1] int32.
  */
 int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t count, int32_t *sel_out,
                           int32_t *out_count, void *stream);
+
+/*
+ * Stage timing for benchmarks (measurement aid; the look-up results do not depend on it).
+ * While enabled, freeze_lookup records HIP events on its stream around its three stages
+ * (query preparation, distance pass, finishing kernel) for up to FREEZE_PROFILE_MAX_CALLS
+ * calls.  freeze_profile_read waits for the recorded events, adds up the stage durations
+ * and clears the record.
+ *   stage_ms  host array [3]: summed milliseconds of {prep, distance pass, finish}.
+ *   calls     host: number of look-ups the sums cover.
+ * Events are host-side objects; no device memory is allocated.
+ */
+#define FREEZE_PROFILE_MAX_CALLS 256
+int freeze_profile_enable(freeze_ctx *ctx, int enable);
+int freeze_profile_read(freeze_ctx *ctx, float *stage_ms, int *calls);
 
 /* Static description of an error code (host string, never NULL). */
 const char *freeze_strerror(int code);

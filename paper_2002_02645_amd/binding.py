@@ -56,6 +56,10 @@ def lib():
     L.freeze_lookup_cascade.argtypes = [p, i32, p, p, i64, i32, p, i32, p, p, p, p, sz, p]
     L.freeze_compact_misses.restype = i32
     L.freeze_compact_misses.argtypes = [p, p, i64, p, p, p]
+    L.freeze_profile_enable.restype = i32
+    L.freeze_profile_enable.argtypes = [p, i32]
+    L.freeze_profile_read.restype = i32
+    L.freeze_profile_read.argtypes = [p, p, p]
     L.freeze_strerror.restype = ctypes.c_char_p
     L.freeze_strerror.argtypes = [i32]
     _lib = L
@@ -151,6 +155,20 @@ def freeze_compact_misses(hit: torch.Tensor, sel_in: Optional[torch.Tensor], sel
     assert hit.is_cuda and hit.dtype == torch.uint8
     _check(lib().freeze_compact_misses(_ptr(hit), _ptr(sel_in), hit.numel(), _ptr(sel_out), _ptr(out_count),
                                        _stream(stream)), "freeze_compact_misses")
+
+
+def freeze_profile_enable(ctx, enable: bool) -> None:
+    _check(lib().freeze_profile_enable(ctx, int(enable)), "freeze_profile_enable")
+
+
+def freeze_profile_read(ctx):
+    """Returns ([prep_ms, dist_ms, finish_ms] summed, number of look-ups covered)."""
+    ms = (ctypes.c_float * 3)()
+    calls = ctypes.c_int(0)
+    _check(lib().freeze_profile_read(ctx, ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(ctypes.byref(calls),
+                                                                                     ctypes.c_void_p)),
+           "freeze_profile_read")
+    return [float(x) for x in ms], int(calls.value)
 
 
 # ---- convenience holder: owns the context, the per-layer storage and a reusable workspace ---------

@@ -166,7 +166,13 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
             }
         }
     }
-    if (tid < r) idx_s[tid] = (int32_t)(uint32_t)(ent[tid] & 0xffffffffu);
+    if (tid < r) {
+        // With finite inputs every one of the first r entries is a real cache row.  Non-finite
+        // inputs (outside the contract) can leave "no entry" markers here: map them to row 0 so
+        // that nothing is read out of bounds.
+        const uint32_t ci = (uint32_t)(ent[tid] & 0xffffffffu);
+        idx_s[tid] = ci < (uint32_t)a.n ? (int32_t)ci : 0;
+    }
     __syncthreads();
 
     // 2. exact fp32 re-scoring, 8 candidates at a time

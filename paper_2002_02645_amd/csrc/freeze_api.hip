@@ -13,6 +13,10 @@ using namespace fz;
 struct freeze_ctx {
     std::vector<LayerCache> layers;
     int num_cus = 256;
+    // stage timing (measurement aid): 4 events per recorded look-up
+    bool profile = false;
+    std::vector<hipEvent_t> events;
+    int profiled_calls = 0;
 };
 
 namespace {
@@ -95,14 +99,45 @@ const LayerCache *get_layer(const freeze_ctx *ctx, int layer, int *err)
 }
 
 // Enqueue one look-up.  `sel` / `count` (device) restrict it to the live requests of a cascade.
-int enqueue_lookup(const LayerCache &L, const LookupShape &sh, const float *queries, const int32_t *sel,
+// Records the next stage boundary of a profiled look-up (no-op when profiling is off).
+struct StageMarks {
+    freeze_ctx *ctx;
+    hipStream_t s;
+    int slot;   // event index of this call's first mark, or -1
+    StageMarks(freeze_ctx *c, hipStream_t st) : ctx(c), s(st), slot(-1)
+    {
+        if (c && c->profile && c->profiled_calls < FREEZE_PROFILE_MAX_CALLS) {
+            slot = 4 * c->profiled_calls;
+            while ((int)c->events.size() < slot + 4) {
+                hipEvent_t e;
+                if (hipEventCreate(&e) != hipSuccess) {
+                    slot = -1;
+                    return;
+                }
+                c->events.push_back(e);
+            }
+        }
+    }
+    void mark(int i)
+    {
+        if (slot >= 0) (void)hipEventRecord(ctx->events[slot + i], s);
+    }
+    void done()
+    {
+        if (slot >= 0) ++ctx->profiled_calls;
+    }
+};
+
+int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, const float *queries, const int32_t *sel,
                    const int32_t *count, int64_t b, int k, int vote_threshold, int32_t *out_labels, uint8_t *out_hit,
                    int32_t *out_votes, int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace, hipStream_t s)
 {
     Carver ws(workspace);
     uint16_t *q_bf = ws.take<uint16_t>((size_t)sh.plan.b_pad * L.d_pad);
     uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * sh.plan.n_splits * sh.r);
+    StageMarks marks(ctx, s);
 
+    marks.mark(0);
     if (launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf, s) != hipSuccess)
         return FREEZE_EHIP;
 
@@ -115,7 +150,9 @@ int enqueue_lookup(const LayerCache &L, const LookupShape &sh, const float *quer
     da.b = (int)b;
     da.n = (int)L.n;
     da.d_pad = (int)L.d_pad;
+    marks.mark(1);
     if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
+    marks.mark(2);
 
     FinishArgs fa{};
     fa.part = part;
@@ -125,6 +162,7 @@ int enqueue_lookup(const LayerCache &L, const LookupShape &sh, const float *quer
     fa.sel = sel;
     fa.count = count;
     fa.b = (int)b;
+    fa.n = (int)L.n;
     fa.d = L.d;
     fa.d_pad = L.d_pad;
     fa.c_bf = L.c_bf;
@@ -138,6 +176,8 @@ int enqueue_lookup(const LayerCache &L, const LookupShape &sh, const float *quer
     fa.out_nbr_idx = out_nbr_idx;
     fa.out_nbr_dist = out_nbr_dist;
     if (launch_finish(fa, s) != hipSuccess) return FREEZE_EHIP;
+    marks.mark(3);
+    marks.done();
     return FREEZE_OK;
 }
 
@@ -197,6 +237,7 @@ int freeze_create(freeze_ctx **out, int num_layers)
 int freeze_destroy(freeze_ctx *ctx)
 {
     if (!ctx) return FREEZE_EINVAL;
+    for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
     delete ctx;
     return FREEZE_OK;
 }
@@ -266,7 +307,7 @@ int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, i
     if (workspace_bytes < sh.ws_bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
         return FREEZE_EWORKSPACE;
     if (b == 0) return FREEZE_OK;
-    return enqueue_lookup(*L, sh, queries, nullptr, nullptr, b, k, vote_threshold, out_labels, out_hit, out_votes,
+    return enqueue_lookup(ctx, *L, sh, queries, nullptr, nullptr, b, k, vote_threshold, out_labels, out_hit, out_votes,
                           out_nbr_idx, out_nbr_dist, workspace, static_cast<hipStream_t>(stream));
 }
 
@@ -326,7 +367,7 @@ int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers, co
         const LayerCache &L = ctx->layers[layers[l]];
         LookupShape sh;
         lookup_shape(ctx, L, b, k, rescore_r, &sh);
-        int rc = enqueue_lookup(L, sh, queries_per_layer[l], sel, count, b, k, vote_thresholds[l], t_labels, t_hit,
+        int rc = enqueue_lookup(ctx, L, sh, queries_per_layer[l], sel, count, b, k, vote_thresholds[l], t_labels, t_hit,
                                 t_votes, t_idx, t_dist, lookup_ws, s);
         if (rc != FREEZE_OK) return rc;
         if (launch_cascade_scatter(t_labels, t_hit, sel, count, b, l, out_labels, out_exit_layer, s) != hipSuccess)
@@ -344,10 +385,37 @@ int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers, co
 int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t count, int32_t *sel_out,
                           int32_t *out_count, void *stream)
 {
-    if (!hit || !sel_out || !out_count || count < 0 || count > (int64_t)1 << 30) return FREEZE_EINVAL;
+    if (!out_count || count < 0 || count > (int64_t)1 << 30) return FREEZE_EINVAL;
+    if (count > 0 && (!hit || !sel_out)) return FREEZE_EINVAL;
     if (launch_compact(hit, sel_in, nullptr, count, sel_out, out_count, nullptr, static_cast<hipStream_t>(stream)) !=
         hipSuccess)
         return FREEZE_EHIP;
+    return FREEZE_OK;
+}
+
+int freeze_profile_enable(freeze_ctx *ctx, int enable)
+{
+    if (!ctx) return FREEZE_EINVAL;
+    ctx->profile = enable != 0;
+    ctx->profiled_calls = 0;
+    return FREEZE_OK;
+}
+
+int freeze_profile_read(freeze_ctx *ctx, float *stage_ms, int *calls)
+{
+    if (!ctx || !stage_ms || !calls) return FREEZE_EINVAL;
+    stage_ms[0] = stage_ms[1] = stage_ms[2] = 0.f;
+    for (int c = 0; c < ctx->profiled_calls; ++c) {
+        if (hipEventSynchronize(ctx->events[4 * c + 3]) != hipSuccess) return FREEZE_EHIP;
+        for (int i = 0; i < 3; ++i) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, ctx->events[4 * c + i], ctx->events[4 * c + i + 1]) != hipSuccess)
+                return FREEZE_EHIP;
+            stage_ms[i] += ms;
+        }
+    }
+    *calls = ctx->profiled_calls;
+    ctx->profiled_calls = 0;
     return FREEZE_OK;
 }
 

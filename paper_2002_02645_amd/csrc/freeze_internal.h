@@ -68,6 +68,7 @@ struct FinishArgs {
     const int32_t *sel;     // compact position -> row of `queries`, or null
     const int32_t *count;   // device live-query count or null
     int b;
+    int n;                  // cache entries (candidate indices are checked against it)
     int64_t d, d_pad;
     const uint16_t *c_bf;
     const float *c_f32;     // non-null: re-score against the fp32 rows
