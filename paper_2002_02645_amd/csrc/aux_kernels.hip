@@ -31,35 +31,44 @@ __device__ __forceinline__ float block_sum_256(float v, float *scratch4)
 
 // ---------------------------------------------------------------------------------------
 // Cache ingest (Pseudocode 1, ConstructCache: the layer's list of <output, label>).
-// One block per padded cache row: bf16 copy (round to nearest even when given fp32), zero
-// padding, |c|^2 of the bf16 row in fp32, optional fp32 copy for exact re-scoring.
+// One block per padded cache row: bf16 copy (round to nearest even when given fp32) into the
+// tiled layout, zero padding, |c|^2 of the bf16 row in fp32, optional row-major fp32 copy for
+// exact re-scoring.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, int dtype, int64_t n, int64_t d,
                                                           int64_t d_pad, uint16_t *c_bf, float *norm, float *c_f32)
 {
     __shared__ float red[4];
     const int64_t row = blockIdx.x;
-    uint16_t *dst = c_bf + row * d_pad;
+    const int64_t tile = row / kTileN;
+    const int rit = (int)(row % kTileN);
+    uint4 *tile_base = reinterpret_cast<uint4 *>(c_bf + tile * kTileN * d_pad);
     float ss = 0.f;
-    if (row < n) {
-        for (int64_t i = threadIdx.x; i < d_pad; i += 256) {
-            uint16_t h = 0;
+    for (int64_t j = threadIdx.x; j < d_pad / 8; j += 256) {   // one 16-byte chunk (8 elements) per step
+        uint16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t i = j * 8 + e;
             float f = 0.f;
-            if (i < d) {
+            h[e] = 0;
+            if (row < n && i < d) {
                 if (dtype == 0) {
                     f = reinterpret_cast<const float *>(entries)[row * d + i];
-                    h = bf16_rne(f);
+                    h[e] = bf16_rne(f);
                 } else {
-                    h = reinterpret_cast<const uint16_t *>(entries)[row * d + i];
+                    h[e] = reinterpret_cast<const uint16_t *>(entries)[row * d + i];
                 }
             }
-            dst[i] = h;
-            if (c_f32) c_f32[row * d_pad + i] = f;
-            const float x = bf16_to_f32(h);
+            if (c_f32 && row < n) c_f32[row * d_pad + i] = f;
+            const float x = bf16_to_f32(h[e]);
             ss = __builtin_fmaf(x, x, ss);
         }
-    } else {
-        for (int64_t i = threadIdx.x; i < d_pad; i += 256) dst[i] = 0;
+        uint4 v;
+        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
+        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+        tile_base[tiled_chunk_offset(rit, j, kTileN)] = v;
     }
     const float tot = block_sum_256(ss, red);
     if (threadIdx.x == 0) norm[row] = (row < n) ? tot : __builtin_inff();
@@ -85,8 +94,8 @@ hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t
 
 // ---------------------------------------------------------------------------------------
 // Query preparation: bf16 copy (round to nearest even) of the live queries for the matrix
-// cores, gathered through the miss list when there is one; rows up to the next tile
-// boundary are zero filled.  One block per row.
+// cores in the tiled layout (tiles of bm rows), gathered through the miss list when there is
+// one; rows up to the next tile boundary are zero filled.  One block per row.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, const int32_t *sel, const int32_t *count,
                                                          int b, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf)
@@ -95,12 +104,22 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
     const int row = blockIdx.x;
     const int live_pad = ((nq + bm - 1) / bm) * bm;
     if (row >= live_pad) return;
-    uint16_t *dst = q_bf + (int64_t)row * d_pad;
-    if (row < nq) {
-        const float *src = queries + (int64_t)(sel ? sel[row] : row) * d;
-        for (int64_t i = threadIdx.x; i < d_pad; i += 256) dst[i] = (i < d) ? bf16_rne(src[i]) : (uint16_t)0;
-    } else {
-        for (int64_t i = threadIdx.x; i < d_pad; i += 256) dst[i] = 0;
+    const int rit = row % bm;
+    uint4 *tile_base = reinterpret_cast<uint4 *>(q_bf + (int64_t)(row / bm) * bm * d_pad);
+    const float *src = (row < nq) ? queries + (int64_t)(sel ? sel[row] : row) * d : nullptr;
+    for (int64_t j = threadIdx.x; j < d_pad / 8; j += 256) {
+        uint16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t i = j * 8 + e;
+            h[e] = (src && i < d) ? bf16_rne(src[i]) : (uint16_t)0;
+        }
+        uint4 v;
+        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
+        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+        tile_base[tiled_chunk_offset(rit, j, bm)] = v;
     }
 }
 
@@ -131,7 +150,7 @@ struct FinishKernelArgs {
 __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
 {
     const FinishArgs &a = fa.a;
-    __shared__ uint64_t ent[kMaxMergeEntries];
+    extern __shared__ uint64_t ent[];   // sort_n entries (dynamic: small merges keep occupancy high)
     __shared__ float red[4][8];
     __shared__ float dist_s[kMaxRescore];
     __shared__ int32_t idx_s[kMaxRescore];
@@ -183,8 +202,14 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.f;
         int64_t cand[8];
+        const uint4 *cand_tile[8];   // tile base of the candidate's row in the tiled bf16 cache
+        int cand_rit[8];             // its row inside the tile
 #pragma unroll
-        for (int j = 0; j < 8; ++j) cand[j] = idx_s[(r0 + j < r) ? r0 + j : r - 1];
+        for (int j = 0; j < 8; ++j) {
+            cand[j] = idx_s[(r0 + j < r) ? r0 + j : r - 1];
+            cand_tile[j] = reinterpret_cast<const uint4 *>(a.c_bf + (cand[j] / kTileN) * kTileN * a.d_pad);
+            cand_rit[j] = (int)(cand[j] % kTileN);
+        }
         if (vec) {
             for (int64_t i = (int64_t)tid * 8; i < a.d; i += 256 * 8) {
                 const f32x4 q0 = *reinterpret_cast<const f32x4 *>(qrow + i);
@@ -206,7 +231,7 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
                 } else {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
-                        const uint4 cb = *reinterpret_cast<const uint4 *>(a.c_bf + cand[j] * a.d_pad + i);
+                        const uint4 cb = cand_tile[j][tiled_chunk_offset(cand_rit[j], i >> 3, kTileN)];
                         const uint32_t wv[4] = {cb.x, cb.y, cb.z, cb.w};
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
@@ -225,7 +250,14 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
                 const float qv = qrow[i];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float cv = a.c_f32 ? a.c_f32[cand[j] * a.d_pad + i] : bf16_to_f32(a.c_bf[cand[j] * a.d_pad + i]);
+                    float cv;
+                    if (a.c_f32) {
+                        cv = a.c_f32[cand[j] * a.d_pad + i];
+                    } else {
+                        const uint16_t *chunk = reinterpret_cast<const uint16_t *>(
+                            cand_tile[j] + tiled_chunk_offset(cand_rit[j], i >> 3, kTileN));
+                        cv = bf16_to_f32(chunk[i & 7]);
+                    }
                     const float df = qv - cv;
                     acc[j] = __builtin_fmaf(df, df, acc[j]);
                 }
@@ -293,7 +325,7 @@ hipError_t launch_finish(const FinishArgs &a, hipStream_t s)
     if (total > kMaxMergeEntries || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r) return hipErrorInvalidValue;
     FinishKernelArgs fa{a, 2};
     while (fa.sort_n < total) fa.sort_n <<= 1;
-    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)a.b), dim3(256), 0, s, fa);
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)a.b), dim3(256), (size_t)fa.sort_n * sizeof(uint64_t), s, fa);
     return hipGetLastError();
 }
 

@@ -18,11 +18,14 @@
 // cache tiles, so that operand re-reads are served by that XCD's L2.
 //
 // Main loop: 8 waves (2 x 4), each owning a (TM*32) x 64 block of the tile as
-// 32x32x16 bf16 MFMA accumulators.  Operands are streamed global -> LDS with
-// LDS-direct 16-byte loads (no VGPR staging) into two stages; 16-byte chunks are
-// XOR-swizzled inside each row so the ds_read_b128 fragment reads are bank-conflict
-// free.  The loads are issued with inline asm: the compiler would otherwise order
-// every LDS read behind the outstanding direct loads, serialising load and compute.
+// 32x32x16 bf16 MFMA accumulators.  Both operands are stored in memory in a tiled,
+// pre-swizzled layout ([row tile][k-block][row][32 elements], see tiled_chunk_offset)
+// whose per-k-step blocks are contiguous and are exactly the LDS image, so a stage is
+// filled by a linear copy with LDS-direct 16-byte loads (no VGPR staging, fully
+// sequential DRAM access) into a ring of NS stages with NS-1 stages in flight.  The
+// chunk swizzle makes the ds_read_b128 fragment reads bank-conflict free.  The loads
+// are issued with inline asm: the compiler would otherwise order every LDS read
+// behind the outstanding direct loads, serialising load and compute.
 //
 // Epilogue (per tile, in column slabs that reuse the operand LDS): waves write their
 // keys to the slab; thread t scans row t, collecting a bit mask of keys not above the
@@ -44,7 +47,9 @@ __device__ __forceinline__ void load16_global_to_lds(const void *g, uint32_t lds
                  : "memory", "m0");
 }
 
-__device__ __forceinline__ void wait_all_global_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Wait until at most N of this wave's global loads are outstanding (loads complete in order).
+template <int N>
+__device__ __forceinline__ void wait_global_loads_le() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 // fp32 -> unsigned with the same order (so that (key, index) packs into one u64)
 __device__ __forceinline__ uint32_t ordered_bits(float x)
@@ -57,19 +62,20 @@ __device__ __forceinline__ float from_ordered_bits(uint32_t u)
     return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
 }
 
-template <int BM_, int BK_, int RMAX_>
+template <int BM_, int BK_, int RMAX_, int NS_>
 struct DistCfg {
     static constexpr int BM = BM_, BN = kTileN, BK = BK_, RMAX = RMAX_;
-    static constexpr int NS = 2;                    // operand stages in LDS
+    static constexpr int NS = NS_;                  // operand stages in LDS (NS - 1 loads in flight)
     static constexpr int WM = 2, WN = 4;            // wave grid
     static constexpr int NWAVES = WM * WN, THREADS = 64 * NWAVES;
     static constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
-    static constexpr int CPR = BK / 8;              // 16-byte chunks per operand row
+    static constexpr int NSUB = BK / kKB;           // k-blocks (of 32 elements) per stage
     static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
     static constexpr int A_BYTES = BM * BK * 2;
     static constexpr int OP_BYTES = NS * STAGE_BYTES;
-    static constexpr int NI_A = BM * CPR / 64 / NWAVES;   // direct-load instructions per wave and stage
-    static constexpr int NI_B = BN * CPR / 64 / NWAVES;
+    static constexpr int NI_A = BM * BK * 2 / 1024 / NWAVES;   // direct-load instructions per wave and stage
+    static constexpr int NI_B = BN * BK * 2 / 1024 / NWAVES;
+    static_assert(BK % kKB == 0, "a stage is a whole number of k-blocks");
     // slab pass: WNS wave columns at a time
     static constexpr int WNS = (BM * 4 * 32 * 4 <= OP_BYTES) ? 4 : ((BM * 2 * 32 * 4 <= OP_BYTES) ? 2 : 1);
     static constexpr int SLABW = WNS * 32;          // keys per row in one slab
@@ -79,17 +85,9 @@ struct DistCfg {
     static_assert(LDS_BYTES <= 163840, "LDS budget");
     static_assert(NI_A >= 1 && NI_B >= 1, "load split");
     static_assert(BM <= THREADS, "one scanning thread per row");
+    static constexpr int LPS = NI_A + NI_B;         // direct loads per thread and stage
+    static_assert(NS >= 2 && NS <= 4 && (NS - 2) * LPS <= 63, "vmcnt range");
 };
-
-// chunk swizzle: physical chunk = logical chunk ^ swz(row); conflict-free for 8- and 16-lane groups
-template <int CPR>
-__device__ __forceinline__ int swz(int row)
-{
-    if constexpr (CPR == 8)
-        return ((row ^ (row >> 3)) & 1) | (row & 6);
-    else
-        return (((row >> 1) ^ (row >> 3)) & 1) | ((row >> 1) & 2);
-}
 
 struct DistKernelArgs {
     const uint16_t *q_bf;
@@ -105,7 +103,7 @@ struct DistKernelArgs {
 template <class C>
 __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 {
-    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, CPR = C::CPR, TM = C::TM, TN = C::TN;
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, TM = C::TM, TN = C::TN;
     __shared__ __attribute__((aligned(16))) unsigned char smem[C::LDS_BYTES];
     uint64_t *top = reinterpret_cast<uint64_t *>(smem + C::OP_BYTES);   // [RMAX][BM]
     float *slab = reinterpret_cast<float *>(smem);                      // [BM][SLABW], aliases operands
@@ -140,42 +138,34 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     }
 
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
-    const size_t row_bytes = (size_t)p.d_pad * 2;
+    const size_t tile_row_bytes = (size_t)p.d_pad * 2;   // bytes of one row; a tile of T rows holds T * this
 
-    // global source pointers of this thread's direct loads (k offset 0)
-    const unsigned char *srcA[C::NI_A];
-    const unsigned char *srcB[C::NI_B];
-#pragma unroll
-    for (int i = 0; i < C::NI_A; ++i) {
-        const int ch = (i * C::NWAVES + w) * 64 + lane;
-        const int row = ch / CPR, pc = ch % CPR, c = pc ^ swz<CPR>(row);
-        srcA[i] = reinterpret_cast<const unsigned char *>(p.q_bf) + ((size_t)mt * BM + row) * row_bytes + c * 16;
-    }
-    // fragment read addresses (in 16-byte units, relative to the stage's A / B area)
+    // Direct loads copy a stage linearly: wave w, instruction i moves the 1 KiB at offset
+    // (i * NWAVES + w) * 1024 of the stage's A (or B) image; lane l moves 16 bytes at + 16 l.
+    const unsigned char *gA = reinterpret_cast<const unsigned char *>(p.q_bf) + (size_t)mt * BM * tile_row_bytes +
+                              w * 1024 + lane * 16;
+    // fragment read addresses, in 16-byte units relative to the stage's A / B image
     const int g = lane >> 5;
     const int rowA = wm * TM * 32 + (lane & 31);
     const int rowB = wn * TN * 32 + (lane & 31);
-    const int rdA = rowA * CPR, pcxA = g ^ swz<CPR>(rowA);
-    const int rdB = rowB * CPR, pcxB = g ^ swz<CPR>(rowB);
+    const int rdA = rowA * 4, pcxA = g ^ tiled_chunk_swizzle(rowA);
+    const int rdB = rowB * 4, pcxB = g ^ tiled_chunk_swizzle(rowB);
     const int nk = p.d_pad / BK;
 
     for (int nt = nt0; nt < nt1; ++nt) {
         const int n0 = nt * BN;
-#pragma unroll
-        for (int i = 0; i < C::NI_B; ++i) {
-            const int ch = (i * C::NWAVES + w) * 64 + lane;
-            const int row = ch / CPR, pc = ch % CPR, c = pc ^ swz<CPR>(row);
-            srcB[i] = reinterpret_cast<const unsigned char *>(p.c_bf) + ((size_t)n0 + row) * row_bytes + c * 16;
-        }
+        const unsigned char *gB = reinterpret_cast<const unsigned char *>(p.c_bf) + (size_t)nt * BN * tile_row_bytes +
+                                  w * 1024 + lane * 16;
         auto issue = [&](int stage, int kt) {
-            const uint32_t sbase = smem_base + stage * C::STAGE_BYTES;
-            const size_t koff = (size_t)kt * (BK * 2);
+            const uint32_t sbase = smem_base + stage * C::STAGE_BYTES + w * 1024;
+            const unsigned char *a = gA + (size_t)kt * C::A_BYTES;
+            const unsigned char *b = gB + (size_t)kt * (BN * BK * 2);
 #pragma unroll
             for (int i = 0; i < C::NI_A; ++i)
-                load16_global_to_lds(srcA[i] + koff, sbase + (i * C::NWAVES + w) * 1024);
+                load16_global_to_lds(a + i * (C::NWAVES * 1024), sbase + i * (C::NWAVES * 1024));
 #pragma unroll
             for (int i = 0; i < C::NI_B; ++i)
-                load16_global_to_lds(srcB[i] + koff, sbase + C::A_BYTES + (i * C::NWAVES + w) * 1024);
+                load16_global_to_lds(b + i * (C::NWAVES * 1024), sbase + C::A_BYTES + i * (C::NWAVES * 1024));
         };
 
         f32x16 acc[TM][TN];
@@ -186,27 +176,39 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-        issue(0, 0);
+#pragma unroll
+        for (int ps = 0; ps < C::NS - 1; ++ps)
+            if (ps < nk) issue(ps, ps);
+        int st = 0;
         for (int kt = 0; kt < nk; ++kt) {
-            const int st = kt & 1;
-            wait_all_global_loads();   // stage `st` has landed
-            __syncthreads();           // ... for every wave; and all reads of the other stage are done
-            if (kt + 1 < nk) issue(st ^ 1, kt + 1);
+            // stage `st` must have landed; the (up to NS-2) younger stages may stay in flight
+            const int younger = nk - 1 - kt;
+            if (C::NS >= 4 && younger >= 2)
+                wait_global_loads_le<(C::NS >= 4 ? 2 : 0) * C::LPS>();
+            else if (C::NS >= 3 && younger >= 1)
+                wait_global_loads_le<(C::NS >= 3 ? 1 : 0) * C::LPS>();
+            else
+                wait_global_loads_le<0>();
+            __syncthreads();   // ... for every wave; and all reads of the stage refilled next are done
+            if (kt + C::NS - 1 < nk) issue((st + C::NS - 1) % C::NS, kt + C::NS - 1);
             const int baseA = st * (C::STAGE_BYTES / 16) + rdA;
             const int baseB = st * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB;
 #pragma unroll
             for (int kk = 0; kk < BK / 16; ++kk) {
                 bf16x8 af[TM], bfr[TN];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) af[i] = smem16[baseA + i * 32 * CPR + ((kk << 1) ^ pcxA)];
+                for (int i = 0; i < TM; ++i)
+                    af[i] = smem16[baseA + (kk >> 1) * (BM * 4) + i * 128 + (((kk & 1) << 1) ^ pcxA)];
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bfr[j] = smem16[baseB + j * 32 * CPR + ((kk << 1) ^ pcxB)];
+                for (int j = 0; j < TN; ++j)
+                    bfr[j] = smem16[baseB + (kk >> 1) * (BN * 4) + j * 128 + (((kk & 1) << 1) ^ pcxB)];
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
             }
+            st = (st + 1 == C::NS) ? 0 : st + 1;
         }
         __syncthreads();   // operand LDS is free: the slab may overwrite it
 
@@ -301,21 +303,25 @@ DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus)
     if (pl.m_tiles < 1) pl.m_tiles = 1;
     pl.n_tiles = (int)((n + kTileN - 1) / kTileN);
     pl.b_pad = (int64_t)pl.m_tiles * pl.bm;
-    // Choose the number of splits: best fill of the CUs over whole rounds, fewest splits on ties.
+    // Choose the number of splits.  More splits fill the CUs more evenly, but every split restarts
+    // its top-R lists from scratch and adds entries to the merge, so take the FEWEST splits whose
+    // CU fill (over whole rounds of workgroups) is within 10% of the best achievable.
     const int max_splits = pl.n_tiles < kMaxMergeEntries / r ? pl.n_tiles : kMaxMergeEntries / r;
-    double best_eff = -1.0;
-    int best_s = 1;
     const double total = (double)pl.m_tiles * pl.n_tiles;
-    for (int s = 1; s <= max_splits; ++s) {
+    auto fill = [&](int s) {
         const int64_t units = (int64_t)pl.m_tiles * s;
         const int64_t rounds = (units + num_cus - 1) / num_cus;
         const int tiles_per_unit = (pl.n_tiles + s - 1) / s;
-        const double eff = total / ((double)rounds * num_cus * tiles_per_unit);
-        if (eff > best_eff * 1.02) {   // a later (larger) s must win by 2% to be taken
-            best_eff = eff;
+        return total / ((double)rounds * num_cus * tiles_per_unit);
+    };
+    double best_eff = 0.0;
+    for (int s = 1; s <= max_splits; ++s) best_eff = fill(s) > best_eff ? fill(s) : best_eff;
+    int best_s = 1;
+    for (int s = 1; s <= max_splits; ++s)
+        if (fill(s) >= 0.9 * best_eff) {
             best_s = s;
+            break;
         }
-    }
     pl.n_splits = best_s;
     return pl;
 }
@@ -344,9 +350,9 @@ hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t
 {
     if (plan.r < 1 || plan.r > kMaxRescore || a.d_pad % kPadD != 0) return hipErrorInvalidValue;
     switch (plan.variant) {
-    case 0: return launch_variant<DistCfg<256, 64, 16>>(plan, a, s);
-    case 1: return launch_variant<DistCfg<256, 32, 32>>(plan, a, s);
-    default: return launch_variant<DistCfg<128, 64, 64>>(plan, a, s);
+    case 0: return launch_variant<DistCfg<256, 64, 16, 2>>(plan, a, s);
+    case 1: return launch_variant<DistCfg<256, 32, 32, 3>>(plan, a, s);
+    default: return launch_variant<DistCfg<128, 32, 64, 3>>(plan, a, s);
     }
 }
 

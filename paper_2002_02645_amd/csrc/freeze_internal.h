@@ -10,6 +10,26 @@ namespace fz {
 
 constexpr int kTileN = 256;      // cache entries per matrix-core tile; cache rows are padded to it
 constexpr int kPadD = 64;        // activation length is padded to a multiple of this (bf16 copies)
+constexpr int kKB = 32;          // elements per k-block of the tiled bf16 layout (64 bytes per row piece)
+
+// Tiled bf16 operand layout (cache and prepared queries).  A matrix of rows x d_pad is stored as
+//   [row tile][k-block][row in tile][32 elements]
+// so that the operands of one k-step of one tile are one contiguous run of memory that the
+// distance kernel copies verbatim into LDS.  Inside each 64-byte row piece the four 16-byte
+// chunks are XOR-swizzled with a function of the row so that the matrix-core fragment reads
+// (one chunk per lane, 32 consecutive rows) fall into distinct LDS banks.
+__host__ __device__ inline int tiled_chunk_swizzle(int row)
+{
+    return (((row >> 1) ^ (row >> 3)) & 1) | ((row >> 1) & 2);
+}
+// Offset, in 16-byte chunks, of logical chunk `j` (elements 8j .. 8j+7) of row `row_in_tile`
+// inside a row tile of `tile_rows` rows.
+__host__ __device__ inline int64_t tiled_chunk_offset(int row_in_tile, int64_t j, int tile_rows)
+{
+    const int64_t kb = j >> 2;
+    const int c = (int)(j & 3);
+    return (kb * tile_rows + row_in_tile) * 4 + (c ^ tiled_chunk_swizzle(row_in_tile));
+}
 constexpr int kMaxRescore = 64;  // largest re-scoring width R
 constexpr int kMaxK = 64;
 constexpr int kMaxMergeEntries = 8192;  // n_splits * R gathered per query in the finishing kernel
@@ -22,7 +42,7 @@ struct LayerCache {
     int64_t n_pad = 0, d_pad = 0;
     int32_t num_classes = 0;
     int entries_dtype = 0;
-    const uint16_t *c_bf = nullptr;   // [n_pad, d_pad] bf16, zero padded
+    const uint16_t *c_bf = nullptr;   // n_pad x d_pad bf16, zero padded, tiled layout (tiles of kTileN rows)
     const float *norm = nullptr;      // [n_pad] sum of squares of the bf16 row, fp32
     const int32_t *labels = nullptr;  // [n]
     const float *c_f32 = nullptr;     // [n, d_pad] fp32 rows when the cache was given in fp32, else null
@@ -42,8 +62,8 @@ struct DistPlan {
 DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus);
 
 struct DistArgs {
-    const uint16_t *q_bf;   // [b_pad, d_pad]
-    const uint16_t *c_bf;   // [n_pad, d_pad]
+    const uint16_t *q_bf;   // b_pad x d_pad, tiled layout (tiles of plan.bm rows)
+    const uint16_t *c_bf;   // n_pad x d_pad, tiled layout (tiles of kTileN rows)
     const float *norm;      // [n_pad]
     uint64_t *part;         // [b_pad, n_splits, r] packed (ordered key, index)
     const int32_t *count;   // device: number of live queries, or null (= b)
