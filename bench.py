@@ -110,7 +110,7 @@ def main() -> int:
         achieved = cache_bytes / (dist_ms * 1e-3) / 1e9
         roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=round(achieved / PEAK_HBM_GBS, 4), traffic=None)
-    roofline["kernel"] = "dist_topr_kernel"
+    roofline["kernel"] = "dist_topr_kernel" if b > 16 or spec.d > 1024 else "dist_skinny_kernel"
     roofline["kernel_ms"] = round(dist_ms, 4)
     roofline["stage_ms"] = {"query_prep": round(stage_ms[0] / max(calls, 1), 4), "dist_topr": round(dist_ms, 4),
                             "finish": round(stage_ms[2] / max(calls, 1), 4)}

@@ -62,11 +62,13 @@ int default_rescore(int k) { return k <= 10 ? 16 : (k <= 24 ? 32 : 64); }
 // Validated parameters of one look-up on one layer.
 struct LookupShape {
     int r;
+    bool skinny;   // small-batch bandwidth-bound kernel instead of the tiled matrix-core kernel
     DistPlan plan;
     size_t ws_bytes;
 };
 
-bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, int rescore_r, LookupShape *out)
+bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, int rescore_r, bool cascade,
+                  LookupShape *out)
 {
     if (b < 0 || b > (int64_t)1 << 30 || k < 1 || k > FREEZE_MAX_K || k > L.n) return false;
     int r = rescore_r == 0 ? default_rescore(k) : rescore_r;
@@ -74,7 +76,20 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     if (r < k) r = k;
     if ((int64_t)r > L.n) r = (int)L.n;
     out->r = r;
-    out->plan = plan_dist(b, L.n, r, ctx->num_cus);
+    out->skinny = !cascade && b <= kSkinnyRows && L.d_pad <= kSkinnyMaxD;
+    if (out->skinny) {
+        DistPlan pl{};
+        pl.variant = -1;
+        pl.bm = 32;   // the query block fed to the matrix cores
+        pl.r = r;
+        pl.m_tiles = 1;
+        pl.n_tiles = (int)((L.n + kTileN - 1) / kTileN);
+        pl.n_splits = plan_skinny_splits(L.n, r, ctx->num_cus);
+        pl.b_pad = 32;
+        out->plan = pl;
+    } else {
+        out->plan = plan_dist(b, L.n, r, ctx->num_cus);
+    }
     out->ws_bytes = align_up((size_t)out->plan.b_pad * L.d_pad * 2) +
                     align_up((size_t)out->plan.b_pad * out->plan.n_splits * r * 8);
     return true;
@@ -151,7 +166,8 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     da.n = (int)L.n;
     da.d_pad = (int)L.d_pad;
     marks.mark(1);
-    if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
+    if ((sh.skinny ? launch_dist_skinny(da, sh.plan.n_splits, sh.r, s) : launch_dist_topr(sh.plan, da, s)) != hipSuccess)
+        return FREEZE_EHIP;
     marks.mark(2);
 
     FinishArgs fa{};
@@ -198,7 +214,7 @@ bool cascade_layout(const freeze_ctx *ctx, int num_layers, const int *layers, in
         const LayerCache *L = get_layer(ctx, layers[l], err);
         if (!L) return false;
         LookupShape sh;
-        if (!lookup_shape(ctx, *L, b, k, rescore_r, &sh)) {
+        if (!lookup_shape(ctx, *L, b, k, rescore_r, true, &sh)) {
             *err = FREEZE_EINVAL;
             return false;
         }
@@ -287,7 +303,7 @@ size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b
     int err;
     const LayerCache *L = get_layer(ctx, layer, &err);
     LookupShape sh;
-    if (!L || !lookup_shape(ctx, *L, b, k, rescore_r, &sh)) return 0;
+    if (!L || !lookup_shape(ctx, *L, b, k, rescore_r, false, &sh)) return 0;
     return sh.ws_bytes;
 }
 
@@ -302,7 +318,7 @@ int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, i
         return FREEZE_EINVAL;
     if ((reinterpret_cast<uintptr_t>(queries) % 16) != 0) return FREEZE_EINVAL;
     LookupShape sh;
-    if (!lookup_shape(ctx, *L, b, k, rescore_r, &sh)) return FREEZE_EINVAL;
+    if (!lookup_shape(ctx, *L, b, k, rescore_r, false, &sh)) return FREEZE_EINVAL;
     if (vote_threshold < 1 || vote_threshold > k) return FREEZE_EINVAL;
     if (workspace_bytes < sh.ws_bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
         return FREEZE_EWORKSPACE;
@@ -366,7 +382,7 @@ int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers, co
     for (int l = 0; l < num_layers; ++l) {
         const LayerCache &L = ctx->layers[layers[l]];
         LookupShape sh;
-        lookup_shape(ctx, L, b, k, rescore_r, &sh);
+        lookup_shape(ctx, L, b, k, rescore_r, true, &sh);
         int rc = enqueue_lookup(ctx, L, sh, queries_per_layer[l], sel, count, b, k, vote_thresholds[l], t_labels, t_hit,
                                 t_votes, t_idx, t_dist, lookup_ws, s);
         if (rc != FREEZE_OK) return rc;

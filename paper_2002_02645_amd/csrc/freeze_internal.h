@@ -33,6 +33,8 @@ __host__ __device__ inline int64_t tiled_chunk_offset(int row_in_tile, int64_t j
 constexpr int kMaxRescore = 64;  // largest re-scoring width R
 constexpr int kMaxK = 64;
 constexpr int kMaxMergeEntries = 8192;  // n_splits * R gathered per query in the finishing kernel
+constexpr int kSkinnyRows = 16;         // small-batch (bandwidth-bound) path: at most this many queries ...
+constexpr int kSkinnyMaxD = 1024;       // ... and at most this padded activation length
 constexpr uint64_t kSentinel = ~0ull;   // "no entry" in (key, index) lists; larger than every real entry
 
 // One layer's cache inside the caller's storage buffer.
@@ -80,6 +82,11 @@ hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int
                              int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, hipStream_t s);
 
 hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t s);
+
+// Small-batch path: one workgroup per range of cache tiles; q_bf is a 32-row tiled block,
+// `part` is [b, n_splits, r].
+int plan_skinny_splits(int64_t n, int r, int num_cus);
+hipError_t launch_dist_skinny(const DistArgs &a, int n_splits, int r, hipStream_t s);
 
 struct FinishArgs {
     const uint64_t *part;   // [b_pad, n_splits, r]

@@ -73,6 +73,10 @@ def test_hand_example_on_gpu():
     (40, 64, 5, 40, 0, torch.bfloat16),        # k = N
     (300, 64, 1, 1, 0, torch.float32),         # batch 1, k = 1
     (1500, 192, 9, 33, 0, torch.bfloat16),     # k > 24 -> default R = 64
+    (20000, 512, 8, 20, 0, torch.bfloat16),    # small-batch kernel, many tiles per workgroup
+    (5000, 1024, 16, 10, 0, torch.bfloat16),   # small-batch kernel, longest supported activation
+    (3000, 960, 3, 5, 0, torch.float32),       # small-batch kernel, fp32 cache, d not a multiple of 64
+    (3000, 1100, 3, 5, 0, torch.bfloat16),     # d too long for the small-batch kernel -> tiled kernel
 ])
 def test_shapes_against_oracle(n, d, b, k, r, dtype):
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
