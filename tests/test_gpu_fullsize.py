@@ -1,0 +1,114 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times:
+the HIP path runs the whole batch; the oracle checks a seeded sample of the queries one by
+one, and properties that hold at any size are checked on every output row."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import freeze_oracle as fo
+from paper_2002_02645_amd import binding, synth
+from tests import parity
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(400)]
+
+TIGHT = 1e-5
+
+
+def _host_entries(t):
+    return synth.bf16_bits(t) if t.dtype == torch.bfloat16 else t.detach().cpu().numpy()
+
+
+def _structural_checks(out, n, k, thr, num_classes):
+    idx = out["idx"].cpu().numpy()
+    dist = out["dist"].cpu().numpy()
+    assert idx.min() >= 0 and idx.max() < n
+    srt = np.sort(idx, axis=1)
+    assert (srt[:, 1:] != srt[:, :-1]).all(), "a neighbour is reported twice"
+    assert (np.diff(dist, axis=1) >= 0).all(), "distances not ascending"
+    assert (dist >= 0).all()
+    votes = out["votes"].cpu().numpy()
+    hit = out["hit"].cpu().numpy()
+    lab = out["label"].cpu().numpy()
+    assert votes.min() >= 1 and votes.max() <= k
+    assert np.array_equal(hit, (votes >= thr).astype(np.uint8))
+    assert lab.min() >= 0 and lab.max() < num_classes
+
+
+def _sample_against_oracle(wl_name, sample):
+    wl = synth.WORKLOADS[wl_name]
+    spec = wl.layers[0]
+    data = synth.make_workload(wl, device="cuda")
+    L = data.layers[0]
+    q = data.queries[0]
+    k, thr, r = wl.k, wl.vote_thresholds[0], wl.rescore_r
+    fc = binding.FreezeCache(1)
+    try:
+        fc.build_layer(0, L.entries, L.labels, spec.num_classes)
+        out = fc.lookup(0, q, k, thr, r)
+        torch.cuda.synchronize()
+        _structural_checks(out, spec.n, k, thr, spec.num_classes)
+        g = torch.Generator().manual_seed(wl.seed + 4242)
+        pick = torch.randperm(wl.batch, generator=g)[:min(sample, wl.batch)].sort().values
+        got = {key: v[pick.cuda()].cpu().numpy() for key, v in out.items()}
+        # the clean synthetic classes are separable: every neighbour shares the query's class
+        if spec.label_flip_p == 0.0:
+            assert np.array_equal(out["label"].cpu().numpy(), data.query_classes.cpu().numpy())
+    finally:
+        fc.close()
+    e_h, l_h = _host_entries(L.entries), L.labels.cpu().numpy()
+    q_h = q[pick.cuda()].cpu().numpy()
+    ref = parity.oracle_reference(q_h, e_h, l_h, spec.num_classes, k, thr)
+    near = parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, spec.num_classes, k, thr, rel=TIGHT, dist_rel=TIGHT)
+    parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, spec.num_classes, k, thr)
+    return near
+
+
+def test_c2_batched_full_size_sample():
+    _sample_against_oracle("c2_batched", 96)
+
+
+def test_c5_latency_batch1_and_batch8_full_size():
+    _sample_against_oracle("c5_latency_b1", 1)
+    _sample_against_oracle("c5_latency_b8", 8)
+
+
+def test_c3_wide_full_size_sample():
+    _sample_against_oracle("c3_wide", 16)
+
+
+@pytest.mark.parametrize("name", ["c4_cascade_noisy", "c4_cascade"])
+def test_c4_cascade_full_size_sample(name):
+    wl = synth.WORKLOADS[name]
+    data = synth.make_workload(wl, device="cuda")
+    nl = len(wl.layers)
+    fc = binding.FreezeCache(nl)
+    try:
+        for l, L in enumerate(data.layers):
+            fc.build_layer(l, L.entries, L.labels, L.spec.num_classes)
+        out = fc.lookup_cascade(list(range(nl)), data.queries, wl.k, list(wl.vote_thresholds), wl.rescore_r)
+        torch.cuda.synchronize()
+        got = {key: v.cpu().numpy() for key, v in out.items()}
+    finally:
+        fc.close()
+    b = wl.batch
+    # structure: every request either froze at exactly one layer or fell through
+    assert got["hits_per_layer"].sum() + (got["exit_layer"] == -1).sum() == b
+    for l in range(nl):
+        assert got["hits_per_layer"][l] == (got["exit_layer"] == l).sum()
+    assert ((got["label"] == -1) == (got["exit_layer"] == -1)).all()
+    if name == "c4_cascade":
+        # separable classes, clean labels: every request freezes at the first layer with its own class
+        assert (got["exit_layer"] == 0).all()
+        assert np.array_equal(got["label"], data.query_classes.cpu().numpy())
+    else:
+        assert len(set(got["exit_layer"].tolist())) >= 3
+    # a seeded sample of requests through the oracle's cascade
+    sample = 24 if name == "c4_cascade_noisy" else 16
+    g = torch.Generator().manual_seed(wl.seed + 4242)
+    pick = torch.randperm(b, generator=g)[:sample].sort().values
+    qs = [q[pick.cuda()].cpu().numpy() for q in data.queries]
+    exp_l, exp_x, _, _ = fo.cascade(qs, [_host_entries(L.entries) for L in data.layers],
+                                    [L.labels.cpu().numpy() for L in data.layers],
+                                    [L.spec.num_classes for L in data.layers], wl.k, wl.vote_thresholds)
+    assert np.array_equal(got["exit_layer"][pick.numpy()], exp_x)
+    assert np.array_equal(got["label"][pick.numpy()], exp_l)
