@@ -33,6 +33,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c2_batched")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (profiling runs)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="queries in the oracle sample (0 = per workload)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (one-GPU boxes; the path has no multi-GPU part); "
@@ -163,6 +165,13 @@ def main() -> int:
         result["config"]["parity_sample"] = {"queries": int(sample), "identical": int((~differ).sum()),
                                              "differ_outside_near_tie": unexplained,
                                              "hit_equal": int((got_hit == ref["hit"]).sum())}
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        result["config"]["copy_calibration_bytes"] = 1 << 30
     fc.close()
     print(json.dumps(result))
     return 0

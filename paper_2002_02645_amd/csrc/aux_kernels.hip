@@ -142,86 +142,38 @@ hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int
 //  4. vote: occurrences m of each label among the k, winner = most occurrences, smaller
 //     label id on equal counts; hit iff m >= vote_threshold (Sec. 2.1 / Sec. 3).
 // ---------------------------------------------------------------------------------------
-struct FinishKernelArgs {
-    FinishArgs a;
-    int sort_n;   // power of two >= n_splits * r
-};
-
-__global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
+// Exact re-scoring by one wave: candidates c0 .. c0+G-1 (c0 = wave * G, stepping 4 G), the 64
+// lanes striding over the activation 8 elements at a time; dist = sum (q_i - c_i)^2 in fp32,
+// per-lane partial sums in index order, then a butterfly over the lanes (fixed order).
+template <int G>
+__device__ __forceinline__ void rescore_wave(const FinishArgs &a, const float *qrow, const int32_t *idx_s,
+                                             float *dist_s, int r, int wave, int lane)
 {
-    const FinishArgs &a = fa.a;
-    extern __shared__ uint64_t ent[];   // sort_n entries (dynamic: small merges keep occupancy high)
-    __shared__ float red[4][8];
-    __shared__ float dist_s[kMaxRescore];
-    __shared__ int32_t idx_s[kMaxRescore];
-    __shared__ int32_t lab_s[kMaxK];
-    __shared__ int32_t cnt_s[kMaxK];
-
-    const int nq = a.count ? *a.count : a.b;
-    const int q = blockIdx.x;
-    if (q >= nq) return;
-    const int tid = threadIdx.x;
-    const int r = a.r;
-
-    // 1. merge the per-split lists
-    const int total = a.n_splits * r;
-    const uint64_t *src = a.part + (size_t)q * total;
-    for (int i = tid; i < fa.sort_n; i += 256) ent[i] = (i < total) ? src[i] : kSentinel;
-    __syncthreads();
-    {
-        for (int size = 2; size <= fa.sort_n; size <<= 1) {
-            for (int stride = size >> 1; stride > 0; stride >>= 1) {
-                for (int i = tid; i < (fa.sort_n >> 1); i += 256) {
-                    const int lo = ((i / stride) * stride * 2) + (i % stride);
-                    const int hi = lo + stride;
-                    const bool up = ((lo & size) == 0);
-                    const uint64_t x = ent[lo], y = ent[hi];
-                    if ((x > y) == up) {
-                        ent[lo] = y;
-                        ent[hi] = x;
-                    }
-                }
-                __syncthreads();
-            }
-        }
-    }
-    if (tid < r) {
-        // With finite inputs every one of the first r entries is a real cache row.  Non-finite
-        // inputs (outside the contract) can leave "no entry" markers here: map them to row 0 so
-        // that nothing is read out of bounds.
-        const uint32_t ci = (uint32_t)(ent[tid] & 0xffffffffu);
-        idx_s[tid] = ci < (uint32_t)a.n ? (int32_t)ci : 0;
-    }
-    __syncthreads();
-
-    // 2. exact fp32 re-scoring, 8 candidates at a time
-    const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
     const bool vec = (a.d % 8) == 0;
-    for (int r0 = 0; r0 < r; r0 += 8) {
-        float acc[8];
+    for (int c0 = wave * G; c0 < r; c0 += 4 * G) {
+        float acc[G];
+        int64_t cand[G];
+        const uint4 *cand_tile[G];   // tile base of the candidate's row in the tiled bf16 cache
+        int cand_rit[G];             // its row inside the tile
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-        int64_t cand[8];
-        const uint4 *cand_tile[8];   // tile base of the candidate's row in the tiled bf16 cache
-        int cand_rit[8];             // its row inside the tile
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            cand[j] = idx_s[(r0 + j < r) ? r0 + j : r - 1];
+        for (int j = 0; j < G; ++j) {
+            acc[j] = 0.f;
+            cand[j] = idx_s[(c0 + j < r) ? c0 + j : r - 1];
             cand_tile[j] = reinterpret_cast<const uint4 *>(a.c_bf + (cand[j] / kTileN) * kTileN * a.d_pad);
             cand_rit[j] = (int)(cand[j] % kTileN);
         }
         if (vec) {
-            for (int64_t i = (int64_t)tid * 8; i < a.d; i += 256 * 8) {
+            for (int64_t i = (int64_t)lane * 8; i < a.d; i += 64 * 8) {
                 const f32x4 q0 = *reinterpret_cast<const f32x4 *>(qrow + i);
                 const f32x4 q1 = *reinterpret_cast<const f32x4 *>(qrow + i + 4);
                 const float qv[8] = {q0[0], q0[1], q0[2], q0[3], q1[0], q1[1], q1[2], q1[3]};
                 if (a.c_f32) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
+                    for (int j = 0; j < G; ++j) {
                         const float *c = a.c_f32 + cand[j] * a.d_pad + i;
-                        const f32x4 c0 = *reinterpret_cast<const f32x4 *>(c);
-                        const f32x4 c1 = *reinterpret_cast<const f32x4 *>(c + 4);
-                        const float cv[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+                        const f32x4 c0v = *reinterpret_cast<const f32x4 *>(c);
+                        const f32x4 c1v = *reinterpret_cast<const f32x4 *>(c + 4);
+                        const float cv[8] = {c0v[0], c0v[1], c0v[2], c0v[3], c1v[0], c1v[1], c1v[2], c1v[3]};
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
                             const float df = qv[e] - cv[e];
@@ -230,7 +182,7 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
                     }
                 } else {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
+                    for (int j = 0; j < G; ++j) {
                         const uint4 cb = cand_tile[j][tiled_chunk_offset(cand_rit[j], i >> 3, kTileN)];
                         const uint32_t wv[4] = {cb.x, cb.y, cb.z, cb.w};
 #pragma unroll
@@ -246,10 +198,10 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
                 }
             }
         } else {
-            for (int64_t i = tid; i < a.d; i += 256) {
+            for (int64_t i = lane; i < a.d; i += 64) {
                 const float qv = qrow[i];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
+                for (int j = 0; j < G; ++j) {
                     float cv;
                     if (a.c_f32) {
                         cv = a.c_f32[cand[j] * a.d_pad + i];
@@ -263,7 +215,68 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
                 }
             }
         }
-        // block reduction in a fixed order
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            float v = acc[j];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == 0 && c0 + j < r) dist_s[c0 + j] = v;
+        }
+    }
+}
+
+// Exact re-scoring by the whole block, 8 candidates at a time (long activations: the query row
+// is read once per 8 candidates and every thread keeps 10 loads in flight).  Same arithmetic as
+// rescore_wave; partial sums are combined wave by wave in a fixed order.
+__device__ __forceinline__ void rescore_block(const FinishArgs &a, const float *qrow, const int32_t *idx_s,
+                                              float *dist_s, float (*red)[8], int r, int tid)
+{
+    for (int r0 = 0; r0 < r; r0 += 8) {
+        float acc[8];
+        const uint4 *cand_tile[8];
+        int cand_rit[8];
+        int64_t cand[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            acc[j] = 0.f;
+            cand[j] = idx_s[(r0 + j < r) ? r0 + j : r - 1];
+            cand_tile[j] = reinterpret_cast<const uint4 *>(a.c_bf + (cand[j] / kTileN) * kTileN * a.d_pad);
+            cand_rit[j] = (int)(cand[j] % kTileN);
+        }
+        for (int64_t i = (int64_t)tid * 8; i < a.d; i += 256 * 8) {
+            const f32x4 q0 = *reinterpret_cast<const f32x4 *>(qrow + i);
+            const f32x4 q1 = *reinterpret_cast<const f32x4 *>(qrow + i + 4);
+            const float qv[8] = {q0[0], q0[1], q0[2], q0[3], q1[0], q1[1], q1[2], q1[3]};
+            if (a.c_f32) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float *c = a.c_f32 + cand[j] * a.d_pad + i;
+                    const f32x4 c0v = *reinterpret_cast<const f32x4 *>(c);
+                    const f32x4 c1v = *reinterpret_cast<const f32x4 *>(c + 4);
+                    const float cv[8] = {c0v[0], c0v[1], c0v[2], c0v[3], c1v[0], c1v[1], c1v[2], c1v[3]};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float df = qv[e] - cv[e];
+                        acc[j] = __builtin_fmaf(df, df, acc[j]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint4 cb = cand_tile[j][tiled_chunk_offset(cand_rit[j], i >> 3, kTileN)];
+                    const uint32_t wv[4] = {cb.x, cb.y, cb.z, cb.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float c_lo = __uint_as_float(wv[e] << 16);
+                        const float c_hi = __uint_as_float(wv[e] & 0xffff0000u);
+                        const float d0 = qv[2 * e] - c_lo;
+                        acc[j] = __builtin_fmaf(d0, d0, acc[j]);
+                        const float d1 = qv[2 * e + 1] - c_hi;
+                        acc[j] = __builtin_fmaf(d1, d1, acc[j]);
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             float v = acc[j];
@@ -275,6 +288,75 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
         if (tid < 8 && r0 + tid < r) dist_s[r0 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
         __syncthreads();
     }
+}
+
+struct FinishKernelArgs {
+    FinishArgs a;
+    int sort_cap;   // power of two >= the largest number of entries gathered per query (LDS allocation)
+};
+
+__global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
+{
+    const FinishArgs &a = fa.a;
+    extern __shared__ uint64_t ent[];   // sort_cap entries (dynamic: small merges keep occupancy high)
+    __shared__ float red[4][8];
+    __shared__ float dist_s[kMaxRescore];
+    __shared__ int32_t idx_s[kMaxRescore];
+    __shared__ int32_t lab_s[kMaxK];
+    __shared__ int32_t cnt_s[kMaxK];
+
+    const int nq = a.count ? *a.count : a.b;
+    const int q = blockIdx.x;
+    if (q >= nq) return;
+    const int tid = threadIdx.x;
+    const int r = a.r;
+
+    // 1. merge the per-split lists (or sort the query's candidate list)
+    int total = a.n_splits * r, stride = total;
+    if (a.part_count) {
+        stride = a.part_stride;
+        total = a.part_count[q] < stride ? a.part_count[q] : stride;
+    }
+    int sort_n = 2;
+    while (sort_n < total) sort_n <<= 1;   // <= fa.sort_cap, the LDS allocation
+    const uint64_t *src = a.part + (size_t)q * stride;
+    for (int i = tid; i < sort_n; i += 256) ent[i] = (i < total) ? src[i] : kSentinel;
+    __syncthreads();
+    for (int size = 2; size <= sort_n; size <<= 1) {
+        for (int stride2 = size >> 1; stride2 > 0; stride2 >>= 1) {
+            for (int i = tid; i < (sort_n >> 1); i += 256) {
+                const int lo = ((i & ~(stride2 - 1)) << 1) | (i & (stride2 - 1));   // stride2 is a power of two
+                const int hi = lo + stride2;
+                const bool up = ((lo & size) == 0);
+                const uint64_t x = ent[lo], y = ent[hi];
+                if ((x > y) == up) {
+                    ent[lo] = y;
+                    ent[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (tid < r) {
+        // With finite inputs every one of the first r entries is a real cache row.  Non-finite
+        // inputs (outside the contract) can leave "no entry" markers here: map them to row 0 so
+        // that nothing is read out of bounds.
+        const uint32_t ci = (uint32_t)(ent[tid] & 0xffffffffu);
+        idx_s[tid] = ci < (uint32_t)a.n ? (int32_t)ci : 0;
+    }
+    __syncthreads();
+
+    // 2. exact fp32 re-scoring: each wave takes a group of candidates and needs no block barrier
+    const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
+    if (a.d >= 4096 && a.d % 8 == 0)
+        rescore_block(a, qrow, idx_s, dist_s, red, r, tid);
+    else if (r <= 16)
+        rescore_wave<4>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
+    else if (r <= 32)
+        rescore_wave<8>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
+    else
+        rescore_wave<16>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
+    __syncthreads();
 
     // 3. final order (dist, index) and the first k
     if (tid < r) {
@@ -321,11 +403,11 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
 
 hipError_t launch_finish(const FinishArgs &a, hipStream_t s)
 {
-    const int total = a.n_splits * a.r;
+    const int total = a.part_count ? a.part_stride : a.n_splits * a.r;
     if (total > kMaxMergeEntries || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r) return hipErrorInvalidValue;
     FinishKernelArgs fa{a, 2};
-    while (fa.sort_n < total) fa.sort_n <<= 1;
-    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)a.b), dim3(256), (size_t)fa.sort_n * sizeof(uint64_t), s, fa);
+    while (fa.sort_cap < total) fa.sort_cap <<= 1;
+    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)a.b), dim3(256), (size_t)fa.sort_cap * sizeof(uint64_t), s, fa);
     return hipGetLastError();
 }
 

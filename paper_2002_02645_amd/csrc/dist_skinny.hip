@@ -1,40 +1,44 @@
 // Distance pass for small batches (at most 16 queries): the bandwidth-bound path.
 //
 // With a handful of queries the look-up is a matrix-vector product: every cache entry is
-// read once and used for a few dot products, so the kernel is built around streaming the
-// cache from HBM exactly once with many bytes in flight, not around the matrix cores' rate.
-// It computes the same ranking key as the batched kernel,
-//     key(b, n) = |c_n|^2 - 2 * sum_i Q_bf[b,i] * C_bf[n,i]      (bf16 x bf16 -> fp32 MFMA),
-// and keeps, per query and per range of cache tiles, the R entries with the smallest
-// (key, index); the finishing kernel re-scores them exactly in fp32.
+// read once and used for a few dot products, so this path is built around streaming the
+// cache from HBM exactly once with many bytes in flight, not around the matrix cores' rate,
+// and nothing in the streaming kernel depends on the data.
+//
+//  1. dist_skinny_kernel streams the cache and writes, per query b and entry n, the ranking key
+//         key(b, n) = |c_n|^2 - 2 * sum_i Q_bf[b,i] * C_bf[n,i]     (bf16 x bf16 -> fp32 MFMA)
+//     (4 bytes per entry and query against 2*d bytes read), and per block of 32 entries the
+//     smallest (key, index) pair of the block.
+//  2. skinny_threshold_kernel finds, per query, the R-th smallest block minimum T.  R blocks
+//     hold an entry <= T, so the R-th smallest entry overall is <= T; and every entry <= T
+//     lies in one of exactly those R blocks, so at most 32 R entries pass.
+//  3. skinny_filter_kernel collects the entries with (key, index) <= T into a candidate list.
+// The finishing kernel sorts the candidates, keeps the best R and re-scores them in fp32.
 //
 // Paper: Sec. 3 (k nearest neighbours of the layer output), Sec. 5 "Cache lookup
 // performance" (look-up latency decides whether freezing pays off).
 //
-// Layout of the work: one workgroup per range of 256-entry cache tiles.  The prepared
-// queries (a 32-row block for the matrix cores, rows past the batch zero) stay resident in
-// LDS for the whole kernel.  The cache, stored in the tiled
-// layout ([tile][k-block][row][32 elements]), is one contiguous stream per workgroup: it is
-// copied verbatim into a ring of NS 16 KiB LDS stages with LDS-direct loads, NS-1 stages in
-// flight, and the ring keeps running across tile boundaries so the epilogue of one tile
-// overlaps the loads of the next.  Each of the 8 waves owns 32 of the tile's 256 entries:
-// one 32x32x16 MFMA per 16 elements of k.  The tile's 256 squared norms travel the same way
-// (one LDS-direct load per wave and tile), so no ordinary load ever drains the ring.  After
-// the last k-block of a tile the keys go to a 16 x 256 slab in LDS; thread t (< batch) scans
-// row t and inserts survivors into its top-R list.
+// Streaming kernel: one workgroup per range of 256-entry cache tiles.  The prepared queries
+// (a 32-row block for the matrix cores, rows past the batch zero) stay resident in LDS.  The
+// cache, stored in the tiled layout ([tile][k-block][row][32 elements]), is one contiguous
+// stream per workgroup: it is copied verbatim into a ring of NS 16 KiB LDS stages with
+// LDS-direct loads, NS-1 stages in flight, and the ring keeps running across tile boundaries.
+// Each of the 8 waves owns 32 of the tile's 256 entries: one 32x32x16 MFMA per 16 elements of
+// k.  The tile's squared norms travel the same way (one LDS-direct load per wave and tile), so
+// no ordinary load ever drains the ring.
 #include "freeze_internal.h"
 
 namespace fz {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
 namespace {
 
 __device__ __forceinline__ void load16_global_to_lds(const void *g, uint32_t lds_byte_addr)
 {
+    // M0 carries the wave-uniform LDS destination; lane i lands at +16*i.
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(g)
                  : "memory", "m0");
 }
@@ -52,34 +56,29 @@ __device__ __forceinline__ uint32_t ordered_bits(float x)
     uint32_t u = __float_as_uint(x);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
-__device__ __forceinline__ float from_ordered_bits(uint32_t u)
-{
-    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
-}
 
 constexpr int kMmaRows = 32;               // rows of the query block fed to the matrix cores
-constexpr int kRows = kSkinnyRows;         // rows that can hold a query (the rest are zero)
 constexpr int kStage = kTileN * kKB * 2;   // 16 KiB: one k-block of one cache tile
-constexpr int kSlab = kRows * kTileN * 4;  // 16 KiB
-constexpr int kTop = kMaxRescore * kRows * 8;   // 8 KiB
 constexpr int kNormBuf = 2 * 8 * 256;      // 4 KiB: per tile parity and wave, 64 floats
-static_assert(kRows <= 16, "slab rows are the first two row groups of the MFMA output");
+static_assert(kSkinnyRows <= 16, "queries occupy the first two row groups of the MFMA output");
 
 template <int DMAX_, int NS_>
 struct SkinnyCfg {
     static constexpr int DMAX = DMAX_, NS = NS_;
     static constexpr int A_BYTES = kMmaRows * DMAX * 2;
-    static constexpr int LDS_BYTES = A_BYTES + kSlab + kTop + kNormBuf + NS * kStage;
+    static constexpr int LDS_BYTES = A_BYTES + kNormBuf + NS * kStage;
     static_assert(LDS_BYTES <= 163840, "LDS budget");
-    static_assert(NS >= 2 && NS <= 6, "stages");
+    static_assert(NS >= 2 && NS <= 8, "stages");
 };
 
 struct SkinnyArgs {
     const uint16_t *q_bf;   // 32 x d_pad (rows >= b zero), tiled layout with 32-row tiles
     const uint16_t *c_bf;
     const float *norm;
-    uint64_t *part;         // [b, n_splits, r]
-    int b, n, d_pad, n_tiles, n_splits, r;
+    float *keys;            // [b, n_pad]
+    uint64_t *bmin;         // [b, n_pad / 32] smallest (ordered key, index) of each block of 32 entries
+    int b, d_pad, n_tiles, n_splits;
+    int64_t n_pad;
 };
 
 template <class C>
@@ -87,29 +86,18 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[C::LDS_BYTES];
     const bf16x8 *smem16 = reinterpret_cast<const bf16x8 *>(smem);
-    float *slab = reinterpret_cast<float *>(smem + C::A_BYTES);                 // [16][256]
-    uint64_t *top = reinterpret_cast<uint64_t *>(smem + C::A_BYTES + kSlab);    // [RMAX][16]
-    constexpr int NORMS = C::A_BYTES + kSlab + kTop;                            // byte offset of the norm buffers
-    const float *normbuf = reinterpret_cast<const float *>(smem + NORMS);       // [2][8 waves][64]
-    constexpr int RING = NORMS + kNormBuf;                                      // byte offset of the stage ring
+    constexpr int NORMS = C::A_BYTES;                                       // byte offset of the norm buffers
+    const float *normbuf = reinterpret_cast<const float *>(smem + NORMS);   // [2][8 waves][64]
+    constexpr int RING = NORMS + kNormBuf;                                  // byte offset of the stage ring
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int sp = blockIdx.x;
     const int nt0 = (int)(((int64_t)sp * p.n_tiles) / p.n_splits);
     const int nt1 = (int)(((int64_t)(sp + 1) * p.n_tiles) / p.n_splits);
-    const int r = p.r;
     const int kblocks = p.d_pad / kKB;                 // k-blocks per tile
     const int total = (nt1 - nt0) * kblocks;           // stages this workgroup streams
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
-
-    uint64_t curmax = kSentinel;
-    int maxpos = 0;
-    float tau = __builtin_inff();
-    if (tid < kRows) {
-#pragma unroll
-        for (int i = 0; i < kMaxRescore; ++i) top[i * kRows + tid] = kSentinel;
-    }
 
     // the cache stream of this workgroup is contiguous: tiles nt0..nt1-1, each kblocks * 16 KiB
     const unsigned char *stream = reinterpret_cast<const unsigned char *>(p.c_bf) +
@@ -157,13 +145,15 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
         case 1: wait_global_loads_le<1 * LPS>(); break;
         case 2: wait_global_loads_le<2 * LPS>(); break;
         case 3: wait_global_loads_le<3 * LPS>(); break;
-        default: wait_global_loads_le<4 * LPS>(); break;
+        case 4: wait_global_loads_le<4 * LPS>(); break;
+        case 5: wait_global_loads_le<5 * LPS>(); break;
+        default: wait_global_loads_le<6 * LPS>(); break;
         }
         __syncthreads();
         // The norms of the NEXT tile are requested at this tile's first step, before this step's
         // stage loads: they are older than every stage still in flight when they are read, and an
-        // extra outstanding load only makes the counted waits above stricter.  (Their buffer was
-        // last read at the end of the tile before this one: a barrier ago.)
+        // extra outstanding load only makes the counted waits above stricter.  Each wave reads and
+        // refills only its own part of the buffer.
         if (kb == 0 && nt + 1 < nt1) issue_norms(nt + 1);
         if (gs + C::NS - 1 < total) issue((slot + C::NS - 1) % C::NS, gs + C::NS - 1);
 
@@ -178,96 +168,202 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
         slot = (slot + 1 == C::NS) ? 0 : slot + 1;
         if (++kb < kblocks) continue;
 
-        // ---- tile finished: fold its 256 keys per query into the top-R lists ----
+        // ---- tile finished: emit its keys and block minima ----
         kb = 0;
         const int n0 = nt * kTileN;
+        // With fewer k-blocks than stages in flight the norm load may still be outstanding.
+        if (kblocks < C::NS) wait_global_loads_le<0>();
+        const int col = w * 32 + (lane & 31);
+        const float nrm = normbuf[((nt & 1) * 8 + w) * 64 + (lane & 31)];
         ++nt;
-        {
-            // With fewer k-blocks than stages in flight the norm load may still be outstanding.
-            if (kblocks < C::NS) wait_global_loads_le<0>();
-            const int col = w * 32 + (lane & 31);
-            const float nrm = normbuf[(((nt - 1) & 1) * 8 + w) * 64 + (lane & 31)];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {   // accumulator rows 0..15: the rows that can hold a query
-                const int row = (e >> 2) * 8 + g * 4 + (e & 3);
-                slab[row * kTileN + ((((col >> 2) ^ row) & 63) << 2) + (col & 3)] = __builtin_fmaf(-2.f, acc[e], nrm);
-            }
+        for (int e = 0; e < 8; ++e) {   // accumulator rows 0..15: the rows that can hold a query
+            const int row_lo = (e >> 2) * 8 + (e & 3);   // row held by lanes 0..31; lanes 32..63 hold row_lo + 4
+            if (row_lo < p.b) {                           // uniform
+                const int row = row_lo + g * 4;
+                const float key = __builtin_fmaf(-2.f, acc[e], nrm);
+                const bool live = row < p.b;
+                if (live) p.keys[(size_t)row * p.n_pad + n0 + col] = key;
+                // block minimum over the 32 lanes of each half-wave (xor offsets < 32 stay inside it)
+                const uint32_t ob = ordered_bits(key);
+                uint32_t mn = ob;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-        }
-        __syncthreads();
-        if (tid < p.b) {
-            const int t = tid;
-            const f32x4 *srow = reinterpret_cast<const f32x4 *>(slab + t * kTileN);
-            const int lim = p.n - n0;   // columns < lim are real entries
-#pragma unroll 1
-            for (int m = 0; m < 4; ++m) {
-                uint64_t mk = 0;
-#pragma unroll 4
-                for (int cgi = 0; cgi < 16; ++cgi) {
-                    const int cg = m * 16 + cgi;
-                    const f32x4 v = srow[(cg ^ t) & 63];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const bool pass = (v[e] <= tau) && (cg * 4 + e < lim);
-                        mk |= (uint64_t)pass << (cgi * 4 + e);
-                    }
+                for (int off = 16; off >= 1; off >>= 1) {
+                    const uint32_t o = (uint32_t)__shfl_xor((int)mn, off, 64);
+                    mn = o < mn ? o : mn;
                 }
-                while (mk) {
-                    const int col = m * 64 + __builtin_ctzll(mk);
-                    mk &= mk - 1;
-                    const float key = slab[t * kTileN + ((((col >> 2) ^ t) & 63) << 2) + (col & 3)];
-                    const uint64_t ent = ((uint64_t)ordered_bits(key) << 32) | (uint32_t)(n0 + col);
-                    if (ent < curmax) {
-                        top[maxpos * kRows + t] = ent;
-                        curmax = 0;
-                        for (int i = 0; i < r; ++i) {
-                            const uint64_t v = top[i * kRows + t];
-                            if (v >= curmax) { curmax = v; maxpos = i; }
-                        }
-                        tau = (curmax == kSentinel) ? __builtin_inff() : from_ordered_bits((uint32_t)(curmax >> 32));
-                    }
-                }
+                const uint64_t eq = __ballot(ob == mn);
+                const uint32_t half = (uint32_t)(g ? (eq >> 32) : (eq & 0xffffffffull));
+                const int first = __builtin_ctz(half);   // lowest column holding the minimum
+                if (live && (lane & 31) == 0)
+                    p.bmin[(size_t)row * (p.n_pad / 32) + (size_t)(n0 / 32) + w] =
+                        ((uint64_t)mn << 32) | (uint32_t)(n0 + w * 32 + first);
             }
         }
-        // the next slab write happens after at least one more __syncthreads (next stage's)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
     }
-    if (tid < p.b) {
-        uint64_t *dst = p.part + ((size_t)tid * p.n_splits + sp) * r;
-        for (int i = 0; i < r; ++i) dst[i] = top[i * kRows + tid];
+}
+
+// ---------------------------------------------------------------------------------------
+// Per query: T = the R-th smallest of the NB block minima (pairs (ordered key, index), all
+// distinct).  One workgroup of 1024 threads per query, two rounds of the same argument as in
+// the file header: thread t holds up to V values and their minimum m_t; the R-th smallest m_t
+// (T1) bounds the answer from above, and at most V * R values are <= T1; those are gathered
+// into LDS and sorted, and the R-th of them is T.  Sorting is bitonic, in LDS.
+// ---------------------------------------------------------------------------------------
+constexpr int kThrThreads = 1024;
+constexpr int kThrList = 4096;   // capacity of the gathered list; the launcher checks V * R <= kThrList
+
+__device__ void bitonic_sort_lds(uint64_t *a, int n_pow2, int tid, int nthreads)
+{
+    for (int size = 2; size <= n_pow2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < (n_pow2 >> 1); i += nthreads) {
+                const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));   // stride is a power of two
+                const int hi = lo + stride;
+                const bool up = ((lo & size) == 0);
+                const uint64_t x = a[lo], y = a[hi];
+                if ((x > y) == up) {
+                    a[lo] = y;
+                    a[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThrThreads) void skinny_threshold_kernel(const uint64_t *bmin, int64_t nb, int r_sel,
+                                                                      uint64_t *tau, int32_t *cand_count)
+{
+    __shared__ uint64_t list[kThrList];
+    __shared__ int list_n;
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const uint64_t *src = bmin + (size_t)q * nb;
+    if (tid == 0) {
+        cand_count[q] = 0;
+        list_n = 0;
+    }
+    if (r_sel >= nb) {   // fewer blocks than wanted entries: everything passes
+        if (tid == 0) tau[q] = kSentinel;
+        return;
+    }
+    // round 1: per-thread minima, sorted; T1 = the r_sel-th smallest of them (r_sel <= 64 < 1024)
+    uint64_t m = kSentinel;
+    for (int64_t j = tid; j < nb; j += kThrThreads) {
+        const uint64_t v = src[j];
+        m = v < m ? v : m;
+    }
+    list[tid] = m;
+    __syncthreads();
+    bitonic_sort_lds(list, kThrThreads, tid, kThrThreads);
+    const uint64_t t1 = list[r_sel - 1];
+    __syncthreads();
+    // round 2: gather the values <= T1 (at least r_sel, at most V * r_sel of them), sort, take the r_sel-th
+    for (int64_t j = tid; j < nb; j += kThrThreads) {
+        const uint64_t v = src[j];
+        if (v <= t1) {
+            const int pos = atomicAdd(&list_n, 1);
+            if (pos < kThrList) list[pos] = v;
+        }
+    }
+    __syncthreads();
+    const int cnt = list_n < kThrList ? list_n : kThrList;
+    int n2 = 2;
+    while (n2 < cnt) n2 <<= 1;
+    for (int i = cnt + tid; i < n2; i += kThrThreads) list[i] = kSentinel;
+    __syncthreads();
+    bitonic_sort_lds(list, n2, tid, kThrThreads);
+    if (tid == 0) tau[q] = list[r_sel - 1];
+}
+
+// ---------------------------------------------------------------------------------------
+// Collect, per query, the entries whose (ordered key, index) pair is <= T.  Grid: (chunks, b).
+// At most 32 * R entries pass (see the file header); `cap` >= that bound.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void skinny_filter_kernel(const float *keys, int64_t n_pad, int n, const uint64_t *tau,
+                                                            uint64_t *cand, int32_t *cand_count, int cap)
+{
+    const int q = blockIdx.y;
+    const uint64_t t = tau[q];
+    const float *kq = keys + (size_t)q * n_pad;
+    const int64_t per = (n_pad / 4 + gridDim.x - 1) / gridDim.x;   // float4 groups per block
+    const int64_t lo = (int64_t)blockIdx.x * per;
+    const int64_t hi = (lo + per < n_pad / 4) ? lo + per : n_pad / 4;
+    for (int64_t j = lo + threadIdx.x; j < hi; j += 256) {
+        const float4 v = reinterpret_cast<const float4 *>(kq)[j];
+        const float kv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t idx = j * 4 + e;
+            const uint64_t pr = ((uint64_t)ordered_bits(kv[e]) << 32) | (uint32_t)idx;
+            if (pr <= t && idx < n) {
+                const int pos = atomicAdd(&cand_count[q], 1);
+                if (pos < cap) cand[(size_t)q * cap + pos] = pr;
+            }
+        }
     }
 }
 
 }  // namespace
 
-int plan_skinny_splits(int64_t n, int r, int num_cus)
+bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r)
+{
+    const int64_t nb = n_pad / 32;
+    return b >= 1 && b <= kSkinnyRows && d_pad <= kSkinnyMaxD && ((nb + kThrThreads - 1) / kThrThreads) * r <= kThrList;
+}
+
+int plan_skinny_splits(int64_t n, int num_cus)
 {
     const int n_tiles = (int)((n + kTileN - 1) / kTileN);
-    int s = num_cus < n_tiles ? num_cus : n_tiles;
-    if (s > kMaxMergeEntries / r) s = kMaxMergeEntries / r;
+    const int s = num_cus < n_tiles ? num_cus : n_tiles;
     return s < 1 ? 1 : s;
 }
 
-hipError_t launch_dist_skinny(const DistArgs &a, int n_splits, int r, hipStream_t s)
+size_t skinny_workspace_bytes(int64_t n_pad, int r, size_t align)
 {
-    if (a.d_pad > kSkinnyMaxD || a.d_pad % kPadD != 0 || r < 1 || r > kMaxRescore || a.count != nullptr ||
-        a.b > kSkinnyRows)
+    auto up = [&](size_t x) { return (x + align - 1) / align * align; };
+    const size_t b = kSkinnyRows;
+    return up(b * (size_t)n_pad * 4) + up(b * (size_t)(n_pad / 32) * 8) + up(b * 8) + up(b * 4) +
+           up(b * (size_t)(32 * r) * 8);
+}
+
+hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
+{
+    if (a.d_pad > kSkinnyMaxD || a.d_pad % kPadD != 0 || a.r < 1 || a.r > kMaxRescore || a.b < 1 || a.b > kSkinnyRows)
         return hipErrorInvalidValue;
     SkinnyArgs k{};
     k.q_bf = a.q_bf;
     k.c_bf = a.c_bf;
     k.norm = a.norm;
-    k.part = a.part;
+    k.keys = a.keys;
+    k.bmin = a.bmin;
     k.b = a.b;
-    k.n = a.n;
     k.d_pad = a.d_pad;
-    k.n_tiles = (a.n + kTileN - 1) / kTileN;
-    k.n_splits = n_splits;
-    k.r = r;
+    k.n_pad = a.n_pad;
+    k.n_tiles = (int)(a.n_pad / kTileN);
+    k.n_splits = a.n_splits;
     if (a.d_pad <= 512)
-        hipLaunchKernelGGL((dist_skinny_kernel<SkinnyCfg<512, 6>>), dim3(n_splits), dim3(512), 0, s, k);
+        hipLaunchKernelGGL((dist_skinny_kernel<SkinnyCfg<512, 7>>), dim3(a.n_splits), dim3(512), 0, s, k);
     else
-        hipLaunchKernelGGL((dist_skinny_kernel<SkinnyCfg<1024, 4>>), dim3(n_splits), dim3(512), 0, s, k);
+        hipLaunchKernelGGL((dist_skinny_kernel<SkinnyCfg<1024, 5>>), dim3(a.n_splits), dim3(512), 0, s, k);
+    return hipGetLastError();
+}
+
+hipError_t launch_skinny_select(const SkinnyLaunch &a, hipStream_t s)
+{
+    const int64_t nb = a.n_pad / 32;
+    if (((nb + kThrThreads - 1) / kThrThreads) * a.r > kThrList) return hipErrorInvalidValue;   // see skinny_supported
+    hipLaunchKernelGGL(skinny_threshold_kernel, dim3(a.b), dim3(kThrThreads), 0, s, a.bmin, nb, a.r, a.tau,
+                       a.cand_count);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    int chunks = (int)((a.n_pad / 4 + 256 * 16 - 1) / (256 * 16));   // ~16 float4 groups per thread
+    if (chunks < 1) chunks = 1;
+    if (chunks > 256) chunks = 256;
+    hipLaunchKernelGGL(skinny_filter_kernel, dim3(chunks, a.b), dim3(256), 0, s, a.keys, a.n_pad, a.n, a.tau, a.cand,
+                       a.cand_count, 32 * a.r);
     return hipGetLastError();
 }
 

@@ -76,22 +76,23 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     if (r < k) r = k;
     if ((int64_t)r > L.n) r = (int)L.n;
     out->r = r;
-    out->skinny = !cascade && b <= kSkinnyRows && L.d_pad <= kSkinnyMaxD;
+    out->skinny = !cascade && skinny_supported(b, L.n_pad, L.d_pad, r);
     if (out->skinny) {
         DistPlan pl{};
         pl.variant = -1;
         pl.bm = 32;   // the query block fed to the matrix cores
         pl.r = r;
         pl.m_tiles = 1;
-        pl.n_tiles = (int)((L.n + kTileN - 1) / kTileN);
-        pl.n_splits = plan_skinny_splits(L.n, r, ctx->num_cus);
+        pl.n_tiles = (int)(L.n_pad / kTileN);
+        pl.n_splits = plan_skinny_splits(L.n, ctx->num_cus);
         pl.b_pad = 32;
         out->plan = pl;
+        out->ws_bytes = align_up((size_t)pl.b_pad * L.d_pad * 2) + skinny_workspace_bytes(L.n_pad, r, kAlign);
     } else {
         out->plan = plan_dist(b, L.n, r, ctx->num_cus);
+        out->ws_bytes = align_up((size_t)out->plan.b_pad * L.d_pad * 2) +
+                        align_up((size_t)out->plan.b_pad * out->plan.n_splits * r * 8);
     }
-    out->ws_bytes = align_up((size_t)out->plan.b_pad * L.d_pad * 2) +
-                    align_up((size_t)out->plan.b_pad * out->plan.n_splits * r * 8);
     return true;
 }
 
@@ -149,30 +150,56 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
 {
     Carver ws(workspace);
     uint16_t *q_bf = ws.take<uint16_t>((size_t)sh.plan.b_pad * L.d_pad);
-    uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * sh.plan.n_splits * sh.r);
     StageMarks marks(ctx, s);
 
     marks.mark(0);
     if (launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf, s) != hipSuccess)
         return FREEZE_EHIP;
 
-    DistArgs da{};
-    da.q_bf = q_bf;
-    da.c_bf = L.c_bf;
-    da.norm = L.norm;
-    da.part = part;
-    da.count = count;
-    da.b = (int)b;
-    da.n = (int)L.n;
-    da.d_pad = (int)L.d_pad;
-    marks.mark(1);
-    if ((sh.skinny ? launch_dist_skinny(da, sh.plan.n_splits, sh.r, s) : launch_dist_topr(sh.plan, da, s)) != hipSuccess)
-        return FREEZE_EHIP;
-    marks.mark(2);
-
     FinishArgs fa{};
-    fa.part = part;
-    fa.n_splits = sh.plan.n_splits;
+    marks.mark(1);
+    bool marked2 = false;
+    if (sh.skinny) {
+        SkinnyLaunch sl{};
+        sl.q_bf = q_bf;
+        sl.c_bf = L.c_bf;
+        sl.norm = L.norm;
+        sl.keys = ws.take<float>((size_t)kSkinnyRows * L.n_pad);
+        sl.bmin = ws.take<uint64_t>((size_t)kSkinnyRows * (L.n_pad / 32));
+        sl.tau = ws.take<uint64_t>(kSkinnyRows);
+        sl.cand_count = ws.take<int32_t>(kSkinnyRows);
+        sl.cand = ws.take<uint64_t>((size_t)kSkinnyRows * 32 * sh.r);
+        sl.b = (int)b;
+        sl.n = (int)L.n;
+        sl.d_pad = (int)L.d_pad;
+        sl.r = sh.r;
+        sl.n_splits = sh.plan.n_splits;
+        sl.n_pad = L.n_pad;
+        if (launch_skinny_stream(sl, s) != hipSuccess) return FREEZE_EHIP;
+        marks.mark(2);   // the stage timing counts the selection kernels with the finishing stage
+        marked2 = true;
+        if (launch_skinny_select(sl, s) != hipSuccess) return FREEZE_EHIP;
+        fa.part = sl.cand;
+        fa.part_count = sl.cand_count;
+        fa.part_stride = 32 * sh.r;
+        fa.n_splits = 1;
+    } else {
+        uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * sh.plan.n_splits * sh.r);
+        DistArgs da{};
+        da.q_bf = q_bf;
+        da.c_bf = L.c_bf;
+        da.norm = L.norm;
+        da.part = part;
+        da.count = count;
+        da.b = (int)b;
+        da.n = (int)L.n;
+        da.d_pad = (int)L.d_pad;
+        if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
+        fa.part = part;
+        fa.n_splits = sh.plan.n_splits;
+    }
+    if (!marked2) marks.mark(2);
+
     fa.r = sh.r;
     fa.queries = queries;
     fa.sel = sel;

@@ -83,13 +83,30 @@ hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int
 
 hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t s);
 
-// Small-batch path: one workgroup per range of cache tiles; q_bf is a 32-row tiled block,
-// `part` is [b, n_splits, r].
-int plan_skinny_splits(int64_t n, int r, int num_cus);
-hipError_t launch_dist_skinny(const DistArgs &a, int n_splits, int r, hipStream_t s);
+// Small-batch (bandwidth-bound) path: streaming kernel + threshold + filter; the result is a
+// candidate list per query for the finishing kernel.
+struct SkinnyLaunch {
+    const uint16_t *q_bf;   // 32 x d_pad prepared queries (rows >= b zero), tiled with 32-row tiles
+    const uint16_t *c_bf;
+    const float *norm;
+    float *keys;            // [b, n_pad] scratch
+    uint64_t *bmin;         // [b, n_pad / 32] scratch
+    uint64_t *tau;          // [b] scratch
+    int32_t *cand_count;    // [b] out: candidates found per query
+    uint64_t *cand;         // [b, 32 * r] out: packed (ordered key, index) candidates, unordered
+    int b, n, d_pad, r, n_splits;
+    int64_t n_pad;
+};
+bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r);
+int plan_skinny_splits(int64_t n, int num_cus);
+size_t skinny_workspace_bytes(int64_t n_pad, int r, size_t align);
+hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s);   // keys + block minima
+hipError_t launch_skinny_select(const SkinnyLaunch &a, hipStream_t s);   // threshold + candidate lists
 
 struct FinishArgs {
-    const uint64_t *part;   // [b_pad, n_splits, r]
+    const uint64_t *part;   // [b_pad, n_splits, r]; or, with part_count, [b, part_stride] candidate lists
+    const int32_t *part_count;   // device: entries per query in `part` (null: n_splits * r each)
+    int part_stride;
     int n_splits, r;
     const float *queries;   // [*, d] fp32 (original batch)
     const int32_t *sel;     // compact position -> row of `queries`, or null
