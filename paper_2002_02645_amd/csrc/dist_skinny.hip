@@ -208,12 +208,16 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
 // ---------------------------------------------------------------------------------------
 // Per query: T = the R-th smallest of the NB block minima (pairs (ordered key, index), all
 // distinct).  One workgroup of 1024 threads per query, two rounds of the same argument as in
-// the file header: thread t holds up to V values and their minimum m_t; the R-th smallest m_t
-// (T1) bounds the answer from above, and at most V * R values are <= T1; those are gathered
-// into LDS and sorted, and the R-th of them is T.  Sorting is bitonic, in LDS.
+// the file header: the minima are dealt into 256 groups (value j belongs to group j mod 256);
+// the R-th smallest group minimum T1 bounds the answer from above, and at most V * R values are
+// <= T1 (V = values per group); those are gathered into LDS and the R-th of them is T.  The
+// R-th smallest of a short list is found by rank counting (each element counts the smaller
+// ones), with a bitonic sort only for an unusually long list.
 // ---------------------------------------------------------------------------------------
 constexpr int kThrThreads = 1024;
-constexpr int kThrList = 4096;   // capacity of the gathered list; the launcher checks V * R <= kThrList
+constexpr int kThrGroups = 256;
+constexpr int kThrRegs = 32;      // values per thread kept in registers between the two rounds
+constexpr int kThrList = 8192;    // capacity of the gathered list; the launcher checks V * R <= kThrList
 
 __device__ void bitonic_sort_lds(uint64_t *a, int n_pow2, int tid, int nthreads)
 {
@@ -234,10 +238,22 @@ __device__ void bitonic_sort_lds(uint64_t *a, int n_pow2, int tid, int nthreads)
     }
 }
 
+// The element of a[0..n) with exactly `rank` smaller elements (all distinct), n <= blockDim.x.
+__device__ __forceinline__ void select_by_rank_counting(const uint64_t *a, int n, int rank, int tid, uint64_t *out)
+{
+    if (tid < n) {
+        const uint64_t mine = a[tid];
+        int c = 0;
+        for (int j = 0; j < n; ++j) c += (a[j] < mine);
+        if (c == rank) *out = mine;
+    }
+}
+
 __global__ __launch_bounds__(kThrThreads) void skinny_threshold_kernel(const uint64_t *bmin, int64_t nb, int r_sel,
                                                                       uint64_t *tau, int32_t *cand_count)
 {
     __shared__ uint64_t list[kThrList];
+    __shared__ uint64_t sel_s;
     __shared__ int list_n;
     const int q = blockIdx.x, tid = threadIdx.x;
     const uint64_t *src = bmin + (size_t)q * nb;
@@ -249,33 +265,65 @@ __global__ __launch_bounds__(kThrThreads) void skinny_threshold_kernel(const uin
         if (tid == 0) tau[q] = kSentinel;
         return;
     }
-    // round 1: per-thread minima, sorted; T1 = the r_sel-th smallest of them (r_sel <= 64 < 1024)
+    // round 1: thread minima -> 256 group minima -> T1 = the r_sel-th smallest group minimum
+    uint64_t v[kThrRegs];
     uint64_t m = kSentinel;
-    for (int64_t j = tid; j < nb; j += kThrThreads) {
-        const uint64_t v = src[j];
-        m = v < m ? v : m;
+#pragma unroll
+    for (int i = 0; i < kThrRegs; ++i) {
+        const int64_t j = (int64_t)i * kThrThreads + tid;
+        v[i] = j < nb ? src[j] : kSentinel;
+        m = v[i] < m ? v[i] : m;
+    }
+    for (int64_t j = (int64_t)kThrRegs * kThrThreads + tid; j < nb; j += kThrThreads) {
+        const uint64_t x = src[j];
+        m = x < m ? x : m;
     }
     list[tid] = m;
     __syncthreads();
-    bitonic_sort_lds(list, kThrThreads, tid, kThrThreads);
-    const uint64_t t1 = list[r_sel - 1];
+    if (tid < kThrGroups) {
+        uint64_t g = list[tid];
+#pragma unroll
+        for (int i = 1; i < kThrThreads / kThrGroups; ++i) {
+            const uint64_t x = list[tid + i * kThrGroups];
+            g = x < g ? x : g;
+        }
+        list[kThrThreads + tid] = g;   // group minima live in list[1024 .. 1280)
+    }
     __syncthreads();
-    // round 2: gather the values <= T1 (at least r_sel, at most V * r_sel of them), sort, take the r_sel-th
-    for (int64_t j = tid; j < nb; j += kThrThreads) {
-        const uint64_t v = src[j];
-        if (v <= t1) {
+    // sentinels (groups with no value) are equal to each other; they rank last and r_sel < nb real values exist
+    select_by_rank_counting(list + kThrThreads, kThrGroups, r_sel - 1, tid, &sel_s);
+    __syncthreads();
+    const uint64_t t1 = sel_s;
+    __syncthreads();
+    // round 2: gather the values <= T1 (at least r_sel, at most V * r_sel of them)
+#pragma unroll
+    for (int i = 0; i < kThrRegs; ++i) {
+        if (v[i] <= t1 && v[i] != kSentinel) {
             const int pos = atomicAdd(&list_n, 1);
-            if (pos < kThrList) list[pos] = v;
+            if (pos < kThrList) list[pos] = v[i];
+        }
+    }
+    for (int64_t j = (int64_t)kThrRegs * kThrThreads + tid; j < nb; j += kThrThreads) {
+        const uint64_t x = src[j];
+        if (x <= t1) {
+            const int pos = atomicAdd(&list_n, 1);
+            if (pos < kThrList) list[pos] = x;
         }
     }
     __syncthreads();
     const int cnt = list_n < kThrList ? list_n : kThrList;
-    int n2 = 2;
-    while (n2 < cnt) n2 <<= 1;
-    for (int i = cnt + tid; i < n2; i += kThrThreads) list[i] = kSentinel;
-    __syncthreads();
-    bitonic_sort_lds(list, n2, tid, kThrThreads);
-    if (tid == 0) tau[q] = list[r_sel - 1];
+    if (cnt <= kThrThreads) {
+        select_by_rank_counting(list, cnt, r_sel - 1, tid, &sel_s);
+        __syncthreads();
+        if (tid == 0) tau[q] = sel_s;
+    } else {
+        int n2 = 2;
+        while (n2 < cnt) n2 <<= 1;
+        for (int i = cnt + tid; i < n2; i += kThrThreads) list[i] = kSentinel;
+        __syncthreads();
+        bitonic_sort_lds(list, n2, tid, kThrThreads);
+        if (tid == 0) tau[q] = list[r_sel - 1];
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -311,7 +359,7 @@ __global__ __launch_bounds__(256) void skinny_filter_kernel(const float *keys, i
 bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r)
 {
     const int64_t nb = n_pad / 32;
-    return b >= 1 && b <= kSkinnyRows && d_pad <= kSkinnyMaxD && ((nb + kThrThreads - 1) / kThrThreads) * r <= kThrList;
+    return b >= 1 && b <= kSkinnyRows && d_pad <= kSkinnyMaxD && ((nb + kThrGroups - 1) / kThrGroups) * r <= kThrList;
 }
 
 int plan_skinny_splits(int64_t n, int num_cus)
@@ -354,7 +402,7 @@ hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
 hipError_t launch_skinny_select(const SkinnyLaunch &a, hipStream_t s)
 {
     const int64_t nb = a.n_pad / 32;
-    if (((nb + kThrThreads - 1) / kThrThreads) * a.r > kThrList) return hipErrorInvalidValue;   // see skinny_supported
+    if (((nb + kThrGroups - 1) / kThrGroups) * a.r > kThrList) return hipErrorInvalidValue;   // see skinny_supported
     hipLaunchKernelGGL(skinny_threshold_kernel, dim3(a.b), dim3(kThrThreads), 0, s, a.bmin, nb, a.r, a.tau,
                        a.cand_count);
     hipError_t e = hipGetLastError();
