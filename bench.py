@@ -25,6 +25,26 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
 
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
+    workload (FETCH_SIZE and WRITE_SIZE in KiB, each scaled by the plain-copy calibration factor
+    recorded in the same file); None when there is no summary."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    vals, factor = {}, {}
+    for line in open(path):
+        parts = line.split()
+        for c in ("FETCH_SIZE", "WRITE_SIZE"):
+            if line.startswith(f"fz::{kernel}") and c in parts:
+                vals[c] = float(parts[parts.index(c) + 1])
+            if line.startswith(f"{c} calibration") and "factor" in parts:
+                factor[c] = float(parts[parts.index("factor") + 1])
+    if set(vals) != {"FETCH_SIZE", "WRITE_SIZE"} or set(factor) != {"FETCH_SIZE", "WRITE_SIZE"}:
+        return None
+    return (vals["FETCH_SIZE"] * factor["FETCH_SIZE"] + vals["WRITE_SIZE"] * factor["WRITE_SIZE"]) * 1024.0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +133,7 @@ def main() -> int:
         roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=round(achieved / PEAK_HBM_GBS, 4), traffic=None)
     roofline["kernel"] = "dist_topr_kernel" if b > 16 or spec.d > 1024 else "dist_skinny_kernel"
+    roofline["traffic"] = measured_traffic(roofline["kernel"], wl.name)
     roofline["kernel_ms"] = round(dist_ms, 4)
     roofline["stage_ms"] = {"query_prep": round(stage_ms[0] / max(calls, 1), 4), "dist_topr": round(dist_ms, 4),
                             "finish": round(stage_ms[2] / max(calls, 1), 4)}
@@ -166,10 +187,10 @@ def main() -> int:
                                              "differ_outside_near_tie": unexplained,
                                              "hit_equal": int((got_hit == ref["hit"]).sum())}
     if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)       # reads 1 GiB, writes 1 GiB
+            torch.bitwise_not(src, out=dst)   # a plain elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         result["config"]["copy_calibration_bytes"] = 1 << 30
     fc.close()
