@@ -356,10 +356,23 @@ __global__ __launch_bounds__(256) void skinny_filter_kernel(const float *keys, i
 
 }  // namespace
 
-bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r)
+bool select_supported(int64_t n_pad, int r)
 {
     const int64_t nb = n_pad / 32;
-    return b >= 1 && b <= kSkinnyRows && d_pad <= kSkinnyMaxD && ((nb + kThrGroups - 1) / kThrGroups) * r <= kThrList;
+    return ((nb + kThrGroups - 1) / kThrGroups) * r <= kThrList;
+}
+
+bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r)
+{
+    return b >= 1 && b <= kSkinnyRows && d_pad <= kSkinnyMaxD && select_supported(n_pad, r);
+}
+
+size_t select_workspace_bytes(int64_t rows, int64_t n_pad, int r, size_t align)
+{
+    auto up = [&](size_t x) { return (x + align - 1) / align * align; };
+    const size_t b = (size_t)rows;
+    return up(b * (size_t)n_pad * 4) + up(b * (size_t)(n_pad / 32) * 8) + up(b * 8) + up(b * 4) +
+           up(b * (size_t)(32 * r) * 8);
 }
 
 int plan_skinny_splits(int64_t n, int num_cus)
@@ -371,10 +384,7 @@ int plan_skinny_splits(int64_t n, int num_cus)
 
 size_t skinny_workspace_bytes(int64_t n_pad, int r, size_t align)
 {
-    auto up = [&](size_t x) { return (x + align - 1) / align * align; };
-    const size_t b = kSkinnyRows;
-    return up(b * (size_t)n_pad * 4) + up(b * (size_t)(n_pad / 32) * 8) + up(b * 8) + up(b * 4) +
-           up(b * (size_t)(32 * r) * 8);
+    return select_workspace_bytes(kSkinnyRows, n_pad, r, align);
 }
 
 hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
@@ -399,20 +409,25 @@ hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_skinny_select(const SkinnyLaunch &a, hipStream_t s)
+hipError_t launch_select(const float *keys, const uint64_t *bmin, int64_t n_pad, int n, int b, int r, uint64_t *tau,
+                         int32_t *cand_count, uint64_t *cand, hipStream_t s)
 {
-    const int64_t nb = a.n_pad / 32;
-    if (((nb + kThrGroups - 1) / kThrGroups) * a.r > kThrList) return hipErrorInvalidValue;   // see skinny_supported
-    hipLaunchKernelGGL(skinny_threshold_kernel, dim3(a.b), dim3(kThrThreads), 0, s, a.bmin, nb, a.r, a.tau,
-                       a.cand_count);
+    const int64_t nb = n_pad / 32;
+    if (!select_supported(n_pad, r) || b < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(skinny_threshold_kernel, dim3(b), dim3(kThrThreads), 0, s, bmin, nb, r, tau, cand_count);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    int chunks = (int)((a.n_pad / 4 + 256 * 16 - 1) / (256 * 16));   // ~16 float4 groups per thread
+    int chunks = (int)((n_pad / 4 + 256 * 16 - 1) / (256 * 16));   // ~16 float4 groups per thread
     if (chunks < 1) chunks = 1;
     if (chunks > 256) chunks = 256;
-    hipLaunchKernelGGL(skinny_filter_kernel, dim3(chunks, a.b), dim3(256), 0, s, a.keys, a.n_pad, a.n, a.tau, a.cand,
-                       a.cand_count, 32 * a.r);
+    hipLaunchKernelGGL(skinny_filter_kernel, dim3(chunks, b), dim3(256), 0, s, keys, n_pad, n, tau, cand, cand_count,
+                       32 * r);
     return hipGetLastError();
+}
+
+hipError_t launch_skinny_select(const SkinnyLaunch &a, hipStream_t s)
+{
+    return launch_select(a.keys, a.bmin, a.n_pad, a.n, a.b, a.r, a.tau, a.cand_count, a.cand, s);
 }
 
 }  // namespace fz

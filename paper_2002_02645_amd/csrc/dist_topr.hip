@@ -79,6 +79,7 @@ struct DistCfg {
     // slab pass: WNS wave columns at a time
     static constexpr int WNS = (BM * 4 * 32 * 4 <= OP_BYTES) ? 4 : ((BM * 2 * 32 * 4 <= OP_BYTES) ? 2 : 1);
     static constexpr int SLABW = WNS * 32;          // keys per row in one slab
+    static constexpr bool KEYS = (RMAX == 0);       // no fused selection: write every key (small batches)
     static constexpr int TOP_BYTES = RMAX * BM * 8;
     static constexpr int LDS_BYTES = OP_BYTES + TOP_BYTES;
     static_assert(BM * SLABW * 4 <= OP_BYTES, "slab must fit in the operand area");
@@ -86,7 +87,7 @@ struct DistCfg {
     static_assert(NI_A >= 1 && NI_B >= 1, "load split");
     static_assert(BM <= THREADS, "one scanning thread per row");
     static constexpr int LPS = NI_A + NI_B;         // direct loads per thread and stage
-    static_assert(NS >= 2 && NS <= 4 && (NS - 2) * LPS <= 63, "vmcnt range");
+    static_assert(NS >= 2 && NS <= 6 && (NS - 2) * LPS <= 63, "vmcnt range");
 };
 
 struct DistKernelArgs {
@@ -98,6 +99,10 @@ struct DistKernelArgs {
     int b, n, d_pad;
     int n_tiles, n_splits, r;
     int units;   // m_tiles * n_splits
+    // keys-out variant only:
+    float *keys;      // [b_pad, n_pad]
+    uint64_t *bmin;   // [b_pad, n_pad / 32]
+    int64_t n_pad;
 };
 
 template <class C>
@@ -132,9 +137,11 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     uint64_t curmax = kSentinel;
     int maxpos = 0;
     float tau = __builtin_inff();
-    if (tid < BM) {
+    if constexpr (!C::KEYS) {
+        if (tid < BM) {
 #pragma unroll
-        for (int i = 0; i < C::RMAX; ++i) top[i * BM + tid] = kSentinel;
+            for (int i = 0; i < C::RMAX; ++i) top[i * BM + tid] = kSentinel;
+        }
     }
 
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
@@ -183,12 +190,13 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         for (int kt = 0; kt < nk; ++kt) {
             // stage `st` must have landed; the (up to NS-2) younger stages may stay in flight
             const int younger = nk - 1 - kt;
-            if (C::NS >= 4 && younger >= 2)
-                wait_global_loads_le<(C::NS >= 4 ? 2 : 0) * C::LPS>();
-            else if (C::NS >= 3 && younger >= 1)
-                wait_global_loads_le<(C::NS >= 3 ? 1 : 0) * C::LPS>();
-            else
-                wait_global_loads_le<0>();
+            switch (younger < C::NS - 2 ? younger : C::NS - 2) {
+            case 0: wait_global_loads_le<0>(); break;
+            case 1: wait_global_loads_le<1 * C::LPS>(); break;
+            case 2: wait_global_loads_le<(C::NS > 3 ? 2 : 0) * C::LPS>(); break;
+            case 3: wait_global_loads_le<(C::NS > 4 ? 3 : 0) * C::LPS>(); break;
+            default: wait_global_loads_le<(C::NS > 5 ? 4 : 0) * C::LPS>(); break;
+            }
             __syncthreads();   // ... for every wave; and all reads of the stage refilled next are done
             if (kt + C::NS - 1 < nk) issue((st + C::NS - 1) % C::NS, kt + C::NS - 1);
             const int baseA = st * (C::STAGE_BYTES / 16) + rdA;
@@ -212,6 +220,58 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         }
         __syncthreads();   // operand LDS is free: the slab may overwrite it
 
+        if constexpr (C::KEYS) {
+            // ---- epilogue (keys-out): every key and the minimum of every block of 32 entries ----
+            // Keys pass through the LDS slab so that the global stores are whole 512-byte row pieces.
+            static_assert(!C::KEYS || C::WNS == C::WN, "keys-out epilogue: one slab pass covers all wave columns");
+#pragma unroll
+            for (int bj = 0; bj < TN; ++bj) {
+                {
+                    const int col = n0 + wn * TN * 32 + bj * 32 + (lane & 31);
+                    const float nrm = p.norm[col];   // col < n_pad always
+                    const int sc = wn * 32 + (lane & 31);
+#pragma unroll
+                    for (int bi = 0; bi < TM; ++bi) {
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                            slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] =
+                                __builtin_fmaf(-2.f, acc[bi][bj][e], nrm);
+                        }
+                    }
+                }
+                __syncthreads();
+                // half-wave h of wave w copies row it*16 + 2w + h: 32 lanes x 4 keys = the slab's 128 columns
+                const int l32 = lane & 31;
+                const int seg = l32 >> 3;                                   // wave column the 4 keys came from
+                const int gcol = n0 + seg * TN * 32 + bj * 32 + (l32 & 7) * 4;   // entry index of the first key
+#pragma unroll 2
+                for (int it = 0; it < BM / 16; ++it) {
+                    const int row = it * 16 + w * 2 + g;
+                    const int grow = mt * BM + row;
+                    const f32x4 v = reinterpret_cast<const f32x4 *>(slab + row * C::SLABW)[(l32 ^ row) & (C::SLABW / 4 - 1)];
+                    const bool live = grow < nq;
+                    if (live) *reinterpret_cast<f32x4 *>(p.keys + (size_t)grow * p.n_pad + gcol) = v;
+                    // minimum (key, index) pair of the 32-entry block: 4 own keys, then the 8 lanes of the block
+                    uint64_t mn = ((uint64_t)ordered_bits(v[0]) << 32) | (uint32_t)gcol;
+#pragma unroll
+                    for (int e = 1; e < 4; ++e) {
+                        const uint64_t pr = ((uint64_t)ordered_bits(v[e]) << 32) | (uint32_t)(gcol + e);
+                        mn = pr < mn ? pr : mn;
+                    }
+#pragma unroll
+                    for (int off = 4; off >= 1; off >>= 1) {
+                        const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)mn, off, 64);
+                        const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(mn >> 32), off, 64);
+                        const uint64_t o = ((uint64_t)hi << 32) | lo;
+                        mn = o < mn ? o : mn;
+                    }
+                    if (live && (l32 & 7) == 0) p.bmin[(size_t)grow * (p.n_pad / 32) + (gcol >> 5)] = mn;
+                }
+                __syncthreads();
+            }
+            continue;
+        }
         // ---- epilogue: fold this tile into the per-row top-R lists ----
 #pragma unroll
         for (int bj = 0; bj < TN; ++bj) {
@@ -285,7 +345,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         }
     }
 
-    if (tid < BM) {
+    if (!C::KEYS && tid < BM) {
         uint64_t *dst = p.part + (((size_t)mt * BM + tid) * p.n_splits + sp) * r;
 #pragma unroll
         for (int i = 0; i < C::RMAX; ++i)
@@ -293,10 +353,10 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     }
 }
 
-DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus)
+DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out)
 {
     DistPlan pl{};
-    pl.variant = r <= 16 ? 0 : (r <= 32 ? 1 : 2);
+    pl.variant = keys_out ? 3 : (r <= 16 ? 0 : (r <= 32 ? 1 : 2));
     pl.bm = pl.variant == 2 ? 128 : 256;
     pl.r = r;
     pl.m_tiles = (int)((b + pl.bm - 1) / pl.bm);
@@ -306,7 +366,7 @@ DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus)
     // Choose the number of splits.  More splits fill the CUs more evenly, but every split restarts
     // its top-R lists from scratch and adds entries to the merge, so take the FEWEST splits whose
     // CU fill (over whole rounds of workgroups) is within 10% of the best achievable.
-    const int max_splits = pl.n_tiles < kMaxMergeEntries / r ? pl.n_tiles : kMaxMergeEntries / r;
+    const int max_splits = (keys_out || pl.n_tiles < kMaxMergeEntries / r) ? pl.n_tiles : kMaxMergeEntries / r;
     const double total = (double)pl.m_tiles * pl.n_tiles;
     auto fill = [&](int s) {
         const int64_t units = (int64_t)pl.m_tiles * s;
@@ -342,6 +402,9 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
     k.n_splits = plan.n_splits;
     k.r = plan.r;
     k.units = plan.m_tiles * plan.n_splits;
+    k.keys = a.keys;
+    k.bmin = a.bmin;
+    k.n_pad = (int64_t)plan.n_tiles * kTileN;
     hipLaunchKernelGGL((dist_topr_kernel<C>), dim3(k.units), dim3(C::THREADS), 0, s, k);
     return hipGetLastError();
 }
@@ -349,10 +412,12 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
 hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t s)
 {
     if (plan.r < 1 || plan.r > kMaxRescore || a.d_pad % kPadD != 0) return hipErrorInvalidValue;
+    if (plan.variant == 3 && (!a.keys || !a.bmin)) return hipErrorInvalidValue;
     switch (plan.variant) {
     case 0: return launch_variant<DistCfg<256, 64, 16, 2>>(plan, a, s);
     case 1: return launch_variant<DistCfg<256, 32, 32, 3>>(plan, a, s);
-    default: return launch_variant<DistCfg<128, 32, 64, 3>>(plan, a, s);
+    case 2: return launch_variant<DistCfg<128, 32, 64, 3>>(plan, a, s);
+    default: return launch_variant<DistCfg<256, 32, 0, 5>>(plan, a, s);
     }
 }
 

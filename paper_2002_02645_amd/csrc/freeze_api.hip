@@ -63,6 +63,7 @@ int default_rescore(int k) { return k <= 10 ? 16 : (k <= 24 ? 32 : 64); }
 struct LookupShape {
     int r;
     bool skinny;   // small-batch bandwidth-bound kernel instead of the tiled matrix-core kernel
+    bool keys;     // tiled kernel writes every key; selection by the threshold / filter kernels
     DistPlan plan;
     size_t ws_bytes;
 };
@@ -77,6 +78,7 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     if ((int64_t)r > L.n) r = (int)L.n;
     out->r = r;
     out->skinny = !cascade && skinny_supported(b, L.n_pad, L.d_pad, r);
+    out->keys = false;
     if (out->skinny) {
         DistPlan pl{};
         pl.variant = -1;
@@ -89,9 +91,16 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
         out->plan = pl;
         out->ws_bytes = align_up((size_t)pl.b_pad * L.d_pad * 2) + skinny_workspace_bytes(L.n_pad, r, kAlign);
     } else {
-        out->plan = plan_dist(b, L.n, r, ctx->num_cus);
-        out->ws_bytes = align_up((size_t)out->plan.b_pad * L.d_pad * 2) +
-                        align_up((size_t)out->plan.b_pad * out->plan.n_splits * r * 8);
+        // One query tile and a long activation: materialising the keys (4 B per entry and query)
+        // is cheap next to the cache stream (2 d B per entry), lets the tile be 256 queries wide for
+        // any R, and keeps the selection out of the streaming kernel.
+        out->keys = !cascade && b <= 256 && b * 20 <= L.d_pad && select_supported(L.n_pad, r);
+        out->plan = plan_dist(b, L.n, r, ctx->num_cus, out->keys);
+        out->ws_bytes = align_up((size_t)out->plan.b_pad * L.d_pad * 2);
+        if (out->keys)
+            out->ws_bytes += select_workspace_bytes(out->plan.b_pad, L.n_pad, r, kAlign);
+        else
+            out->ws_bytes += align_up((size_t)out->plan.b_pad * out->plan.n_splits * r * 8);
     }
     return true;
 }
@@ -184,19 +193,37 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
         fa.part_stride = 32 * sh.r;
         fa.n_splits = 1;
     } else {
-        uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * sh.plan.n_splits * sh.r);
         DistArgs da{};
         da.q_bf = q_bf;
         da.c_bf = L.c_bf;
         da.norm = L.norm;
-        da.part = part;
         da.count = count;
         da.b = (int)b;
         da.n = (int)L.n;
         da.d_pad = (int)L.d_pad;
-        if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
-        fa.part = part;
-        fa.n_splits = sh.plan.n_splits;
+        if (sh.keys) {
+            const size_t rows = (size_t)sh.plan.b_pad;
+            da.keys = ws.take<float>(rows * L.n_pad);
+            da.bmin = ws.take<uint64_t>(rows * (L.n_pad / 32));
+            uint64_t *tau = ws.take<uint64_t>(rows);
+            int32_t *cand_count = ws.take<int32_t>(rows);
+            uint64_t *cand = ws.take<uint64_t>(rows * 32 * sh.r);
+            if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
+            marks.mark(2);
+            marked2 = true;
+            if (launch_select(da.keys, da.bmin, L.n_pad, (int)L.n, (int)b, sh.r, tau, cand_count, cand, s) != hipSuccess)
+                return FREEZE_EHIP;
+            fa.part = cand;
+            fa.part_count = cand_count;
+            fa.part_stride = 32 * sh.r;
+            fa.n_splits = 1;
+        } else {
+            uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * sh.plan.n_splits * sh.r);
+            da.part = part;
+            if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
+            fa.part = part;
+            fa.n_splits = sh.plan.n_splits;
+        }
     }
     if (!marked2) marks.mark(2);
 

@@ -52,7 +52,7 @@ struct LayerCache {
 
 // Which distance kernel variant serves a re-scoring width.
 struct DistPlan {
-    int variant;    // 0: R<=16, 1: R<=32, 2: R<=64
+    int variant;    // 0: R<=16, 1: R<=32, 2: R<=64 (fused top-R); 3: keys-out (selection by separate kernels)
     int bm;         // queries per tile
     int r;          // entries kept per (query, split)
     int m_tiles;    // ceil(b / bm)
@@ -61,13 +61,15 @@ struct DistPlan {
     int64_t b_pad;  // m_tiles * bm
 };
 
-DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus);
+DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out);
 
 struct DistArgs {
     const uint16_t *q_bf;   // b_pad x d_pad, tiled layout (tiles of plan.bm rows)
     const uint16_t *c_bf;   // n_pad x d_pad, tiled layout (tiles of kTileN rows)
     const float *norm;      // [n_pad]
-    uint64_t *part;         // [b_pad, n_splits, r] packed (ordered key, index)
+    uint64_t *part;         // [b_pad, n_splits, r] packed (ordered key, index) (fused variants)
+    float *keys;            // [b_pad, n_pad] every key (keys-out variant)
+    uint64_t *bmin;         // [b_pad, n_pad / 32] block minima (keys-out variant)
     const int32_t *count;   // device: number of live queries, or null (= b)
     int b;
     int n;
@@ -98,6 +100,12 @@ struct SkinnyLaunch {
     int64_t n_pad;
 };
 bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r);
+// Selection from materialised keys (shared by the small-batch and the keys-out paths):
+// threshold from the block minima, then the candidate lists.  b queries, rows of n_pad keys.
+bool select_supported(int64_t n_pad, int r);
+size_t select_workspace_bytes(int64_t rows, int64_t n_pad, int r, size_t align);
+hipError_t launch_select(const float *keys, const uint64_t *bmin, int64_t n_pad, int n, int b, int r, uint64_t *tau,
+                         int32_t *cand_count, uint64_t *cand, hipStream_t s);
 int plan_skinny_splits(int64_t n, int num_cus);
 size_t skinny_workspace_bytes(int64_t n_pad, int r, size_t align);
 hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s);   // keys + block minima

@@ -77,6 +77,9 @@ def test_hand_example_on_gpu():
     (5000, 1024, 16, 10, 0, torch.bfloat16),   # small-batch kernel, longest supported activation
     (3000, 960, 3, 5, 0, torch.float32),       # small-batch kernel, fp32 cache, d not a multiple of 64
     (3000, 1100, 3, 5, 0, torch.bfloat16),     # d too long for the small-batch kernel -> tiled kernel
+    (3000, 2048, 100, 10, 0, torch.bfloat16),  # one query tile, long activation -> keys-out kernel + selection
+    (2500, 4160, 200, 10, 64, torch.float32),  # keys-out, R = 64, fp32 cache, ragged everything
+    (1000, 640, 20, 5, 0, torch.bfloat16),     # keys-out with few cache tiles
 ])
 def test_shapes_against_oracle(n, d, b, k, r, dtype):
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
