@@ -58,8 +58,9 @@ int freeze_create(freeze_ctx **out, int num_layers);
 int freeze_destroy(freeze_ctx *ctx);
 
 /* Bytes of device memory freeze_cache_build needs in `storage` for an n x d cache
- * (bf16 rows padded for the matrix cores, fp32 squared norms, labels, and the fp32
- * rows when the entries are given in fp32).  0 on invalid arguments. */
+ * (bf16 rows tiled and padded for the matrix cores, fp32 squared norms, labels, and a
+ * row-major copy of the stored values for exact re-scoring: about 2x the bf16 size of the
+ * cache, 3x when the entries are given in fp32).  0 on invalid arguments. */
 size_t freeze_cache_storage_bytes(int64_t n, int64_t d, int entries_dtype);
 
 /*

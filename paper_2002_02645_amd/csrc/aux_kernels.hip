@@ -32,11 +32,13 @@ __device__ __forceinline__ float block_sum_256(float v, float *scratch4)
 // ---------------------------------------------------------------------------------------
 // Cache ingest (Pseudocode 1, ConstructCache: the layer's list of <output, label>).
 // One block per padded cache row: bf16 copy (round to nearest even when given fp32) into the
-// tiled layout, zero padding, |c|^2 of the bf16 row in fp32, optional row-major fp32 copy for
-// exact re-scoring.
+// tiled layout, zero padding, |c|^2 of the bf16 row in fp32, and a row-major copy of the stored
+// values for exact re-scoring (fp32 rows when the cache was given in fp32, else bf16 rows): the
+// re-scoring gathers whole rows, which the tiled layout would serve in half-used cache lines.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, int dtype, int64_t n, int64_t d,
-                                                          int64_t d_pad, uint16_t *c_bf, float *norm, float *c_f32)
+                                                          int64_t d_pad, uint16_t *c_bf, float *norm, float *c_f32,
+                                                          uint16_t *c_rows)
 {
     __shared__ float red[4];
     const int64_t row = blockIdx.x;
@@ -69,6 +71,7 @@ __global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, i
         v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
         v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
         tile_base[tiled_chunk_offset(rit, j, kTileN)] = v;
+        if (c_rows && row < n) reinterpret_cast<uint4 *>(c_rows + row * d_pad)[j] = v;
     }
     const float tot = block_sum_256(ss, red);
     if (threadIdx.x == 0) norm[row] = (row < n) ? tot : __builtin_inff();
@@ -81,11 +84,11 @@ __global__ void copy_i32_kernel(const int32_t *src, int32_t *dst, int64_t n)
 }
 
 hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t d, int64_t n_pad, int64_t d_pad,
-                              uint16_t *c_bf, float *norm, float *c_f32, const int32_t *labels_in,
+                              uint16_t *c_bf, float *norm, float *c_f32, uint16_t *c_rows, const int32_t *labels_in,
                               int32_t *labels_out, hipStream_t s)
 {
     hipLaunchKernelGGL(cache_build_kernel, dim3((unsigned)n_pad), dim3(256), 0, s, entries, dtype, n, d, d_pad, c_bf,
-                       norm, c_f32);
+                       norm, c_f32, c_rows);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(copy_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, labels_in, labels_out, n);
@@ -153,14 +156,10 @@ __device__ __forceinline__ void rescore_wave(const FinishArgs &a, const float *q
     for (int c0 = wave * G; c0 < r; c0 += 4 * G) {
         float acc[G];
         int64_t cand[G];
-        const uint4 *cand_tile[G];   // tile base of the candidate's row in the tiled bf16 cache
-        int cand_rit[G];             // its row inside the tile
 #pragma unroll
         for (int j = 0; j < G; ++j) {
             acc[j] = 0.f;
             cand[j] = idx_s[(c0 + j < r) ? c0 + j : r - 1];
-            cand_tile[j] = reinterpret_cast<const uint4 *>(a.c_bf + (cand[j] / kTileN) * kTileN * a.d_pad);
-            cand_rit[j] = (int)(cand[j] % kTileN);
         }
         if (vec) {
             for (int64_t i = (int64_t)lane * 8; i < a.d; i += 64 * 8) {
@@ -183,7 +182,7 @@ __device__ __forceinline__ void rescore_wave(const FinishArgs &a, const float *q
                 } else {
 #pragma unroll
                     for (int j = 0; j < G; ++j) {
-                        const uint4 cb = cand_tile[j][tiled_chunk_offset(cand_rit[j], i >> 3, kTileN)];
+                        const uint4 cb = *reinterpret_cast<const uint4 *>(a.c_rows + cand[j] * a.d_pad + i);
                         const uint32_t wv[4] = {cb.x, cb.y, cb.z, cb.w};
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
@@ -206,9 +205,7 @@ __device__ __forceinline__ void rescore_wave(const FinishArgs &a, const float *q
                     if (a.c_f32) {
                         cv = a.c_f32[cand[j] * a.d_pad + i];
                     } else {
-                        const uint16_t *chunk = reinterpret_cast<const uint16_t *>(
-                            cand_tile[j] + tiled_chunk_offset(cand_rit[j], i >> 3, kTileN));
-                        cv = bf16_to_f32(chunk[i & 7]);
+                        cv = bf16_to_f32(a.c_rows[cand[j] * a.d_pad + i]);
                     }
                     const float df = qv - cv;
                     acc[j] = __builtin_fmaf(df, df, acc[j]);
@@ -225,25 +222,23 @@ __device__ __forceinline__ void rescore_wave(const FinishArgs &a, const float *q
     }
 }
 
-// Exact re-scoring by the whole block, 8 candidates at a time (long activations: the query row
-// is read once per 8 candidates and every thread keeps 10 loads in flight).  Same arithmetic as
+// Exact re-scoring by the whole block of NT threads, 8 candidates at a time (long activations:
+// the query row is read once per 8 candidates and every thread keeps 10 loads in flight; small
+// batches use 1024-thread blocks so that a block per query still fills the memory system).  Same arithmetic as
 // rescore_wave; partial sums are combined wave by wave in a fixed order.
+template <int NT>
 __device__ __forceinline__ void rescore_block(const FinishArgs &a, const float *qrow, const int32_t *idx_s,
                                               float *dist_s, float (*red)[8], int r, int tid)
 {
     for (int r0 = 0; r0 < r; r0 += 8) {
         float acc[8];
-        const uint4 *cand_tile[8];
-        int cand_rit[8];
         int64_t cand[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             acc[j] = 0.f;
             cand[j] = idx_s[(r0 + j < r) ? r0 + j : r - 1];
-            cand_tile[j] = reinterpret_cast<const uint4 *>(a.c_bf + (cand[j] / kTileN) * kTileN * a.d_pad);
-            cand_rit[j] = (int)(cand[j] % kTileN);
         }
-        for (int64_t i = (int64_t)tid * 8; i < a.d; i += 256 * 8) {
+        for (int64_t i = (int64_t)tid * 8; i < a.d; i += NT * 8) {
             const f32x4 q0 = *reinterpret_cast<const f32x4 *>(qrow + i);
             const f32x4 q1 = *reinterpret_cast<const f32x4 *>(qrow + i + 4);
             const float qv[8] = {q0[0], q0[1], q0[2], q0[3], q1[0], q1[1], q1[2], q1[3]};
@@ -263,7 +258,7 @@ __device__ __forceinline__ void rescore_block(const FinishArgs &a, const float *
             } else {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint4 cb = cand_tile[j][tiled_chunk_offset(cand_rit[j], i >> 3, kTileN)];
+                    const uint4 cb = *reinterpret_cast<const uint4 *>(a.c_rows + cand[j] * a.d_pad + i);
                     const uint32_t wv[4] = {cb.x, cb.y, cb.z, cb.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -285,7 +280,13 @@ __device__ __forceinline__ void rescore_block(const FinishArgs &a, const float *
             if ((tid & 63) == 0) red[tid >> 6][j] = v;
         }
         __syncthreads();
-        if (tid < 8 && r0 + tid < r) dist_s[r0 + tid] = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+        if (tid < 8 && r0 + tid < r) {
+            float t = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < NT / 64; wv += 4)   // fixed order: groups of four waves
+                t += (red[wv][tid] + red[wv + 1][tid]) + (red[wv + 2][tid] + red[wv + 3][tid]);
+            dist_s[r0 + tid] = t;
+        }
         __syncthreads();
     }
 }
@@ -295,11 +296,12 @@ struct FinishKernelArgs {
     int sort_cap;   // power of two >= the largest number of entries gathered per query (LDS allocation)
 };
 
-__global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
+template <int NT>
+__global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
 {
     const FinishArgs &a = fa.a;
     extern __shared__ uint64_t ent[];   // sort_cap entries (dynamic: small merges keep occupancy high)
-    __shared__ float red[4][8];
+    __shared__ float red[NT / 64][8];
     __shared__ float dist_s[kMaxRescore];
     __shared__ int32_t idx_s[kMaxRescore];
     __shared__ int32_t lab_s[kMaxK];
@@ -320,11 +322,11 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
     int sort_n = 2;
     while (sort_n < total) sort_n <<= 1;   // <= fa.sort_cap, the LDS allocation
     const uint64_t *src = a.part + (size_t)q * stride;
-    for (int i = tid; i < sort_n; i += 256) ent[i] = (i < total) ? src[i] : kSentinel;
+    for (int i = tid; i < sort_n; i += NT) ent[i] = (i < total) ? src[i] : kSentinel;
     __syncthreads();
     for (int size = 2; size <= sort_n; size <<= 1) {
         for (int stride2 = size >> 1; stride2 > 0; stride2 >>= 1) {
-            for (int i = tid; i < (sort_n >> 1); i += 256) {
+            for (int i = tid; i < (sort_n >> 1); i += NT) {
                 const int lo = ((i & ~(stride2 - 1)) << 1) | (i & (stride2 - 1));   // stride2 is a power of two
                 const int hi = lo + stride2;
                 const bool up = ((lo & size) == 0);
@@ -349,13 +351,15 @@ __global__ __launch_bounds__(256) void finish_kernel(FinishKernelArgs fa)
     // 2. exact fp32 re-scoring: each wave takes a group of candidates and needs no block barrier
     const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
     if (a.d >= 4096 && a.d % 8 == 0)
-        rescore_block(a, qrow, idx_s, dist_s, red, r, tid);
-    else if (r <= 16)
-        rescore_wave<4>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
-    else if (r <= 32)
-        rescore_wave<8>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
-    else
-        rescore_wave<16>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
+        rescore_block<NT>(a, qrow, idx_s, dist_s, red, r, tid);
+    else if (tid < 256) {   // short activations: four waves, one group of candidates each
+        if (r <= 16)
+            rescore_wave<4>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
+        else if (r <= 32)
+            rescore_wave<8>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
+        else
+            rescore_wave<16>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
+    }
     __syncthreads();
 
     // 3. final order (dist, index) and the first k
@@ -407,7 +411,13 @@ hipError_t launch_finish(const FinishArgs &a, hipStream_t s)
     if (total > kMaxMergeEntries || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r) return hipErrorInvalidValue;
     FinishKernelArgs fa{a, 2};
     while (fa.sort_cap < total) fa.sort_cap <<= 1;
-    hipLaunchKernelGGL(finish_kernel, dim3((unsigned)a.b), dim3(256), (size_t)fa.sort_cap * sizeof(uint64_t), s, fa);
+    // a block per query: with few queries and long activations use 1024-thread blocks
+    if (a.b <= 1024 && a.d >= 16384 && a.d % 8 == 0)
+        hipLaunchKernelGGL(finish_kernel<1024>, dim3((unsigned)a.b), dim3(1024), (size_t)fa.sort_cap * sizeof(uint64_t), s,
+                           fa);
+    else
+        hipLaunchKernelGGL(finish_kernel<256>, dim3((unsigned)a.b), dim3(256), (size_t)fa.sort_cap * sizeof(uint64_t), s,
+                           fa);
     return hipGetLastError();
 }
 

@@ -52,7 +52,7 @@ bool cache_layout(int64_t n, int64_t d, int dtype, CacheLayout *out)
     out->d_pad = round_up(d, kPadD);
     size_t bytes = align_up((size_t)out->n_pad * out->d_pad * 2) + align_up((size_t)out->n_pad * 4) +
                    align_up((size_t)n * 4);
-    if (dtype == FREEZE_F32) bytes += align_up((size_t)n * out->d_pad * 4);
+    bytes += align_up((size_t)n * out->d_pad * (dtype == FREEZE_F32 ? 4 : 2));   // row-major copy for re-scoring
     out->bytes = bytes;
     return true;
 }
@@ -235,7 +235,7 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     fa.n = (int)L.n;
     fa.d = L.d;
     fa.d_pad = L.d_pad;
-    fa.c_bf = L.c_bf;
+    fa.c_rows = L.c_rows;
     fa.c_f32 = L.c_f32;
     fa.labels = L.labels;
     fa.k = k;
@@ -332,10 +332,11 @@ int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entr
     float *norm = st.take<float>((size_t)cl.n_pad);
     int32_t *lab = st.take<int32_t>((size_t)n);
     float *c_f32 = entries_dtype == FREEZE_F32 ? st.take<float>((size_t)n * cl.d_pad) : nullptr;
+    uint16_t *c_rows = entries_dtype == FREEZE_BF16 ? st.take<uint16_t>((size_t)n * cl.d_pad) : nullptr;
 
     LayerCache &L = ctx->layers[layer];
     L.built = false;
-    if (launch_cache_build(entries, entries_dtype, n, d, cl.n_pad, cl.d_pad, c_bf, norm, c_f32, labels, lab,
+    if (launch_cache_build(entries, entries_dtype, n, d, cl.n_pad, cl.d_pad, c_bf, norm, c_f32, c_rows, labels, lab,
                            static_cast<hipStream_t>(stream)) != hipSuccess)
         return FREEZE_EHIP;
     L.n = n;
@@ -348,6 +349,7 @@ int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entr
     L.norm = norm;
     L.labels = lab;
     L.c_f32 = c_f32;
+    L.c_rows = c_rows;
     L.built = true;
     return FREEZE_OK;
 }

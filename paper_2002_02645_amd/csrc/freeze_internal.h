@@ -48,6 +48,7 @@ struct LayerCache {
     const float *norm = nullptr;      // [n_pad] sum of squares of the bf16 row, fp32
     const int32_t *labels = nullptr;  // [n]
     const float *c_f32 = nullptr;     // [n, d_pad] fp32 rows when the cache was given in fp32, else null
+    const uint16_t *c_rows = nullptr; // [n, d_pad] row-major bf16 rows when the cache was given in bf16, else null
 };
 
 // Which distance kernel variant serves a re-scoring width.
@@ -77,7 +78,7 @@ struct DistArgs {
 };
 
 hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t d, int64_t n_pad, int64_t d_pad,
-                              uint16_t *c_bf, float *norm, float *c_f32, const int32_t *labels_in,
+                              uint16_t *c_bf, float *norm, float *c_f32, uint16_t *c_rows, const int32_t *labels_in,
                               int32_t *labels_out, hipStream_t s);
 
 hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
@@ -122,8 +123,8 @@ struct FinishArgs {
     int b;
     int n;                  // cache entries (candidate indices are checked against it)
     int64_t d, d_pad;
-    const uint16_t *c_bf;
-    const float *c_f32;     // non-null: re-score against the fp32 rows
+    const uint16_t *c_rows; // row-major bf16 rows (cache given in bf16)
+    const float *c_f32;     // non-null: re-score against the fp32 rows (cache given in fp32)
     const int32_t *labels;
     int k, vote_threshold;
     int32_t *out_labels;    // [b] (compact order)

@@ -42,13 +42,13 @@ def test_host_side_checks_without_gpu():
     assert L.freeze_create(None, 2) == binding.FREEZE_EINVAL
     assert L.freeze_create(ctypes.byref(h), 2) == binding.FREEZE_OK
     try:
-        # layout arithmetic: bf16 rows padded to 256 entries x 64 elements, norms, labels (+ fp32 rows)
+        # layout arithmetic: tiled bf16 rows padded to 256 entries x 64 elements, norms, labels, row-major copy
         n, d = 1000, 100
         n_pad, d_pad = 1024, 128
         up = lambda x: (x + 255) // 256 * 256
-        bf = up(n_pad * d_pad * 2) + up(n_pad * 4) + up(n * 4)
-        assert L.freeze_cache_storage_bytes(n, d, binding.FREEZE_BF16) == bf
-        assert L.freeze_cache_storage_bytes(n, d, binding.FREEZE_F32) == bf + up(n * d_pad * 4)
+        base = up(n_pad * d_pad * 2) + up(n_pad * 4) + up(n * 4)
+        assert L.freeze_cache_storage_bytes(n, d, binding.FREEZE_BF16) == base + up(n * d_pad * 2)
+        assert L.freeze_cache_storage_bytes(n, d, binding.FREEZE_F32) == base + up(n * d_pad * 4)
         assert L.freeze_cache_storage_bytes(0, d, binding.FREEZE_BF16) == 0
         assert L.freeze_cache_storage_bytes(n, 0, binding.FREEZE_BF16) == 0
         assert L.freeze_cache_storage_bytes(n, d, 7) == 0

@@ -80,6 +80,8 @@ def test_hand_example_on_gpu():
     (3000, 2048, 100, 10, 0, torch.bfloat16),  # one query tile, long activation -> keys-out kernel + selection
     (2500, 4160, 200, 10, 64, torch.float32),  # keys-out, R = 64, fp32 cache, ragged everything
     (1000, 640, 20, 5, 0, torch.bfloat16),     # keys-out with few cache tiles
+    (600, 16384, 40, 10, 0, torch.bfloat16),   # long activation, few queries: 1024-thread finishing blocks
+    (600, 16392, 300, 10, 0, torch.float32),   # fused kernel, fp32 cache, long activation, d not a multiple of 64
 ])
 def test_shapes_against_oracle(n, d, b, k, r, dtype):
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
