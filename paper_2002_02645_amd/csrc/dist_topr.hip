@@ -62,11 +62,11 @@ __device__ __forceinline__ float from_ordered_bits(uint32_t u)
     return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
 }
 
-template <int BM_, int BK_, int RMAX_, int NS_>
+template <int BM_, int BK_, int RMAX_, int NS_, int WN_ = 4>
 struct DistCfg {
     static constexpr int BM = BM_, BN = kTileN, BK = BK_, RMAX = RMAX_;
     static constexpr int NS = NS_;                  // operand stages in LDS (NS - 1 loads in flight)
-    static constexpr int WM = 2, WN = 4;            // wave grid
+    static constexpr int WM = 2, WN = WN_;          // wave grid: 2 x 4 (8 waves) or 2 x 2 (4 waves)
     static constexpr int NWAVES = WM * WN, THREADS = 64 * NWAVES;
     static constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
     static constexpr int NSUB = BK / kKB;           // k-blocks (of 32 elements) per stage
@@ -77,7 +77,7 @@ struct DistCfg {
     static constexpr int NI_B = BN * BK * 2 / 1024 / NWAVES;
     static_assert(BK % kKB == 0, "a stage is a whole number of k-blocks");
     // slab pass: WNS wave columns at a time
-    static constexpr int WNS = (BM * 4 * 32 * 4 <= OP_BYTES) ? 4 : ((BM * 2 * 32 * 4 <= OP_BYTES) ? 2 : 1);
+    static constexpr int WNS = (WN >= 4 && BM * 4 * 32 * 4 <= OP_BYTES) ? 4 : ((WN >= 2 && BM * 2 * 32 * 4 <= OP_BYTES) ? 2 : 1);
     static constexpr int SLABW = WNS * 32;          // keys per row in one slab
     static constexpr bool KEYS = (RMAX == 0);       // no fused selection: write every key (small batches)
     static constexpr int TOP_BYTES = RMAX * BM * 8;
@@ -201,20 +201,29 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
             if (kt + C::NS - 1 < nk) issue((st + C::NS - 1) % C::NS, kt + C::NS - 1);
             const int baseA = st * (C::STAGE_BYTES / 16) + rdA;
             const int baseB = st * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB;
-#pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
-                bf16x8 af[TM], bfr[TN];
+            // Fragments are double buffered in registers: the reads of sub-step kk+1 are issued
+            // before the MFMAs of sub-step kk, so that LDS latency hides behind matrix work.
+            bf16x8 af[2][TM], bfr[2][TN];
+            auto load_frags = [&](int buf, int kk) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    af[i] = smem16[baseA + (kk >> 1) * (BM * 4) + i * 128 + (((kk & 1) << 1) ^ pcxA)];
+                    af[buf][i] = smem16[baseA + (kk >> 1) * (BM * 4) + i * 128 + (((kk & 1) << 1) ^ pcxA)];
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    bfr[j] = smem16[baseB + (kk >> 1) * (BN * 4) + j * 128 + (((kk & 1) << 1) ^ pcxB)];
+                    bfr[buf][j] = smem16[baseB + (kk >> 1) * (BN * 4) + j * 128 + (((kk & 1) << 1) ^ pcxB)];
+            };
+            load_frags(0, 0);
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                if (kk + 1 < BK / 16) load_frags((kk + 1) & 1, kk + 1);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+                // keep the order: next sub-step's LDS reads first, then this sub-step's MFMAs
+                if (kk + 1 < BK / 16) __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
             }
             st = (st + 1 == C::NS) ? 0 : st + 1;
         }
@@ -241,13 +250,13 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                     }
                 }
                 __syncthreads();
-                // half-wave h of wave w copies row it*16 + 2w + h: 32 lanes x 4 keys = the slab's 128 columns
+                // half-wave h of wave w copies row it*2*NWAVES + 2w + h: 32 lanes x 4 keys = the slab's 128 columns
                 const int l32 = lane & 31;
                 const int seg = l32 >> 3;                                   // wave column the 4 keys came from
                 const int gcol = n0 + seg * TN * 32 + bj * 32 + (l32 & 7) * 4;   // entry index of the first key
 #pragma unroll 2
-                for (int it = 0; it < BM / 16; ++it) {
-                    const int row = it * 16 + w * 2 + g;
+                for (int it = 0; it < BM / (2 * C::NWAVES); ++it) {
+                    const int row = it * 2 * C::NWAVES + w * 2 + g;
                     const int grow = mt * BM + row;
                     const f32x4 v = reinterpret_cast<const f32x4 *>(slab + row * C::SLABW)[(l32 ^ row) & (C::SLABW / 4 - 1)];
                     const bool live = grow < nq;
