@@ -1,13 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the cache look-up hot path on one MI355X.
 
-One step = one pass of the whole look-up (query preparation, MFMA distance pass with
-fused top-R, merge + fp32 re-scoring + vote + hit decision) over one batch of synthetic
-queries, with cache, queries and workspace already resident in HBM.
+One step = one pass of the whole look-up (query preparation, MFMA distance pass, selection,
+fp32 re-scoring, vote and hit decision; for the cascade workloads: all layers, with miss
+compaction between them) over one batch of synthetic queries, with caches, queries and
+workspace already resident in HBM.
 
-Prints ONE JSON line: queries/s of the whole look-up, the roofline figures of the
-dominant kernel (the distance pass, timed with HIP events on its own stream inside the
-timed region) and the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: queries/s of the whole look-up, the roofline figures of the dominant
+kernel (the distance pass, timed with HIP events on its own stream inside the timed region)
+and the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -36,7 +37,7 @@ def measured_traffic(kernel: str, workload: str):
     for line in open(path):
         parts = line.split()
         for c in ("FETCH_SIZE", "WRITE_SIZE"):
-            if line.startswith(f"fz::{kernel}") and c in parts:
+            if line.startswith(f"fz::{kernel}") and c in parts and c not in vals:
                 vals[c] = float(parts[parts.index(c) + 1])
             if line.startswith(f"{c} calibration") and "factor" in parts:
                 factor[c] = float(parts[parts.index("factor") + 1])
@@ -74,30 +75,35 @@ def main() -> int:
     torch.cuda.set_device(dev)
 
     wl = synth.WORKLOADS[args.workload]
-    if len(wl.layers) != 1:
-        print("bench.py: single-layer workloads only (the cascade is measured by its own parity/bench test)",
-              file=sys.stderr)
-        return 2
-    spec = wl.layers[0]
+    nl = len(wl.layers)
+    cascade = nl > 1
     t0 = time.time()
     data = synth.make_workload(wl, device=dev)
-    L = data.layers[0]
-    queries = data.queries[0]
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
-    fc = binding.FreezeCache(1, dev)
+    fc = binding.FreezeCache(nl, dev)
     t0 = time.time()
-    fc.build_layer(0, L.entries, L.labels, spec.num_classes)
+    for l, L in enumerate(data.layers):
+        fc.build_layer(l, L.entries, L.labels, L.spec.num_classes)
     torch.cuda.synchronize()
     build_s = time.time() - t0
 
-    b, k, thr, r = wl.batch, wl.k, wl.vote_thresholds[0], wl.rescore_r
-    out = fc.alloc_outputs(b, k)
+    b, k, r = wl.batch, wl.k, wl.rescore_r
+    spec = wl.layers[0]
     stream = torch.cuda.current_stream()
+    if cascade:
+        out = dict(label=torch.empty(b, dtype=torch.int32, device=dev),
+                   exit_layer=torch.empty(b, dtype=torch.int32, device=dev),
+                   hits_per_layer=torch.empty(nl, dtype=torch.int64, device=dev))
 
-    def step():
-        fc.lookup(0, queries, k, thr, r, out=out)
+        def step():
+            fc.lookup_cascade(list(range(nl)), data.queries, k, list(wl.vote_thresholds), r, out=out)
+    else:
+        out = fc.alloc_outputs(b, k)
+
+        def step():
+            fc.lookup(0, data.queries[0], k, wl.vote_thresholds[0], r, out=out)
 
     for _ in range(args.warmup):
         step()
@@ -114,29 +120,64 @@ def main() -> int:
     ev1.record(stream)
     torch.cuda.synchronize()
     wall_s = time.perf_counter() - t0
-    stage_ms, calls = binding.freeze_profile_read(fc.ctx)
+    calls = binding.freeze_profile_read_calls(fc.ctx)
     binding.freeze_profile_enable(fc.ctx, False)
     ms_per_step = wall_s * 1e3 / args.steps
     ev_ms_per_step = ev0.elapsed_time(ev1) / args.steps
     qps = b * args.steps / wall_s
 
-    # roofline of the dominant kernel (distance pass): algorithmic flops = 2 * B * N * d per launch
-    dist_ms = stage_ms[1] / max(calls, 1)
+    # per-layer stage times: the recorded look-ups cycle through the layers
+    per_layer = [[0.0, 0.0, 0.0] for _ in range(nl)]
+    counted = [0] * nl
+    for i, c in enumerate(calls):
+        for j in range(3):
+            per_layer[i % nl][j] += c[j]
+        counted[i % nl] += 1
+    per_layer = [[v / max(counted[l], 1) for v in per_layer[l]] for l in range(nl)]
+
+    # roofline of the dominant kernel: the distance pass of the (first) layer.
+    # algorithmic flops per launch = 2 * B * N * d; algorithmic bytes (small batches) = N * d * 2
+    dist_ms = per_layer[0][1]
     flops = 2.0 * b * spec.n * spec.d
     cache_bytes = float(spec.n) * spec.d * 2
-    if b >= 64:
+    skinny = (not cascade) and b <= 16 and spec.d <= 1024
+    if not skinny:
         achieved = flops / (dist_ms * 1e-3) / 1e12
         roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                         frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None)
+        roofline["hbm_view"] = {"cache_stream_GBs": round(cache_bytes / (dist_ms * 1e-3) / 1e9, 1),
+                                "frac_of_hbm_peak": round(cache_bytes / (dist_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
     else:
         achieved = cache_bytes / (dist_ms * 1e-3) / 1e9
         roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=round(achieved / PEAK_HBM_GBS, 4), traffic=None)
-    roofline["kernel"] = "dist_topr_kernel" if b > 16 or spec.d > 1024 else "dist_skinny_kernel"
-    roofline["traffic"] = measured_traffic(roofline["kernel"], wl.name)
+    roofline["kernel"] = "dist_skinny_kernel" if skinny else "dist_topr_kernel"
     roofline["kernel_ms"] = round(dist_ms, 4)
-    roofline["stage_ms"] = {"query_prep": round(stage_ms[0] / max(calls, 1), 4), "dist_topr": round(dist_ms, 4),
-                            "finish": round(stage_ms[2] / max(calls, 1), 4)}
+    roofline["traffic"] = measured_traffic(roofline["kernel"], wl.name)
+    roofline["stage_ms"] = {"query_prep": round(per_layer[0][0], 4), "dist": round(dist_ms, 4),
+                            "select_rescore_vote": round(per_layer[0][2], 4)}
+
+    config = {"workload": f"{wl.name}: " + ", ".join(f"cache {s.n}x{s.d} {'bf16' if s.store_bf16 else 'fp32'}"
+                                                     for s in wl.layers)
+                          + f", batch {b}, k={k}, vote_thresholds={list(wl.vote_thresholds)}, "
+                            f"rescore_r={r if r else 'default'}",
+              "event_ms_per_step": round(ev_ms_per_step, 4), "cache_build_s": round(build_s, 3),
+              "input_gen_s": round(gen_s, 2)}
+    if cascade:
+        hits = out["hits_per_layer"].cpu().numpy().astype(np.int64)
+        entering = [b]
+        for l in range(nl - 1):
+            entering.append(int(entering[-1] - hits[l]))
+        config["cascade"] = {
+            "hits_per_layer": [int(h) for h in hits],
+            "hit_fraction_of_entering": [round(float(hits[l]) / max(entering[l], 1), 4) for l in range(nl)],
+            "entering_per_layer": entering,
+            "fell_through": int(b - hits.sum()),
+            "layer_stage_ms": [{"query_prep": round(p[0], 4), "dist": round(p[1], 4),
+                                "select_rescore_vote": round(p[2], 4)} for p in per_layer],
+            "layer_dist_tflops": [round(2.0 * entering[l] * wl.layers[l].n * wl.layers[l].d
+                                        / max(per_layer[l][1] * 1e-3, 1e-9) / 1e12, 1) for l in range(nl)],
+        }
 
     result = {
         "metric": "queries/sec per layer lookup",
@@ -151,48 +192,55 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"{wl.name}: cache {spec.n}x{spec.d} bf16, batch {b}, k={k}, "
-                               f"vote_threshold={thr}, rescore_r={r if r else 'default'}",
-                   "event_ms_per_step": round(ev_ms_per_step, 4), "cache_build_s": round(build_s, 3),
-                   "input_gen_s": round(gen_s, 2)},
+        "config": config,
         "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
         from oracle import freeze_oracle as fo
-        sample = args.cpu_sample or {"c2_batched": 128, "c3_wide": 16, "c1_tiny": 256}.get(wl.name, min(b, 64))
-        sample = min(sample, b)
+        default_sample = {"c2_batched": 128, "c3_wide": 16, "c1_tiny": 256, "c4_cascade": 16, "c4_cascade_noisy": 16}
+        sample = min(args.cpu_sample or default_sample.get(wl.name, min(b, 64)), b)
         g = torch.Generator().manual_seed(wl.seed + 999)
         pick = torch.randperm(b, generator=g)[:sample].sort().values
-        q_h = queries[pick.to(dev)].cpu().numpy()
-        e_h = synth.bf16_bits(L.entries) if L.entries.dtype == torch.bfloat16 else L.entries.cpu().numpy()
-        l_h = L.labels.cpu().numpy()
-        t0 = time.perf_counter()
-        kk = min(k + 1, spec.n)   # one extra neighbour: tells a near-tie at the k-th place
-        o_idx, o_dist, o_threads = fo.knn(q_h, e_h, kk)
-        o_lab, o_votes, o_hit = fo.vote(l_h, o_idx[:, :k], spec.num_classes, thr)
-        cpu_s = time.perf_counter() - t0
-        ref = dict(idx=o_idx[:, :k], sqdist=o_dist, hit=o_hit, threads=o_threads)
-        result["cpu_baseline"] = {"value": round(sample / cpu_s, 3), "unit": "queries/s", "cores": int(ref["threads"]),
-                                  "kind": "oracle",
-                                  "sample": f"{sample} of the {b} queries (seeded subset) against the full cache, "
-                                            f"{cpu_s:.1f} s"}
-        # the sample doubles as a parity spot check of the timed configuration
-        got_idx = out["idx"][pick.to(dev)].cpu().numpy()
-        got_hit = out["hit"][pick.to(dev)].cpu().numpy()
-        gaps = np.diff(ref["sqdist"], axis=1) / np.maximum(ref["sqdist"][:, 1:], 1e-30)
-        differ = (got_idx != ref["idx"]).any(axis=1)
-        unexplained = int((differ & ~(gaps < 1e-4).any(axis=1)).sum())
-        result["config"]["parity_sample"] = {"queries": int(sample), "identical": int((~differ).sum()),
-                                             "differ_outside_near_tie": unexplained,
-                                             "hit_equal": int((got_hit == ref["hit"]).sum())}
+        host_entries = [synth.bf16_bits(L.entries) if L.entries.dtype == torch.bfloat16 else L.entries.cpu().numpy()
+                        for L in data.layers]
+        host_labels = [L.labels.cpu().numpy() for L in data.layers]
+        host_q = [q[pick.to(dev)].cpu().numpy() for q in data.queries]
+        if cascade:
+            t0 = time.perf_counter()
+            o_lab, o_exit, _, o_threads = fo.cascade(host_q, host_entries, host_labels,
+                                                     [L.spec.num_classes for L in data.layers], k, wl.vote_thresholds)
+            cpu_s = time.perf_counter() - t0
+            got_exit = out["exit_layer"][pick.to(dev)].cpu().numpy()
+            got_lab = out["label"][pick.to(dev)].cpu().numpy()
+            config["parity_sample"] = {"requests": int(sample),
+                                       "exit_layer_equal": int((got_exit == o_exit).sum()),
+                                       "label_equal": int((got_lab == o_lab).sum())}
+            what = f"{sample} of the {b} requests (seeded subset) through the oracle's cascade"
+        else:
+            t0 = time.perf_counter()
+            kk = min(k + 1, spec.n)   # one extra neighbour: tells a near-tie at the k-th place
+            o_idx, o_dist, o_threads = fo.knn(host_q[0], host_entries[0], kk)
+            o_lab, o_votes, o_hit = fo.vote(host_labels[0], o_idx[:, :k], spec.num_classes, wl.vote_thresholds[0])
+            cpu_s = time.perf_counter() - t0
+            got_idx = out["idx"][pick.to(dev)].cpu().numpy()
+            got_hit = out["hit"][pick.to(dev)].cpu().numpy()
+            gaps = np.diff(o_dist, axis=1) / np.maximum(o_dist[:, 1:], 1e-30)
+            differ = (got_idx != o_idx[:, :k]).any(axis=1)
+            config["parity_sample"] = {"queries": int(sample), "identical": int((~differ).sum()),
+                                       "differ_outside_near_tie": int((differ & ~(gaps < 1e-4).any(axis=1)).sum()),
+                                       "hit_equal": int((got_hit == o_hit).sum())}
+            what = f"{sample} of the {b} queries (seeded subset) against the full cache"
+        result["cpu_baseline"] = {"value": round(sample / cpu_s, 3), "unit": "queries/s", "cores": int(o_threads),
+                                  "kind": "oracle", "sample": f"{what}, {cpu_s:.1f} s"}
+
     if args.copy_calibration:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
             torch.bitwise_not(src, out=dst)   # a plain elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
-        result["config"]["copy_calibration_bytes"] = 1 << 30
+        config["copy_calibration_bytes"] = 1 << 30
     fc.close()
     print(json.dumps(result))
     return 0

@@ -156,6 +156,9 @@ int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t cou
 #define FREEZE_PROFILE_MAX_CALLS 256
 int freeze_profile_enable(freeze_ctx *ctx, int enable);
 int freeze_profile_read(freeze_ctx *ctx, float *stage_ms, int *calls);
+/* Same, per look-up: call_ms is a host array [max_calls][3], filled in call order (a cascade
+ * records one look-up per layer); *calls = number of rows written.  Clears the record. */
+int freeze_profile_read_calls(freeze_ctx *ctx, float *call_ms, int max_calls, int *calls);
 
 /* Static description of an error code (host string, never NULL). */
 const char *freeze_strerror(int code);

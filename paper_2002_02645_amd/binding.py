@@ -60,6 +60,8 @@ def lib():
     L.freeze_profile_enable.argtypes = [p, i32]
     L.freeze_profile_read.restype = i32
     L.freeze_profile_read.argtypes = [p, p, p]
+    L.freeze_profile_read_calls.restype = i32
+    L.freeze_profile_read_calls.argtypes = [p, p, i32, p]
     L.freeze_strerror.restype = ctypes.c_char_p
     L.freeze_strerror.argtypes = [i32]
     _lib = L
@@ -169,6 +171,16 @@ def freeze_profile_read(ctx):
                                                                                      ctypes.c_void_p)),
            "freeze_profile_read")
     return [float(x) for x in ms], int(calls.value)
+
+
+def freeze_profile_read_calls(ctx, max_calls: int = 256):
+    """Returns a list of [prep_ms, dist_ms, finish_ms], one per recorded look-up, in call order."""
+    ms = (ctypes.c_float * (3 * max_calls))()
+    calls = ctypes.c_int(0)
+    _check(lib().freeze_profile_read_calls(ctx, ctypes.cast(ms, ctypes.c_void_p), max_calls,
+                                           ctypes.cast(ctypes.byref(calls), ctypes.c_void_p)),
+           "freeze_profile_read_calls")
+    return [[float(ms[3 * c + i]) for i in range(3)] for c in range(calls.value)]
 
 
 # ---- convenience holder: owns the context, the per-layer storage and a reusable workspace ---------

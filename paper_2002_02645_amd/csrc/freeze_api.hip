@@ -491,6 +491,22 @@ int freeze_profile_read(freeze_ctx *ctx, float *stage_ms, int *calls)
     return FREEZE_OK;
 }
 
+int freeze_profile_read_calls(freeze_ctx *ctx, float *call_ms, int max_calls, int *calls)
+{
+    if (!ctx || !call_ms || !calls || max_calls < 0) return FREEZE_EINVAL;
+    const int n = ctx->profiled_calls < max_calls ? ctx->profiled_calls : max_calls;
+    for (int c = 0; c < n; ++c) {
+        if (hipEventSynchronize(ctx->events[4 * c + 3]) != hipSuccess) return FREEZE_EHIP;
+        for (int i = 0; i < 3; ++i)
+            if (hipEventElapsedTime(&call_ms[3 * c + i], ctx->events[4 * c + i], ctx->events[4 * c + i + 1]) !=
+                hipSuccess)
+                return FREEZE_EHIP;
+    }
+    *calls = n;
+    ctx->profiled_calls = 0;
+    return FREEZE_OK;
+}
+
 const char *freeze_strerror(int code)
 {
     switch (code) {
