@@ -314,7 +314,10 @@ __global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
     const int r = a.r;
 
     // 1. merge the per-split lists (or sort the query's candidate list)
-    int total = a.n_splits * r, stride = total;
+    int n_splits = a.n_splits;
+    if (a.count && !a.part_count)   // cascade: the distance pass derived its splits from the live count
+        n_splits = splits_for((nq + a.bm - 1) / a.bm, a.n_tiles, a.num_cus, a.max_splits);
+    int total = n_splits * r, stride = a.alloc_splits * r;
     if (a.part_count) {
         stride = a.part_stride;
         total = a.part_count[q] < stride ? a.part_count[q] : stride;
@@ -407,7 +410,7 @@ __global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
 
 hipError_t launch_finish(const FinishArgs &a, hipStream_t s)
 {
-    const int total = a.part_count ? a.part_stride : a.n_splits * a.r;
+    const int total = a.part_count ? a.part_stride : a.alloc_splits * a.r;
     if (total > kMaxMergeEntries || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r) return hipErrorInvalidValue;
     FinishKernelArgs fa{a, 2};
     while (fa.sort_cap < total) fa.sort_cap <<= 1;

@@ -98,7 +98,7 @@ struct DistKernelArgs {
     const int32_t *count;
     int b, n, d_pad;
     int n_tiles, n_splits, r;
-    int units;   // m_tiles * n_splits
+    int alloc_splits, max_splits, num_cus;
     // keys-out variant only:
     float *keys;      // [b_pad, n_pad]
     uint64_t *bmin;   // [b_pad, n_pad / 32]
@@ -118,19 +118,24 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = w / C::WN, wn = w % C::WN;
 
+    // How many query tiles are live decides the number of splits (on the device when the count
+    // lives there); workgroups beyond live tiles x splits have nothing to do.
+    const int nq = p.count ? *p.count : p.b;
+    const int live_mt = (nq + BM - 1) / BM;
+    const int n_splits = p.count ? splits_for(live_mt, p.n_tiles, p.num_cus, p.max_splits) : p.n_splits;
+    const int units = live_mt * n_splits;
+    if ((int)blockIdx.x >= units) return;   // uniform per workgroup, before any barrier
     // XCD-aware unit numbering: blocks with equal (id % 8) run on one XCD; give them a contiguous
     // range of units.  units = 8a + rem: XCD x owns a (+1 if x < rem) consecutive units.
     int unit;
     {
-        const int g = p.units, a = g >> 3, rem = g & 7;
+        const int a = units >> 3, rem = units & 7;
         const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
         unit = x * a + (x < rem ? x : rem) + j;
     }
-    const int mt = unit / p.n_splits, sp = unit % p.n_splits;
-    const int nq = p.count ? *p.count : p.b;
-    if (mt * BM >= nq) return;   // uniform per workgroup, before any barrier
-    const int nt0 = (int)(((int64_t)sp * p.n_tiles) / p.n_splits);
-    const int nt1 = (int)(((int64_t)(sp + 1) * p.n_tiles) / p.n_splits);
+    const int mt = unit / n_splits, sp = unit % n_splits;
+    const int nt0 = (int)(((int64_t)sp * p.n_tiles) / n_splits);
+    const int nt1 = (int)(((int64_t)(sp + 1) * p.n_tiles) / n_splits);
     const int r = p.r;
 
     // per-row selection state lives with thread t (< BM)
@@ -355,7 +360,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     }
 
     if (!C::KEYS && tid < BM) {
-        uint64_t *dst = p.part + (((size_t)mt * BM + tid) * p.n_splits + sp) * r;
+        uint64_t *dst = p.part + (((size_t)mt * BM + tid) * p.alloc_splits + sp) * r;
 #pragma unroll
         for (int i = 0; i < C::RMAX; ++i)
             if (i < r) dst[i] = top[i * BM + tid];
@@ -372,26 +377,17 @@ DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out)
     if (pl.m_tiles < 1) pl.m_tiles = 1;
     pl.n_tiles = (int)((n + kTileN - 1) / kTileN);
     pl.b_pad = (int64_t)pl.m_tiles * pl.bm;
-    // Choose the number of splits.  More splits fill the CUs more evenly, but every split restarts
-    // its top-R lists from scratch and adds entries to the merge, so take the FEWEST splits whose
-    // CU fill (over whole rounds of workgroups) is within 10% of the best achievable.
-    const int max_splits = (keys_out || pl.n_tiles < kMaxMergeEntries / r) ? pl.n_tiles : kMaxMergeEntries / r;
-    const double total = (double)pl.m_tiles * pl.n_tiles;
-    auto fill = [&](int s) {
-        const int64_t units = (int64_t)pl.m_tiles * s;
-        const int64_t rounds = (units + num_cus - 1) / num_cus;
-        const int tiles_per_unit = (pl.n_tiles + s - 1) / s;
-        return total / ((double)rounds * num_cus * tiles_per_unit);
-    };
-    double best_eff = 0.0;
-    for (int s = 1; s <= max_splits; ++s) best_eff = fill(s) > best_eff ? fill(s) : best_eff;
-    int best_s = 1;
-    for (int s = 1; s <= max_splits; ++s)
-        if (fill(s) >= 0.9 * best_eff) {
-            best_s = s;
-            break;
-        }
-    pl.n_splits = best_s;
+    pl.num_cus = num_cus;
+    pl.max_splits = keys_out ? pl.n_tiles : kMaxMergeEntries / r;
+    pl.n_splits = splits_for(pl.m_tiles, pl.n_tiles, num_cus, pl.max_splits);
+    // a cascade may run this plan with any live count from 1 tile to all of them
+    pl.alloc_splits = pl.n_splits;
+    pl.grid_units = pl.m_tiles * pl.n_splits;
+    for (int live = 1; live < pl.m_tiles; ++live) {
+        const int s = splits_for(live, pl.n_tiles, num_cus, pl.max_splits);
+        if (s > pl.alloc_splits) pl.alloc_splits = s;
+        if (live * s > pl.grid_units) pl.grid_units = live * s;
+    }
     return pl;
 }
 
@@ -410,11 +406,14 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
     k.n_tiles = plan.n_tiles;
     k.n_splits = plan.n_splits;
     k.r = plan.r;
-    k.units = plan.m_tiles * plan.n_splits;
+    k.alloc_splits = a.count ? plan.alloc_splits : plan.n_splits;
+    k.max_splits = plan.max_splits;
+    k.num_cus = plan.num_cus;
+    const int grid = a.count ? plan.grid_units : plan.m_tiles * plan.n_splits;
     k.keys = a.keys;
     k.bmin = a.bmin;
     k.n_pad = (int64_t)plan.n_tiles * kTileN;
-    hipLaunchKernelGGL((dist_topr_kernel<C>), dim3(k.units), dim3(C::THREADS), 0, s, k);
+    hipLaunchKernelGGL((dist_topr_kernel<C>), dim3(grid), dim3(C::THREADS), 0, s, k);
     return hipGetLastError();
 }
 

@@ -100,7 +100,7 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
         if (out->keys)
             out->ws_bytes += select_workspace_bytes(out->plan.b_pad, L.n_pad, r, kAlign);
         else
-            out->ws_bytes += align_up((size_t)out->plan.b_pad * out->plan.n_splits * r * 8);
+            out->ws_bytes += align_up((size_t)out->plan.b_pad * (cascade ? out->plan.alloc_splits : out->plan.n_splits) * r * 8);
     }
     return true;
 }
@@ -218,11 +218,17 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
             fa.part_stride = 32 * sh.r;
             fa.n_splits = 1;
         } else {
-            uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * sh.plan.n_splits * sh.r);
+            const int alloc = count ? sh.plan.alloc_splits : sh.plan.n_splits;
+            uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * alloc * sh.r);
             da.part = part;
             if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
             fa.part = part;
             fa.n_splits = sh.plan.n_splits;
+            fa.alloc_splits = alloc;
+            fa.bm = sh.plan.bm;
+            fa.n_tiles = sh.plan.n_tiles;
+            fa.num_cus = sh.plan.num_cus;
+            fa.max_splits = sh.plan.max_splits;
         }
     }
     if (!marked2) marks.mark(2);

@@ -51,6 +51,36 @@ struct LayerCache {
     const uint16_t *c_rows = nullptr; // [n, d_pad] row-major bf16 rows when the cache was given in bf16, else null
 };
 
+// Number of splits of the cache tiles for `live_mt` live query tiles.  Units (query tile, split)
+// run one per CU in rounds of num_cus; every split restarts its top-R lists and adds entries to
+// the merge, so among the candidates s_j = floor(j * num_cus / live_mt), j = 1..4 (j rounds of
+// workgroups), take the first, and a later one only if it fills the CUs more than 10% better
+// (measured on C2: at equal fill, 12 and 19 splits are 12-15% slower than 6).  Evaluated
+// identically on the host (sizing) and on the device (cascade: the live count is only known there).
+__host__ __device__ inline int splits_for(int live_mt, int n_tiles, int num_cus, int max_splits)
+{
+    if (live_mt < 1) return 1;
+    const int cap = n_tiles < max_splits ? n_tiles : max_splits;
+    int best_s = 1;
+    long long best_num = 0, best_den = 1;   // fill = num / den
+    for (int j = 1; j <= 4; ++j) {
+        int s = (int)(((long long)j * num_cus) / live_mt);
+        if (s < 1) s = 1;
+        if (s > cap) s = cap;
+        const long long units = (long long)live_mt * s;
+        const long long rounds = (units + num_cus - 1) / num_cus;
+        const long long tiles_per_unit = (n_tiles + s - 1) / s;
+        const long long num = (long long)live_mt * n_tiles;
+        const long long den = rounds * num_cus * tiles_per_unit;
+        if (best_num == 0 || num * best_den * 10 > best_num * den * 11) {   // > 10% better fill
+            best_num = num;
+            best_den = den;
+            best_s = s;
+        }
+    }
+    return best_s;
+}
+
 // Which distance kernel variant serves a re-scoring width.
 struct DistPlan {
     int variant;    // 0: R<=16, 1: R<=32, 2: R<=64 (fused top-R); 3: keys-out (selection by separate kernels)
@@ -58,7 +88,11 @@ struct DistPlan {
     int r;          // entries kept per (query, split)
     int m_tiles;    // ceil(b / bm)
     int n_tiles;    // ceil(n / kTileN)
-    int n_splits;   // ranges of cache tiles scanned by separate workgroups
+    int n_splits;   // ranges of cache tiles scanned by separate workgroups (for all m_tiles live)
+    int alloc_splits;   // largest n_splits over every possible live count (stride of the lists)
+    int grid_units;     // largest live_mt * n_splits over every possible live count (grid size)
+    int max_splits;     // cap on n_splits (merge capacity)
+    int num_cus;
     int64_t b_pad;  // m_tiles * bm
 };
 
@@ -68,7 +102,7 @@ struct DistArgs {
     const uint16_t *q_bf;   // b_pad x d_pad, tiled layout (tiles of plan.bm rows)
     const uint16_t *c_bf;   // n_pad x d_pad, tiled layout (tiles of kTileN rows)
     const float *norm;      // [n_pad]
-    uint64_t *part;         // [b_pad, n_splits, r] packed (ordered key, index) (fused variants)
+    uint64_t *part;         // [b_pad, alloc_splits, r] packed (ordered key, index) (fused variants)
     float *keys;            // [b_pad, n_pad] every key (keys-out variant)
     uint64_t *bmin;         // [b_pad, n_pad / 32] block minima (keys-out variant)
     const int32_t *count;   // device: number of live queries, or null (= b)
@@ -113,10 +147,13 @@ hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s);   // keys
 hipError_t launch_skinny_select(const SkinnyLaunch &a, hipStream_t s);   // threshold + candidate lists
 
 struct FinishArgs {
-    const uint64_t *part;   // [b_pad, n_splits, r]; or, with part_count, [b, part_stride] candidate lists
+    const uint64_t *part;   // [b_pad, alloc_splits, r]; or, with part_count, [b, part_stride] candidate lists
     const int32_t *part_count;   // device: entries per query in `part` (null: n_splits * r each)
     int part_stride;
     int n_splits, r;
+    int alloc_splits;            // stride (in lists) between queries in `part`
+    // with a device-side live count the number of splits is re-derived from it (splits_for):
+    int bm, n_tiles, num_cus, max_splits;
     const float *queries;   // [*, d] fp32 (original batch)
     const int32_t *sel;     // compact position -> row of `queries`, or null
     const int32_t *count;   // device live-query count or null
