@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c2_batched")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (profiling runs)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="queries in the oracle sample (0 = per workload)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also measure what this GPU sustains on a pure MFMA loop and on a pure 1 GiB read")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -234,6 +236,15 @@ def main() -> int:
         result["cpu_baseline"] = {"value": round(sample / cpu_s, 3), "unit": "queries/s", "cores": int(o_threads),
                                   "kind": "oracle", "sample": f"{what}, {cpu_s:.1f} s"}
 
+    if args.calibrate:
+        scratch = torch.empty(1 << 22, dtype=torch.uint8, device=dev)
+        tf, mhz = binding.freeze_calibrate_mfma(scratch)
+        buf = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        gbs = binding.freeze_calibrate_hbm_read(buf)
+        del buf
+        result["calibration"] = {"peaks_used": {"bf16_mfma_TFLOPs": PEAK_BF16_TFLOPS, "hbm_GBs": PEAK_HBM_GBS},
+                                 "pure_mfma_loop_TFLOPs": round(tf, 1), "shader_clock_MHz_under_mfma": round(mhz),
+                                 "pure_read_1GiB_GBs": round(gbs, 1)}
     if args.copy_calibration:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
         dst = torch.empty_like(src)

@@ -101,7 +101,8 @@ size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b
  *                  in fp32 (exactly 0 for an entry identical to the query).
  *   workspace      >= freeze_lookup_workspace_bytes() bytes, 256-byte aligned;
  *                  scratch only, contents undefined afterwards.
- * b == 0 is a no-op.  Calls that share a workspace must be ordered on one stream.
+ * b == 0 is a no-op (the data pointers may then be NULL).  Calls that share a workspace must
+ * be ordered on one stream.
  */
 int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k, int vote_threshold,
                   int rescore_r, int32_t *out_labels, uint8_t *out_hit, int32_t *out_votes,
@@ -159,6 +160,19 @@ int freeze_profile_read(freeze_ctx *ctx, float *stage_ms, int *calls);
 /* Same, per look-up: call_ms is a host array [max_calls][3], filled in call order (a cascade
  * records one look-up per layer); *calls = number of rows written.  Clears the record. */
 int freeze_profile_read_calls(freeze_ctx *ctx, float *call_ms, int max_calls, int *calls);
+
+/*
+ * Calibration microbenchmarks for benchmarks (they synchronise the device; default stream).
+ * freeze_calibrate_mfma: back-to-back bf16 32x32x16 MFMAs from registers on every CU.
+ *   scratch        device buffer, 8-byte aligned, >= 2 MiB; contents overwritten.
+ *   tflops         host out: sustained dense bf16 rate in TFLOP/s.
+ *   shader_mhz     host out: shader clock held under that load, in MHz.
+ * freeze_calibrate_hbm_read: reads every byte of `buffer` (device, 16-byte aligned, >= 1 MiB,
+ *   initialised by the caller, not modified for any realistic content) five times.
+ *   gbytes_per_s   host out: sustained read rate in GB/s.
+ */
+int freeze_calibrate_mfma(void *scratch, size_t scratch_bytes, double *tflops, double *shader_mhz);
+int freeze_calibrate_hbm_read(const void *buffer, size_t bytes, double *gbytes_per_s);
 
 /* Static description of an error code (host string, never NULL). */
 const char *freeze_strerror(int code);

@@ -62,6 +62,10 @@ def lib():
     L.freeze_profile_read.argtypes = [p, p, p]
     L.freeze_profile_read_calls.restype = i32
     L.freeze_profile_read_calls.argtypes = [p, p, i32, p]
+    L.freeze_calibrate_mfma.restype = i32
+    L.freeze_calibrate_mfma.argtypes = [p, sz, p, p]
+    L.freeze_calibrate_hbm_read.restype = i32
+    L.freeze_calibrate_hbm_read.argtypes = [p, sz, p]
     L.freeze_strerror.restype = ctypes.c_char_p
     L.freeze_strerror.argtypes = [i32]
     _lib = L
@@ -181,6 +185,24 @@ def freeze_profile_read_calls(ctx, max_calls: int = 256):
                                            ctypes.cast(ctypes.byref(calls), ctypes.c_void_p)),
            "freeze_profile_read_calls")
     return [[float(ms[3 * c + i]) for i in range(3)] for c in range(calls.value)]
+
+
+def freeze_calibrate_mfma(scratch: torch.Tensor):
+    """Returns (sustained bf16 MFMA TFLOP/s, shader clock in MHz under that load)."""
+    tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().freeze_calibrate_mfma(_ptr(scratch), scratch.numel() * scratch.element_size(),
+                                       ctypes.cast(ctypes.byref(tf), ctypes.c_void_p),
+                                       ctypes.cast(ctypes.byref(mhz), ctypes.c_void_p)), "freeze_calibrate_mfma")
+    return float(tf.value), float(mhz.value)
+
+
+def freeze_calibrate_hbm_read(buffer: torch.Tensor) -> float:
+    """Returns the sustained read rate over `buffer` in GB/s."""
+    gbs = ctypes.c_double(0.0)
+    _check(lib().freeze_calibrate_hbm_read(_ptr(buffer), buffer.numel() * buffer.element_size(),
+                                           ctypes.cast(ctypes.byref(gbs), ctypes.c_void_p)),
+           "freeze_calibrate_hbm_read")
+    return float(gbs.value)
 
 
 # ---- convenience holder: owns the context, the per-layer storage and a reusable workspace ---------

@@ -1,0 +1,120 @@
+// Calibration microbenchmarks (measurement aids, not part of the look-up): what this GPU
+// sustains on the two roofs the look-up kernels are priced against.
+//  - pure MFMA: every wave issues back-to-back, independent v_mfma_f32_32x32x16_bf16 from
+//    registers (no memory traffic at all); also reports the shader clock the chip holds
+//    under that load (shader-clock counter against the 100 MHz real-time counter);
+//  - pure read: every byte of a buffer is read once with 16-byte loads (grid-stride).
+// Both synchronise the device: they are for benchmarks, not for the serving path.
+#include "../../include/freeze.h"
+
+#include <hip/hip_runtime.h>
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__global__ __launch_bounds__(512) void mfma_peak_kernel(float *out, unsigned long long *clk, int iters)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        clk[0] = clock64();
+        clk[1] = wall_clock64();
+    }
+    bf16x8 a, b;
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(0.001f * (float)(threadIdx.x + i));
+        b[i] = (__bf16)(0.002f * (float)(threadIdx.x ^ i));
+    }
+    f32x16 acc[8];
+    for (int j = 0; j < 8; ++j)
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int j = 0; j < 8; ++j)
+        for (int e = 0; e < 16; ++e) s += acc[j][e];
+    out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        clk[2] = clock64();
+        clk[3] = wall_clock64();
+    }
+}
+
+__global__ __launch_bounds__(256) void read_kernel(const uint4 *__restrict__ p, size_t n16, unsigned *sink)
+{
+    unsigned s = 0;
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        s += a.x ^ b.y ^ c.z ^ d.w;
+    }
+    for (; i < n16; i += stride) s += p[i].x;
+    if (s == 0x12345678u) sink[0] = s;   // keeps the loads alive; practically never true
+}
+
+}  // namespace
+
+extern "C" {
+
+int freeze_calibrate_mfma(void *scratch, size_t scratch_bytes, double *tflops, double *shader_mhz)
+{
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (!scratch || !tflops || !shader_mhz) return FREEZE_EINVAL;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return FREEZE_EHIP;
+    const int cus = prop.multiProcessorCount;
+    const size_t need = (size_t)cus * 512 * sizeof(float) + 4 * sizeof(unsigned long long);
+    if (scratch_bytes < need || (reinterpret_cast<uintptr_t>(scratch) % 8) != 0) return FREEZE_EWORKSPACE;
+    unsigned long long *clk = static_cast<unsigned long long *>(scratch);
+    float *out = reinterpret_cast<float *>(clk + 4);
+    const int iters = 20000;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return FREEZE_EHIP;
+    hipLaunchKernelGGL(mfma_peak_kernel, dim3(cus), dim3(512), 0, nullptr, out, clk, 200);   // warm-up
+    (void)hipEventRecord(e0, nullptr);
+    hipLaunchKernelGGL(mfma_peak_kernel, dim3(cus), dim3(512), 0, nullptr, out, clk, iters);
+    (void)hipEventRecord(e1, nullptr);
+    int rc = FREEZE_OK;
+    float ms = 0.f;
+    unsigned long long h[4] = {0, 0, 0, 0};
+    if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess ||
+        hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess)
+        rc = FREEZE_EHIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != FREEZE_OK) return rc;
+    const double flops = (double)cus * 8.0 /*waves*/ * iters * 8.0 /*mfma*/ * 32768.0;
+    *tflops = flops / (ms * 1e-3) / 1e12;
+    *shader_mhz = (h[3] > h[1]) ? (double)(h[2] - h[0]) / ((double)(h[3] - h[1]) / 100.0) : 0.0;
+    return FREEZE_OK;
+}
+
+int freeze_calibrate_hbm_read(const void *buffer, size_t bytes, double *gbytes_per_s)
+{
+    if (!buffer || !gbytes_per_s || bytes < (1u << 20) || (reinterpret_cast<uintptr_t>(buffer) % 16) != 0)
+        return FREEZE_EINVAL;
+    unsigned *sink = nullptr;   // the kernel writes only in a practically impossible case; use the buffer's start
+    sink = const_cast<unsigned *>(static_cast<const unsigned *>(buffer));
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return FREEZE_EHIP;
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(read_kernel, dim3(2048), dim3(256), 0, nullptr, static_cast<const uint4 *>(buffer), n16, sink);
+    (void)hipEventRecord(e0, nullptr);
+    const int reps = 5;
+    for (int i = 0; i < reps; ++i)
+        hipLaunchKernelGGL(read_kernel, dim3(2048), dim3(256), 0, nullptr, static_cast<const uint4 *>(buffer), n16, sink);
+    (void)hipEventRecord(e1, nullptr);
+    float ms = 0.f;
+    int rc = FREEZE_OK;
+    if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = FREEZE_EHIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != FREEZE_OK) return rc;
+    *gbytes_per_s = (double)(n16 * 16) * reps / (ms * 1e-3) / 1e9;
+    return FREEZE_OK;
+}
+
+}  // extern "C"

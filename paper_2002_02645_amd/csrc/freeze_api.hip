@@ -376,15 +376,15 @@ int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, i
     int err;
     const LayerCache *L = get_layer(ctx, layer, &err);
     if (!L) return err;
-    if (!queries || !out_labels || !out_hit || !out_votes || !out_nbr_idx || !out_nbr_dist || !workspace)
-        return FREEZE_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(queries) % 16) != 0) return FREEZE_EINVAL;
     LookupShape sh;
     if (!lookup_shape(ctx, *L, b, k, rescore_r, false, &sh)) return FREEZE_EINVAL;
     if (vote_threshold < 1 || vote_threshold > k) return FREEZE_EINVAL;
+    if (b == 0) return FREEZE_OK;   // nothing to look up: data pointers may be null
+    if (!queries || !out_labels || !out_hit || !out_votes || !out_nbr_idx || !out_nbr_dist || !workspace)
+        return FREEZE_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(queries) % 16) != 0) return FREEZE_EINVAL;
     if (workspace_bytes < sh.ws_bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
         return FREEZE_EWORKSPACE;
-    if (b == 0) return FREEZE_OK;
     return enqueue_lookup(ctx, *L, sh, queries, nullptr, nullptr, b, k, vote_threshold, out_labels, out_hit, out_votes,
                           out_nbr_idx, out_nbr_dist, workspace, static_cast<hipStream_t>(stream));
 }
@@ -405,10 +405,10 @@ int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers, co
     CascadeLayout cl;
     int err;
     if (!cascade_layout(ctx, num_layers, layers, b, k, rescore_r, &cl, &err)) return err;
-    if (!queries_per_layer || !vote_thresholds || !out_labels || !out_exit_layer || !out_hits_per_layer || !workspace)
-        return FREEZE_EINVAL;
+    if (!queries_per_layer || !vote_thresholds || !out_hits_per_layer || !workspace) return FREEZE_EINVAL;
+    if (b > 0 && (!out_labels || !out_exit_layer)) return FREEZE_EINVAL;
     for (int l = 0; l < num_layers; ++l) {
-        if (!queries_per_layer[l] || (reinterpret_cast<uintptr_t>(queries_per_layer[l]) % 16) != 0)
+        if (b > 0 && (!queries_per_layer[l] || (reinterpret_cast<uintptr_t>(queries_per_layer[l]) % 16) != 0))
             return FREEZE_EINVAL;
         if (vote_thresholds[l] < 1 || vote_thresholds[l] > k) return FREEZE_EINVAL;
     }

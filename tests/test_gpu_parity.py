@@ -233,3 +233,68 @@ def test_argument_errors_launch_nothing():
         torch.cuda.synchronize()
     finally:
         fc.close()
+
+
+def test_empty_batch_and_stage_timing():
+    fc = binding.FreezeCache(2)
+    try:
+        ent = torch.randn(300, 64, device="cuda")
+        lab = torch.zeros(300, dtype=torch.int32, device="cuda")
+        fc.build_layer(0, ent, lab, 2)
+        fc.build_layer(1, ent.to(torch.bfloat16), lab, 2)
+        # b == 0: a no-op that still succeeds
+        q0 = torch.empty((0, 64), dtype=torch.float32, device="cuda")
+        out = fc.lookup(0, q0, 3, 2)
+        assert out["idx"].shape == (0, 3)
+        oc = fc.lookup_cascade([0, 1], [q0, q0], 3, [2, 2])
+        torch.cuda.synchronize()
+        assert oc["hits_per_layer"].tolist() == [0, 0]
+        # stage timing covers exactly the recorded look-ups and clears itself
+        q = torch.randn(40, 64, device="cuda")
+        binding.freeze_profile_enable(fc.ctx, True)
+        fc.lookup(0, q, 3, 2)
+        fc.lookup_cascade([0, 1], [q, q], 3, [3, 3])
+        calls = binding.freeze_profile_read_calls(fc.ctx)
+        assert len(calls) == 3 and all(len(c) == 3 and min(c) >= 0.0 for c in calls)
+        ms, n = binding.freeze_profile_read(fc.ctx)
+        assert n == 0 and ms == [0.0, 0.0, 0.0]
+        binding.freeze_profile_enable(fc.ctx, False)
+        fc.lookup(0, q, 3, 2)
+        assert binding.freeze_profile_read(fc.ctx)[1] == 0
+    finally:
+        fc.close()
+
+
+def test_cascade_single_tile_and_rebuild():
+    # a cascade over few requests (one query tile), and rebuilding a layer replaces its cache
+    got, exp_l, exp_x, exp_h = _cascade_case("c4_cascade_noisy", 700, 128, 9)
+    assert np.array_equal(got["exit_layer"], exp_x) and np.array_equal(got["label"], exp_l)
+    fc = binding.FreezeCache(1)
+    try:
+        a = torch.randn(200, 32, device="cuda")
+        b2 = torch.randn(260, 32, device="cuda") + 5.0
+        lab_a = torch.zeros(200, dtype=torch.int32, device="cuda")
+        lab_b = torch.ones(260, dtype=torch.int32, device="cuda")
+        q = torch.randn(10, 32, device="cuda") + 5.0
+        fc.build_layer(0, a, lab_a, 2)
+        o1 = fc.lookup(0, q, 3, 2)
+        torch.cuda.synchronize()
+        assert (o1["label"] == 0).all()
+        fc.build_layer(0, b2, lab_b, 2)
+        o2 = fc.lookup(0, q, 3, 2)
+        torch.cuda.synchronize()
+        assert (o2["label"] == 1).all() and (o2["idx"] < 260).all()
+    finally:
+        fc.close()
+
+
+def test_calibration_microbenchmarks():
+    scratch = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+    tf, mhz = binding.freeze_calibrate_mfma(scratch)
+    assert 300.0 < tf < 2600.0 and 500.0 < mhz < 3000.0      # below the published 2.5 PFLOP/s, above a tenth of it
+    buf = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
+    gbs = binding.freeze_calibrate_hbm_read(buf)
+    assert 1000.0 < gbs < 8100.0                               # below the published 8 TB/s
+    assert (buf[:64] == 0).all()
+    tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
+    assert binding.lib().freeze_calibrate_mfma(tiny.data_ptr(), 16, None, None) == binding.FREEZE_EINVAL
