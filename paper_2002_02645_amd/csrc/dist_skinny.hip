@@ -18,8 +18,9 @@
 // Paper: Sec. 3 (k nearest neighbours of the layer output), Sec. 5 "Cache lookup
 // performance" (look-up latency decides whether freezing pays off).
 //
-// Streaming kernel: one workgroup per range of 256-entry cache tiles.  The prepared queries
-// (a 32-row block for the matrix cores, rows past the batch zero) stay resident in LDS.  The
+// Streaming kernel: one workgroup per range of 256-entry cache tiles, two workgroups per CU.
+// The prepared queries (16 rows; the matrix cores' other 16 rows are fed zeros from registers)
+// stay resident in LDS.  The
 // cache, stored in the tiled layout ([tile][k-block][row][32 elements]), is one contiguous
 // stream per workgroup: it is copied verbatim into a ring of NS 16 KiB LDS stages with
 // LDS-direct loads, NS-1 stages in flight, and the ring keeps running across tile boundaries.
@@ -57,7 +58,7 @@ __device__ __forceinline__ uint32_t ordered_bits(float x)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-constexpr int kMmaRows = 32;               // rows of the query block fed to the matrix cores
+constexpr int kQRows = kSkinnyRows;        // query rows held in LDS (the MFMA's rows 16..31 are zero registers)
 constexpr int kStage = kTileN * kKB * 2;   // 16 KiB: one k-block of one cache tile
 constexpr int kNormBuf = 2 * 8 * 256;      // 4 KiB: per tile parity and wave, 64 floats
 static_assert(kSkinnyRows <= 16, "queries occupy the first two row groups of the MFMA output");
@@ -65,14 +66,14 @@ static_assert(kSkinnyRows <= 16, "queries occupy the first two row groups of the
 template <int DMAX_, int NS_>
 struct SkinnyCfg {
     static constexpr int DMAX = DMAX_, NS = NS_;
-    static constexpr int A_BYTES = kMmaRows * DMAX * 2;
+    static constexpr int A_BYTES = kQRows * DMAX * 2;
     static constexpr int LDS_BYTES = A_BYTES + kNormBuf + NS * kStage;
-    static_assert(LDS_BYTES <= 163840, "LDS budget");
+    static_assert(LDS_BYTES <= 81920, "two workgroups per CU");
     static_assert(NS >= 2 && NS <= 8, "stages");
 };
 
 struct SkinnyArgs {
-    const uint16_t *q_bf;   // 32 x d_pad (rows >= b zero), tiled layout with 32-row tiles
+    const uint16_t *q_bf;   // 16 x d_pad (rows >= b zero), tiled layout with 16-row tiles
     const uint16_t *c_bf;
     const float *norm;
     float *keys;            // [b, n_pad]
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
     {
         const uint4 *src = reinterpret_cast<const uint4 *>(p.q_bf);
         uint4 *dst = reinterpret_cast<uint4 *>(smem);
-        for (int i = tid; i < kMmaRows * p.d_pad * 2 / 16; i += 512) dst[i] = src[i];
+        for (int i = tid; i < kQRows * p.d_pad * 2 / 16; i += 512) dst[i] = src[i];
     }
     if (total > 0) issue_norms(nt0);
 #pragma unroll
@@ -128,7 +129,8 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
         if (ps < total) issue(ps, ps);
 
     const int g = lane >> 5;
-    const int rowA = lane & 31;
+    const int rowA = lane & 15;              // lanes whose MFMA row is 16..31 supply zeros instead
+    const bool has_q = (lane & 31) < kQRows;
     const int rowB = w * 32 + (lane & 31);
     const int rdA = rowA * 4, pcxA = g ^ tiled_chunk_swizzle(rowA);
     const int rdB = rowB * 4, pcxB = g ^ tiled_chunk_swizzle(rowB);
@@ -157,11 +159,12 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
         if (kb == 0 && nt + 1 < nt1) issue_norms(nt + 1);
         if (gs + C::NS - 1 < total) issue((slot + C::NS - 1) % C::NS, gs + C::NS - 1);
 
-        const int baseA = kb * (kMmaRows * 4) + rdA;
+        const int baseA = kb * (kQRows * 4) + rdA;
         const int baseB = (RING + slot * kStage) / 16 + rdB;
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 af = smem16[baseA + ((kk << 1) ^ pcxA)];
+            bf16x8 af = smem16[baseA + ((kk << 1) ^ pcxA)];
+            if (!has_q) af = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
             const bf16x8 bfr = smem16[baseB + ((kk << 1) ^ pcxB)];
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc, 0, 0, 0);
         }
@@ -378,7 +381,7 @@ size_t select_workspace_bytes(int64_t rows, int64_t n_pad, int r, size_t align)
 int plan_skinny_splits(int64_t n, int num_cus)
 {
     const int n_tiles = (int)((n + kTileN - 1) / kTileN);
-    const int s = num_cus < n_tiles ? num_cus : n_tiles;
+    const int s = 2 * num_cus < n_tiles ? 2 * num_cus : n_tiles;   // two workgroups per CU
     return s < 1 ? 1 : s;
 }
 
@@ -403,9 +406,9 @@ hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
     k.n_tiles = (int)(a.n_pad / kTileN);
     k.n_splits = a.n_splits;
     if (a.d_pad <= 512)
-        hipLaunchKernelGGL((dist_skinny_kernel<SkinnyCfg<512, 7>>), dim3(a.n_splits), dim3(512), 0, s, k);
+        hipLaunchKernelGGL((dist_skinny_kernel<SkinnyCfg<512, 3>>), dim3(a.n_splits), dim3(512), 0, s, k);
     else
-        hipLaunchKernelGGL((dist_skinny_kernel<SkinnyCfg<1024, 5>>), dim3(a.n_splits), dim3(512), 0, s, k);
+        hipLaunchKernelGGL((dist_skinny_kernel<SkinnyCfg<1024, 2>>), dim3(a.n_splits), dim3(512), 0, s, k);
     return hipGetLastError();
 }
 

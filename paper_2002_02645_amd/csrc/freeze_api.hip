@@ -82,12 +82,12 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     if (out->skinny) {
         DistPlan pl{};
         pl.variant = -1;
-        pl.bm = 32;   // the query block fed to the matrix cores
+        pl.bm = kSkinnyRows;   // the query block held by the streaming kernel
         pl.r = r;
         pl.m_tiles = 1;
         pl.n_tiles = (int)(L.n_pad / kTileN);
         pl.n_splits = plan_skinny_splits(L.n, ctx->num_cus);
-        pl.b_pad = 32;
+        pl.b_pad = kSkinnyRows;
         out->plan = pl;
         out->ws_bytes = align_up((size_t)pl.b_pad * L.d_pad * 2) + skinny_workspace_bytes(L.n_pad, r, kAlign);
     } else {

@@ -123,7 +123,7 @@ hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t
 // Small-batch (bandwidth-bound) path: streaming kernel + threshold + filter; the result is a
 // candidate list per query for the finishing kernel.
 struct SkinnyLaunch {
-    const uint16_t *q_bf;   // 32 x d_pad prepared queries (rows >= b zero), tiled with 32-row tiles
+    const uint16_t *q_bf;   // 16 x d_pad prepared queries (rows >= b zero), tiled with 16-row tiles
     const uint16_t *c_bf;
     const float *norm;
     float *keys;            // [b, n_pad] scratch
