@@ -37,11 +37,18 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
 namespace {
 
-__device__ __forceinline__ void load16_global_to_lds(const void *g, uint32_t lds_byte_addr)
+// LDS-direct 16-byte load: lane i reads 16 bytes at sbase + voff (scalar 64-bit base, 32-bit
+// per-lane offset) and they land in LDS at lds_byte_addr + 16 i (M0 = wave-uniform destination).
+__device__ __forceinline__ void load16_global_to_lds(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
 {
-    // M0 carries the wave-uniform LDS destination; lane i lands at +16*i.
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(g)
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
                  : "memory", "m0");
+}
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
 }
 __device__ __forceinline__ void load4_global_to_lds(const void *g, uint32_t lds_byte_addr)
 {
@@ -101,14 +108,14 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
 
     // the cache stream of this workgroup is contiguous: tiles nt0..nt1-1, each kblocks * 16 KiB
-    const unsigned char *stream = reinterpret_cast<const unsigned char *>(p.c_bf) +
-                                  (size_t)nt0 * kTileN * p.d_pad * 2 + w * 1024 + lane * 16;
+    const uint64_t stream = uniform_u64((uint64_t)(uintptr_t)p.c_bf + (size_t)nt0 * kTileN * p.d_pad * 2);
+    const uint32_t lane_off = w * 1024 + lane * 16;
     auto issue = [&](int slot, int gstep) {
         // 16 KiB = 16 wave-instructions of 1 KiB: two per wave
-        const unsigned char *src = stream + (size_t)gstep * kStage;
+        const uint64_t src = stream + (size_t)gstep * kStage;
         const uint32_t dst = smem_base + RING + slot * kStage + w * 1024;
-        load16_global_to_lds(src, dst);
-        load16_global_to_lds(src + 8192, dst + 8192);
+        load16_global_to_lds(src, lane_off, dst);
+        load16_global_to_lds(src + 8192, lane_off, dst + 8192);
     };
     constexpr int LPS = 2;   // loads per wave and stage
     // norms of this wave's 32 entries of tile `t` -> normbuf[t & 1][w][lane] (lanes 32..63 duplicate)

@@ -40,11 +40,19 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
-__device__ __forceinline__ void load16_global_to_lds(const void *g, uint32_t lds_byte_addr)
+// LDS-direct 16-byte load: lane i reads 16 bytes at sbase + voff (scalar 64-bit base, 32-bit
+// per-lane offset: half the address traffic of a 64-bit per-lane pointer) and they land in LDS at
+// lds_byte_addr + 16 i.  M0 carries the wave-uniform LDS destination.
+__device__ __forceinline__ void load16_global_to_lds(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
 {
-    // M0 carries the wave-uniform LDS destination; lane i lands at +16*i.
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_byte_addr), "v"(g)
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
                  : "memory", "m0");
+}
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
 }
 
 // Wait until at most N of this wave's global loads are outstanding (loads complete in order).
@@ -154,8 +162,8 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 
     // Direct loads copy a stage linearly: wave w, instruction i moves the 1 KiB at offset
     // (i * NWAVES + w) * 1024 of the stage's A (or B) image; lane l moves 16 bytes at + 16 l.
-    const unsigned char *gA = reinterpret_cast<const unsigned char *>(p.q_bf) + (size_t)mt * BM * tile_row_bytes +
-                              w * 1024 + lane * 16;
+    const uint64_t gA = uniform_u64((uint64_t)(uintptr_t)p.q_bf + (size_t)mt * BM * tile_row_bytes);
+    const uint32_t lane_off = w * 1024 + lane * 16;
     // fragment read addresses, in 16-byte units relative to the stage's A / B image
     const int g = lane >> 5;
     const int rowA = wm * TM * 32 + (lane & 31);
@@ -166,18 +174,18 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 
     for (int nt = nt0; nt < nt1; ++nt) {
         const int n0 = nt * BN;
-        const unsigned char *gB = reinterpret_cast<const unsigned char *>(p.c_bf) + (size_t)nt * BN * tile_row_bytes +
-                                  w * 1024 + lane * 16;
+        const uint64_t gB = uniform_u64((uint64_t)(uintptr_t)p.c_bf + (size_t)nt * BN * tile_row_bytes);
         auto issue = [&](int stage, int kt) {
             const uint32_t sbase = smem_base + stage * C::STAGE_BYTES + w * 1024;
-            const unsigned char *a = gA + (size_t)kt * C::A_BYTES;
-            const unsigned char *b = gB + (size_t)kt * (BN * BK * 2);
+            const uint64_t a = gA + (size_t)kt * C::A_BYTES;
+            const uint64_t b = gB + (size_t)kt * (BN * BK * 2);
 #pragma unroll
             for (int i = 0; i < C::NI_A; ++i)
-                load16_global_to_lds(a + i * (C::NWAVES * 1024), sbase + i * (C::NWAVES * 1024));
+                load16_global_to_lds(a + i * (C::NWAVES * 1024), lane_off, sbase + i * (C::NWAVES * 1024));
 #pragma unroll
             for (int i = 0; i < C::NI_B; ++i)
-                load16_global_to_lds(b + i * (C::NWAVES * 1024), sbase + C::A_BYTES + i * (C::NWAVES * 1024));
+                load16_global_to_lds(b + i * (C::NWAVES * 1024), lane_off,
+                                     sbase + C::A_BYTES + i * (C::NWAVES * 1024));
         };
 
         f32x16 acc[TM][TN];
