@@ -134,6 +134,53 @@ int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers,
                           size_t workspace_bytes, void *stream);
 
 /*
+ * Look-up under the distance-weighted confidence heuristic of Sec. 3: with m_i of the k
+ * neighbours carrying label i at distances d_1 .. d_{m_i} (d = square root of the reported
+ * squared distance), C_i = (m_i / k) * sum_j 1 / d_j; the label with the largest C_i wins
+ * (equal values -> smaller label id) and its C_i is the confidence.  Pseudocode 1,
+ * FreezeInference: the look-up is a hit iff confidence > threshold (strict).
+ * Arguments as freeze_lookup, except:
+ *   conf_threshold  >= 0 (fp32).
+ *   out_conf        [b] fp32  confidence of the winning label; +inf when one of its
+ *                   neighbours is identical to the query (always a hit).
+ *   out_votes       [b] int32 occurrences m of the winning label.
+ * The sums are formed in fp64 from the fp32 distances in neighbour order and rounded once.
+ */
+int freeze_lookup_confidence(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k,
+                             float conf_threshold, int rescore_r, int32_t *out_labels,
+                             uint8_t *out_hit, float *out_conf, int32_t *out_votes,
+                             int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/*
+ * freeze_lookup_cascade under the confidence rule: position l freezes a request iff its
+ * confidence there is > conf_thresholds[l] (host array [num_layers], each >= 0).  Workspace:
+ * freeze_cascade_workspace_bytes().
+ */
+int freeze_lookup_cascade_confidence(freeze_ctx *ctx, int num_layers, const int *layers,
+                                     const float *const *queries_per_layer, int64_t b, int k,
+                                     const float *conf_thresholds, int rescore_r,
+                                     int32_t *out_labels, int32_t *out_exit_layer,
+                                     int64_t *out_hits_per_layer, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
+/*
+ * Per-layer thresholds from a validation set (Pseudocode 1, ComputeThresholds; Sec. 3.1
+ * "Offline Phase"): every validation item is looked up at every layer under the confidence
+ * rule, and a layer's threshold is the largest confidence of a look-up whose label differs
+ * from the model's own prediction for that item; 0 when no look-up differs.
+ *   queries_per_layer  host array [num_layers] of device pointers, [b, d_l] fp32: the
+ *                      validation items' intermediate outputs.
+ *   model_labels       [b] int32 (device): the label the model predicts for each item.
+ *   out_thresholds     [num_layers] fp32 (device).
+ * Workspace: freeze_cascade_workspace_bytes().  b == 0 gives thresholds of 0.
+ */
+int freeze_compute_thresholds(freeze_ctx *ctx, int num_layers, const int *layers,
+                              const float *const *queries_per_layer, int64_t b, int k,
+                              int rescore_r, const int32_t *model_labels, float *out_thresholds,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Batch reconstruction on its own (Sec. 5): writes to sel_out the entries
  * sel_in[j] (or j itself when sel_in is NULL) with hit[j] == 0, j < count, in
  * order, and their number to *out_count.

@@ -27,7 +27,13 @@
  *   - no layer hits -> label -1, exit layer -1 (the model's own output layer
  *     would decide; the model is outside this path).
  * The distance-weighted confidence of Sec. 3 (C_i = S_i * sum_j 1/d_j) is
- * computed by fz_oracle_confidence for reference.
+ * computed by fz_oracle_confidence; the look-up, cascade and ComputeThresholds
+ * (Pseudocode 1) built on it are in freeze_oracle.py.  Readings for that rule:
+ * d_j is the Euclidean distance (square root of the squared distance); a zero
+ * distance gives +inf, i.e. always a hit; equal confidences -> the smaller
+ * label id; hit iff confidence > threshold (strict, as the pseudocode writes
+ * it), the confidence rounded once to fp32 and compared in fp32; the running
+ * maximum of ComputeThresholds starts at 0.
  */
 #include <math.h>
 #include <pthread.h>

@@ -162,3 +162,55 @@ def cascade(queries: Sequence[np.ndarray], entries: Sequence[np.ndarray], labels
     if used < 0:
         raise ValueError("fz_oracle_cascade: invalid arguments")
     return out_l, out_x, hits, used
+
+
+def lookup_confidence(queries, entries, labels, num_classes, k, conf_threshold, nthreads: int = 0):
+    """Look-up under the paper's distance-weighted confidence (Sec. 3) and the strict float
+    threshold of Pseudocode 1 (FreezeInference: hit iff confidence > threshold).  The confidence
+    is formed in double from the double distances, rounded once to fp32, and compared in fp32.
+    Returns dict(idx, sqdist, label, conf (float32), hit)."""
+    idx, dist, used = knn(queries, entries, k, nthreads)
+    lab, conf = confidence(labels, idx, dist, num_classes)
+    with np.errstate(over="ignore"):
+        conf32 = conf.astype(np.float32)
+    hit = (conf32 > np.float32(conf_threshold)).astype(np.uint8)
+    return dict(idx=idx, sqdist=dist, label=lab, conf=conf32, hit=hit, threads=used)
+
+
+def cascade_confidence(queries: Sequence[np.ndarray], entries: Sequence[np.ndarray], labels: Sequence[np.ndarray],
+                       num_classes: Sequence[int], k: int, thresholds: Sequence[float], nthreads: int = 0):
+    """Pseudocode 1, FreezeInference, under the confidence rule: layers in order, the first layer
+    whose confidence exceeds its threshold ends the request; none -> (-1, -1).
+    Returns (label [b], exit_layer [b], hits_per_layer [L])."""
+    L = len(queries)
+    b = queries[0].shape[0]
+    out_l = np.full(b, -1, dtype=np.int32)
+    out_x = np.full(b, -1, dtype=np.int32)
+    hits = np.zeros(L, dtype=np.int64)
+    per_layer = [lookup_confidence(queries[l], entries[l], labels[l], num_classes[l], k, thresholds[l], nthreads)
+                 for l in range(L)]
+    for i in range(b):
+        for l in range(L):
+            if per_layer[l]["hit"][i]:
+                out_l[i] = per_layer[l]["label"][i]
+                out_x[i] = l
+                hits[l] += 1
+                break
+    return out_l, out_x, hits
+
+
+def compute_thresholds(val_queries: Sequence[np.ndarray], entries: Sequence[np.ndarray],
+                       labels: Sequence[np.ndarray], num_classes: Sequence[int], k: int,
+                       model_labels: np.ndarray, nthreads: int = 0) -> np.ndarray:
+    """Pseudocode 1, ComputeThresholds (Sec. 3.1): per layer, the largest confidence among the
+    validation items whose look-up label differs from the model's label; the running maximum
+    starts at 0 (the paper gives no initial value; confidences are positive).  float32 [L]."""
+    L = len(val_queries)
+    y = np.asarray(model_labels)
+    thr = np.zeros(L, dtype=np.float32)
+    for l in range(L):
+        res = lookup_confidence(val_queries[l], entries[l], labels[l], num_classes[l], k, 0.0, nthreads)
+        for i in range(y.shape[0]):
+            if res["label"][i] != y[i]:
+                thr[l] = max(thr[l], res["conf"][i])
+    return thr

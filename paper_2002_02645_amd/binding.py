@@ -56,6 +56,12 @@ def lib():
     L.freeze_lookup_cascade.argtypes = [p, i32, p, p, i64, i32, p, i32, p, p, p, p, sz, p]
     L.freeze_compact_misses.restype = i32
     L.freeze_compact_misses.argtypes = [p, p, i64, p, p, p]
+    L.freeze_lookup_confidence.restype = i32
+    L.freeze_lookup_confidence.argtypes = [p, i32, p, i64, i32, ctypes.c_float, i32, p, p, p, p, p, p, p, sz, p]
+    L.freeze_lookup_cascade_confidence.restype = i32
+    L.freeze_lookup_cascade_confidence.argtypes = [p, i32, p, p, i64, i32, p, i32, p, p, p, p, sz, p]
+    L.freeze_compute_thresholds.restype = i32
+    L.freeze_compute_thresholds.argtypes = [p, i32, p, p, i64, i32, i32, p, p, p, sz, p]
     L.freeze_profile_enable.restype = i32
     L.freeze_profile_enable.argtypes = [p, i32]
     L.freeze_profile_read.restype = i32
@@ -154,6 +160,55 @@ def freeze_lookup_cascade(ctx, layers: Sequence[int], queries_per_layer: Sequenc
                                        _ptr(out_exit_layer), _ptr(out_hits_per_layer), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(), _stream(stream)),
            "freeze_lookup_cascade")
+
+
+def freeze_lookup_confidence(ctx, layer: int, queries: torch.Tensor, k: int, conf_threshold: float, rescore_r: int,
+                             out_labels: torch.Tensor, out_hit: torch.Tensor, out_conf: torch.Tensor,
+                             out_votes: torch.Tensor, out_nbr_idx: torch.Tensor, out_nbr_dist: torch.Tensor,
+                             workspace: torch.Tensor, stream=None) -> None:
+    assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous() and queries.dim() == 2
+    b = queries.shape[0]
+    _check(lib().freeze_lookup_confidence(ctx, layer, _ptr(queries), b, k, conf_threshold, rescore_r,
+                                          _ptr(out_labels), _ptr(out_hit), _ptr(out_conf), _ptr(out_votes),
+                                          _ptr(out_nbr_idx), _ptr(out_nbr_dist), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+           "freeze_lookup_confidence")
+
+
+def _cascade_arrays(layers, queries_per_layer):
+    nl = len(layers)
+    assert len(queries_per_layer) == nl
+    b = queries_per_layer[0].shape[0]
+    for q in queries_per_layer:
+        assert q.is_cuda and q.dtype == torch.float32 and q.is_contiguous() and q.shape[0] == b
+    larr = (ctypes.c_int * nl)(*layers)
+    qarr = (ctypes.c_void_p * nl)(*[q.data_ptr() for q in queries_per_layer])
+    return nl, b, larr, qarr
+
+
+def freeze_lookup_cascade_confidence(ctx, layers: Sequence[int], queries_per_layer: Sequence[torch.Tensor], k: int,
+                                     conf_thresholds: Sequence[float], rescore_r: int, out_labels: torch.Tensor,
+                                     out_exit_layer: torch.Tensor, out_hits_per_layer: torch.Tensor,
+                                     workspace: torch.Tensor, stream=None) -> None:
+    nl, b, larr, qarr = _cascade_arrays(layers, queries_per_layer)
+    assert len(conf_thresholds) == nl
+    tarr = (ctypes.c_float * nl)(*conf_thresholds)
+    _check(lib().freeze_lookup_cascade_confidence(ctx, nl, larr, qarr, b, k, tarr, rescore_r, _ptr(out_labels),
+                                                  _ptr(out_exit_layer), _ptr(out_hits_per_layer), _ptr(workspace),
+                                                  workspace.numel() * workspace.element_size(), _stream(stream)),
+           "freeze_lookup_cascade_confidence")
+
+
+def freeze_compute_thresholds(ctx, layers: Sequence[int], queries_per_layer: Sequence[torch.Tensor], k: int,
+                              rescore_r: int, model_labels: torch.Tensor, out_thresholds: torch.Tensor,
+                              workspace: torch.Tensor, stream=None) -> None:
+    nl, b, larr, qarr = _cascade_arrays(layers, queries_per_layer)
+    assert model_labels.is_cuda and model_labels.dtype == torch.int32 and model_labels.numel() == b
+    assert out_thresholds.is_cuda and out_thresholds.dtype == torch.float32 and out_thresholds.numel() == nl
+    _check(lib().freeze_compute_thresholds(ctx, nl, larr, qarr, b, k, rescore_r, _ptr(model_labels),
+                                           _ptr(out_thresholds), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream(stream)),
+           "freeze_compute_thresholds")
 
 
 def freeze_compact_misses(hit: torch.Tensor, sel_in: Optional[torch.Tensor], sel_out: torch.Tensor,
@@ -269,3 +324,40 @@ class FreezeCache:
         freeze_lookup_cascade(self.ctx, layers, queries_per_layer, k, vote_thresholds, rescore_r, out["label"],
                               out["exit_layer"], out["hits_per_layer"], ws)
         return out
+
+    def lookup_confidence(self, layer: int, queries: torch.Tensor, k: int, conf_threshold: float, rescore_r: int = 0,
+                          out: Optional[dict] = None) -> dict:
+        b = queries.shape[0]
+        if out is None:
+            out = self.alloc_outputs(b, k)
+            out["conf"] = torch.empty(b, dtype=torch.float32, device=self.device)
+        nbytes = freeze_lookup_workspace_bytes(self.ctx, layer, b, k, rescore_r)
+        ws = self._workspace(nbytes)
+        freeze_lookup_confidence(self.ctx, layer, queries, k, conf_threshold, rescore_r, out["label"], out["hit"],
+                                 out["conf"], out["votes"], out["idx"], out["dist"], ws)
+        return out
+
+    def lookup_cascade_confidence(self, layers: Sequence[int], queries_per_layer: List[torch.Tensor], k: int,
+                                  conf_thresholds: Sequence[float], rescore_r: int = 0) -> dict:
+        b = queries_per_layer[0].shape[0]
+        out = dict(label=torch.empty(b, dtype=torch.int32, device=self.device),
+                   exit_layer=torch.empty(b, dtype=torch.int32, device=self.device),
+                   hits_per_layer=torch.empty(len(layers), dtype=torch.int64, device=self.device))
+        nbytes = freeze_cascade_workspace_bytes(self.ctx, layers, b, k, rescore_r)
+        if nbytes == 0:
+            raise FreezeError(FREEZE_EINVAL, "freeze_cascade_workspace_bytes")
+        ws = self._workspace(nbytes)
+        freeze_lookup_cascade_confidence(self.ctx, layers, queries_per_layer, k, conf_thresholds, rescore_r,
+                                         out["label"], out["exit_layer"], out["hits_per_layer"], ws)
+        return out
+
+    def compute_thresholds(self, layers: Sequence[int], queries_per_layer: List[torch.Tensor], k: int,
+                           model_labels: torch.Tensor, rescore_r: int = 0) -> torch.Tensor:
+        b = queries_per_layer[0].shape[0]
+        thr = torch.empty(len(layers), dtype=torch.float32, device=self.device)
+        nbytes = freeze_cascade_workspace_bytes(self.ctx, layers, b, k, rescore_r)
+        if nbytes == 0:
+            raise FreezeError(FREEZE_EINVAL, "freeze_cascade_workspace_bytes")
+        ws = self._workspace(nbytes)
+        freeze_compute_thresholds(self.ctx, layers, queries_per_layer, k, rescore_r, model_labels, thr, ws)
+        return thr

@@ -144,6 +144,11 @@ hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int
 //     distance) tuples);
 //  4. vote: occurrences m of each label among the k, winner = most occurrences, smaller
 //     label id on equal counts; hit iff m >= vote_threshold (Sec. 2.1 / Sec. 3).
+//     With the distance-weighted rule of Sec. 3 instead: C_i = (m_i / k) * sum_j 1/d_j over the
+//     label's neighbours (d = square root of the reported squared distance, sums in fp64 in
+//     neighbour order), winner = largest C_i, smaller label id on equality; the confidence is
+//     reported in fp32 and the look-up is a hit iff it is strictly greater than the layer's
+//     threshold (Pseudocode 1, FreezeInference).  A zero distance gives +inf, i.e. a hit.
 // ---------------------------------------------------------------------------------------
 // Exact re-scoring by one wave: candidates c0 .. c0+G-1 (c0 = wave * G, stepping 4 G), the 64
 // lanes striding over the activation 8 elements at a time; dist = sum (q_i - c_i)^2 in fp32,
@@ -306,6 +311,8 @@ __global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
     __shared__ int32_t idx_s[kMaxRescore];
     __shared__ int32_t lab_s[kMaxK];
     __shared__ int32_t cnt_s[kMaxK];
+    __shared__ float dsel_s[kMaxK];
+    __shared__ double conf_s[kMaxK];
 
     const int nq = a.count ? *a.count : a.b;
     const int q = blockIdx.x;
@@ -379,6 +386,7 @@ __global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
             a.out_nbr_idx[(int64_t)q * a.k + rank] = im;
             a.out_nbr_dist[(int64_t)q * a.k + rank] = dm;
             lab_s[rank] = a.labels[im];
+            dsel_s[rank] = dm;
         }
     }
     __syncthreads();
@@ -389,9 +397,33 @@ __global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
         int c = 0;
         for (int j = 0; j < a.k; ++j) c += (lab_s[j] == lm);
         cnt_s[tid] = c;
+        if (a.weighted) {
+            double inv = 0.0;
+            for (int j = 0; j < a.k; ++j)
+                if (lab_s[j] == lm) inv += 1.0 / __builtin_sqrt((double)dsel_s[j]);
+            conf_s[tid] = ((double)c / (double)a.k) * inv;
+        }
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0 && a.weighted) {
+        double best_conf = -1.0;
+        int best_c = 0;
+        int32_t best_l = 0;
+        for (int j = 0; j < a.k; ++j) {
+            const double cf = conf_s[j];
+            const int32_t l = lab_s[j];
+            if (cf > best_conf || (cf == best_conf && l < best_l)) {
+                best_conf = cf;
+                best_l = l;
+                best_c = cnt_s[j];
+            }
+        }
+        const float conf = (float)best_conf;
+        a.out_labels[q] = best_l;
+        a.out_votes[q] = best_c;
+        a.out_conf[q] = conf;
+        a.out_hit[q] = (uint8_t)(conf > a.conf_threshold);
+    } else if (tid == 0) {
         int best_c = 0;
         int32_t best_l = 0;
         for (int j = 0; j < a.k; ++j) {
@@ -507,6 +539,46 @@ hipError_t launch_cascade_scatter(const int32_t *labels, const uint8_t *hit, con
 {
     hipLaunchKernelGGL(cascade_scatter_kernel, dim3((unsigned)((b + 255) / 256)), dim3(256), 0, s, labels, hit, sel,
                        count, (int)b, layer_pos, out_labels, out_exit);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Per-layer threshold (Pseudocode 1, ComputeThresholds): the largest confidence among the
+// validation items whose look-up disagrees with the model's label; 0 when none disagrees.
+// Confidences are >= 0 (or +inf), so their fp32 bit patterns order like unsigned integers.
+// ---------------------------------------------------------------------------------------
+__global__ void threshold_init_kernel(float *thr, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) thr[i] = 0.f;
+}
+
+__global__ void threshold_max_kernel(const int32_t *pred, const float *conf, const int32_t *model_labels, int64_t b,
+                                     float *thr)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t v = 0;
+    if (i < b && pred[i] != model_labels[i]) v = __float_as_uint(conf[i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+        v = o > v ? o : v;
+    }
+    if ((threadIdx.x & 63) == 0 && v != 0) atomicMax(reinterpret_cast<unsigned int *>(thr), v);
+}
+
+hipError_t launch_threshold_init(float *thr, int n, hipStream_t s)
+{
+    hipLaunchKernelGGL(threshold_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, thr, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_threshold_max(const int32_t *pred, const float *conf, const int32_t *model_labels, int64_t b,
+                                float *thr, hipStream_t s)
+{
+    if (b <= 0) return hipSuccess;
+    hipLaunchKernelGGL(threshold_max_kernel, dim3((unsigned)((b + 255) / 256)), dim3(256), 0, s, pred, conf,
+                       model_labels, b, thr);
     return hipGetLastError();
 }
 

@@ -153,8 +153,17 @@ struct StageMarks {
     }
 };
 
+// How the k neighbours become a label and a hit decision: the plurality count against an
+// integer threshold, or the distance-weighted confidence of Sec. 3 against a float threshold.
+struct HitRule {
+    int weighted;
+    int vote_threshold;
+    float conf_threshold;
+    float *out_conf;   // [b], weighted rule only
+};
+
 int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, const float *queries, const int32_t *sel,
-                   const int32_t *count, int64_t b, int k, int vote_threshold, int32_t *out_labels, uint8_t *out_hit,
+                   const int32_t *count, int64_t b, int k, const HitRule &rule, int32_t *out_labels, uint8_t *out_hit,
                    int32_t *out_votes, int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace, hipStream_t s)
 {
     Carver ws(workspace);
@@ -245,7 +254,10 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     fa.c_f32 = L.c_f32;
     fa.labels = L.labels;
     fa.k = k;
-    fa.vote_threshold = vote_threshold;
+    fa.vote_threshold = rule.vote_threshold;
+    fa.weighted = rule.weighted;
+    fa.conf_threshold = rule.conf_threshold;
+    fa.out_conf = rule.out_conf;
     fa.out_labels = out_labels;
     fa.out_hit = out_hit;
     fa.out_votes = out_votes;
@@ -287,6 +299,90 @@ bool cascade_layout(const freeze_ctx *ctx, int num_layers, const int *layers, in
                  2 * align_up(4);
     *err = FREEZE_OK;
     return true;
+}
+
+int lookup_checked(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k, const HitRule &rule,
+                   int rescore_r, int32_t *out_labels, uint8_t *out_hit, int32_t *out_votes, int32_t *out_nbr_idx,
+                   float *out_nbr_dist, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int err;
+    const LayerCache *L = get_layer(ctx, layer, &err);
+    if (!L) return err;
+    LookupShape sh;
+    if (!lookup_shape(ctx, *L, b, k, rescore_r, false, &sh)) return FREEZE_EINVAL;
+    if (b == 0) return FREEZE_OK;   // nothing to look up: data pointers may be null
+    if (!queries || !out_labels || !out_hit || !out_votes || !out_nbr_idx || !out_nbr_dist || !workspace)
+        return FREEZE_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(queries) % 16) != 0) return FREEZE_EINVAL;
+    if (workspace_bytes < sh.ws_bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return FREEZE_EWORKSPACE;
+    return enqueue_lookup(ctx, *L, sh, queries, nullptr, nullptr, b, k, rule, out_labels, out_hit, out_votes,
+                          out_nbr_idx, out_nbr_dist, workspace, static_cast<hipStream_t>(stream));
+}
+
+// The cascade of Pseudocode 1 (FreezeInference) under either hit rule; `rules` has one entry per
+// position in `layers` (out_conf is filled in here).
+int cascade_checked(freeze_ctx *ctx, int num_layers, const int *layers, const float *const *queries_per_layer,
+                    int64_t b, int k, const std::vector<HitRule> &rules, int rescore_r, int32_t *out_labels,
+                    int32_t *out_exit_layer, int64_t *out_hits_per_layer, void *workspace, size_t workspace_bytes,
+                    void *stream)
+{
+    CascadeLayout cl;
+    int err;
+    if (!cascade_layout(ctx, num_layers, layers, b, k, rescore_r, &cl, &err)) return err;
+    if (!queries_per_layer || !out_hits_per_layer || !workspace) return FREEZE_EINVAL;
+    if (b > 0 && (!out_labels || !out_exit_layer)) return FREEZE_EINVAL;
+    for (int l = 0; l < num_layers; ++l) {
+        if (b > 0 && (!queries_per_layer[l] || (reinterpret_cast<uintptr_t>(queries_per_layer[l]) % 16) != 0))
+            return FREEZE_EINVAL;
+    }
+    if (workspace_bytes < cl.bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return FREEZE_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    Carver ws(workspace);
+    unsigned char *lookup_ws = ws.take<unsigned char>(cl.lookup_ws);
+    const size_t bb = (size_t)(b > 0 ? b : 1);
+    int32_t *t_labels = ws.take<int32_t>(bb);
+    int32_t *t_votes = ws.take<int32_t>(bb);
+    float *t_conf = ws.take<float>(bb);
+    uint8_t *t_hit = ws.take<uint8_t>(bb);
+    int32_t *t_idx = ws.take<int32_t>(bb * k);
+    float *t_dist = ws.take<float>(bb * k);
+    int32_t *sel_buf[2] = {ws.take<int32_t>(bb), ws.take<int32_t>(bb)};
+    int32_t *cnt_buf[2] = {ws.take<int32_t>(1), ws.take<int32_t>(1)};
+
+    if (b == 0) {
+        // nothing to look up: every layer froze zero requests
+        for (int l = 0; l < num_layers; ++l)
+            if (launch_compact(t_hit, nullptr, nullptr, 0, sel_buf[0], cnt_buf[0], out_hits_per_layer + l, s) !=
+                hipSuccess)
+                return FREEZE_EHIP;
+        return FREEZE_OK;
+    }
+    if (launch_cascade_init(out_labels, out_exit_layer, b, s) != hipSuccess) return FREEZE_EHIP;
+
+    const int32_t *sel = nullptr;     // layer 0: every request, identity order
+    const int32_t *count = nullptr;
+    for (int l = 0; l < num_layers; ++l) {
+        const LayerCache &L = ctx->layers[layers[l]];
+        LookupShape sh;
+        lookup_shape(ctx, L, b, k, rescore_r, true, &sh);
+        HitRule rule = rules[(size_t)l];
+        rule.out_conf = t_conf;
+        int rc = enqueue_lookup(ctx, L, sh, queries_per_layer[l], sel, count, b, k, rule, t_labels, t_hit, t_votes,
+                                t_idx, t_dist, lookup_ws, s);
+        if (rc != FREEZE_OK) return rc;
+        if (launch_cascade_scatter(t_labels, t_hit, sel, count, b, l, out_labels, out_exit_layer, s) != hipSuccess)
+            return FREEZE_EHIP;
+        int32_t *sel_next = sel_buf[l & 1];
+        int32_t *cnt_next = cnt_buf[l & 1];
+        if (launch_compact(t_hit, sel, count, b, sel_next, cnt_next, out_hits_per_layer + l, s) != hipSuccess)
+            return FREEZE_EHIP;
+        sel = sel_next;
+        count = cnt_next;
+    }
+    return FREEZE_OK;
 }
 
 }  // namespace
@@ -373,20 +469,22 @@ int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, i
                   int rescore_r, int32_t *out_labels, uint8_t *out_hit, int32_t *out_votes, int32_t *out_nbr_idx,
                   float *out_nbr_dist, void *workspace, size_t workspace_bytes, void *stream)
 {
-    int err;
-    const LayerCache *L = get_layer(ctx, layer, &err);
-    if (!L) return err;
-    LookupShape sh;
-    if (!lookup_shape(ctx, *L, b, k, rescore_r, false, &sh)) return FREEZE_EINVAL;
     if (vote_threshold < 1 || vote_threshold > k) return FREEZE_EINVAL;
-    if (b == 0) return FREEZE_OK;   // nothing to look up: data pointers may be null
-    if (!queries || !out_labels || !out_hit || !out_votes || !out_nbr_idx || !out_nbr_dist || !workspace)
-        return FREEZE_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(queries) % 16) != 0) return FREEZE_EINVAL;
-    if (workspace_bytes < sh.ws_bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
-        return FREEZE_EWORKSPACE;
-    return enqueue_lookup(ctx, *L, sh, queries, nullptr, nullptr, b, k, vote_threshold, out_labels, out_hit, out_votes,
-                          out_nbr_idx, out_nbr_dist, workspace, static_cast<hipStream_t>(stream));
+    const HitRule rule{0, vote_threshold, 0.f, nullptr};
+    return lookup_checked(ctx, layer, queries, b, k, rule, rescore_r, out_labels, out_hit, out_votes, out_nbr_idx,
+                          out_nbr_dist, workspace, workspace_bytes, stream);
+}
+
+int freeze_lookup_confidence(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k, float conf_threshold,
+                             int rescore_r, int32_t *out_labels, uint8_t *out_hit, float *out_conf,
+                             int32_t *out_votes, int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    if (!(conf_threshold >= 0.f)) return FREEZE_EINVAL;   // also rejects NaN
+    if (b > 0 && !out_conf) return FREEZE_EINVAL;
+    const HitRule rule{1, 1, conf_threshold, out_conf};
+    return lookup_checked(ctx, layer, queries, b, k, rule, rescore_r, out_labels, out_hit, out_votes, out_nbr_idx,
+                          out_nbr_dist, workspace, workspace_bytes, stream);
 }
 
 size_t freeze_cascade_workspace_bytes(const freeze_ctx *ctx, int num_layers, const int *layers, int64_t b, int k,
@@ -402,16 +500,45 @@ int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers, co
                           int32_t *out_exit_layer, int64_t *out_hits_per_layer, void *workspace,
                           size_t workspace_bytes, void *stream)
 {
+    if (!vote_thresholds || num_layers < 1 || num_layers > 1024) return FREEZE_EINVAL;
+    std::vector<HitRule> rules((size_t)num_layers);
+    for (int l = 0; l < num_layers; ++l) {
+        if (vote_thresholds[l] < 1 || vote_thresholds[l] > k) return FREEZE_EINVAL;
+        rules[(size_t)l] = HitRule{0, vote_thresholds[l], 0.f, nullptr};
+    }
+    return cascade_checked(ctx, num_layers, layers, queries_per_layer, b, k, rules, rescore_r, out_labels,
+                           out_exit_layer, out_hits_per_layer, workspace, workspace_bytes, stream);
+}
+
+int freeze_lookup_cascade_confidence(freeze_ctx *ctx, int num_layers, const int *layers,
+                                     const float *const *queries_per_layer, int64_t b, int k,
+                                     const float *conf_thresholds, int rescore_r, int32_t *out_labels,
+                                     int32_t *out_exit_layer, int64_t *out_hits_per_layer, void *workspace,
+                                     size_t workspace_bytes, void *stream)
+{
+    if (!conf_thresholds || num_layers < 1 || num_layers > 1024) return FREEZE_EINVAL;
+    std::vector<HitRule> rules((size_t)num_layers);
+    for (int l = 0; l < num_layers; ++l) {
+        if (!(conf_thresholds[l] >= 0.f)) return FREEZE_EINVAL;
+        rules[(size_t)l] = HitRule{1, 1, conf_thresholds[l], nullptr};
+    }
+    return cascade_checked(ctx, num_layers, layers, queries_per_layer, b, k, rules, rescore_r, out_labels,
+                           out_exit_layer, out_hits_per_layer, workspace, workspace_bytes, stream);
+}
+
+int freeze_compute_thresholds(freeze_ctx *ctx, int num_layers, const int *layers,
+                              const float *const *queries_per_layer, int64_t b, int k, int rescore_r,
+                              const int32_t *model_labels, float *out_thresholds, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
     CascadeLayout cl;
     int err;
     if (!cascade_layout(ctx, num_layers, layers, b, k, rescore_r, &cl, &err)) return err;
-    if (!queries_per_layer || !vote_thresholds || !out_hits_per_layer || !workspace) return FREEZE_EINVAL;
-    if (b > 0 && (!out_labels || !out_exit_layer)) return FREEZE_EINVAL;
-    for (int l = 0; l < num_layers; ++l) {
+    if (!queries_per_layer || !out_thresholds || !workspace) return FREEZE_EINVAL;
+    if (b > 0 && !model_labels) return FREEZE_EINVAL;
+    for (int l = 0; l < num_layers; ++l)
         if (b > 0 && (!queries_per_layer[l] || (reinterpret_cast<uintptr_t>(queries_per_layer[l]) % 16) != 0))
             return FREEZE_EINVAL;
-        if (vote_thresholds[l] < 1 || vote_thresholds[l] > k) return FREEZE_EINVAL;
-    }
     if (workspace_bytes < cl.bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
         return FREEZE_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -421,41 +548,24 @@ int freeze_lookup_cascade(freeze_ctx *ctx, int num_layers, const int *layers, co
     const size_t bb = (size_t)(b > 0 ? b : 1);
     int32_t *t_labels = ws.take<int32_t>(bb);
     int32_t *t_votes = ws.take<int32_t>(bb);
-    int32_t *t_spare = ws.take<int32_t>(bb);
-    (void)t_spare;
+    float *t_conf = ws.take<float>(bb);
     uint8_t *t_hit = ws.take<uint8_t>(bb);
     int32_t *t_idx = ws.take<int32_t>(bb * k);
     float *t_dist = ws.take<float>(bb * k);
-    int32_t *sel_buf[2] = {ws.take<int32_t>(bb), ws.take<int32_t>(bb)};
-    int32_t *cnt_buf[2] = {ws.take<int32_t>(1), ws.take<int32_t>(1)};
 
-    if (b == 0) {
-        // nothing to look up: every layer froze zero requests
-        for (int l = 0; l < num_layers; ++l)
-            if (launch_compact(t_hit, nullptr, nullptr, 0, sel_buf[0], cnt_buf[0], out_hits_per_layer + l, s) !=
-                hipSuccess)
-                return FREEZE_EHIP;
-        return FREEZE_OK;
-    }
-    if (launch_cascade_init(out_labels, out_exit_layer, b, s) != hipSuccess) return FREEZE_EHIP;
-
-    const int32_t *sel = nullptr;     // layer 0: every request, identity order
-    const int32_t *count = nullptr;
+    if (launch_threshold_init(out_thresholds, num_layers, s) != hipSuccess) return FREEZE_EHIP;
+    if (b == 0) return FREEZE_OK;
+    // every validation item is looked up at every layer (no early exit while calibrating)
     for (int l = 0; l < num_layers; ++l) {
         const LayerCache &L = ctx->layers[layers[l]];
         LookupShape sh;
         lookup_shape(ctx, L, b, k, rescore_r, true, &sh);
-        int rc = enqueue_lookup(ctx, L, sh, queries_per_layer[l], sel, count, b, k, vote_thresholds[l], t_labels, t_hit,
-                                t_votes, t_idx, t_dist, lookup_ws, s);
+        const HitRule rule{1, 1, 0.f, t_conf};
+        int rc = enqueue_lookup(ctx, L, sh, queries_per_layer[l], nullptr, nullptr, b, k, rule, t_labels, t_hit, t_votes,
+                                t_idx, t_dist, lookup_ws, s);
         if (rc != FREEZE_OK) return rc;
-        if (launch_cascade_scatter(t_labels, t_hit, sel, count, b, l, out_labels, out_exit_layer, s) != hipSuccess)
+        if (launch_threshold_max(t_labels, t_conf, model_labels, b, out_thresholds + l, s) != hipSuccess)
             return FREEZE_EHIP;
-        int32_t *sel_next = sel_buf[l & 1];
-        int32_t *cnt_next = cnt_buf[l & 1];
-        if (launch_compact(t_hit, sel, count, b, sel_next, cnt_next, out_hits_per_layer + l, s) != hipSuccess)
-            return FREEZE_EHIP;
-        sel = sel_next;
-        count = cnt_next;
     }
     return FREEZE_OK;
 }

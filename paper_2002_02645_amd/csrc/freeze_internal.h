@@ -164,6 +164,9 @@ struct FinishArgs {
     const float *c_f32;     // non-null: re-score against the fp32 rows (cache given in fp32)
     const int32_t *labels;
     int k, vote_threshold;
+    int weighted;           // 0: plurality count and vote_threshold; 1: distance-weighted confidence
+    float conf_threshold;   // weighted rule: hit iff confidence > conf_threshold
+    float *out_conf;        // [b] (compact order), weighted rule only
     int32_t *out_labels;    // [b] (compact order)
     uint8_t *out_hit;
     int32_t *out_votes;
@@ -181,5 +184,9 @@ hipError_t launch_cascade_init(int32_t *out_labels, int32_t *out_exit, int64_t b
 hipError_t launch_cascade_scatter(const int32_t *labels, const uint8_t *hit, const int32_t *sel,
                                   const int32_t *count, int64_t b, int layer_pos, int32_t *out_labels,
                                   int32_t *out_exit, hipStream_t s);
+
+hipError_t launch_threshold_init(float *thr, int n, hipStream_t s);
+hipError_t launch_threshold_max(const int32_t *pred, const float *conf, const int32_t *model_labels, int64_t b,
+                                float *thr, hipStream_t s);
 
 }  // namespace fz

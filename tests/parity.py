@@ -94,3 +94,82 @@ def assert_lookup_matches(got, ref, queries, entries, labels, num_classes, k, vo
                                  dist_rel)
     assert not fails, f"{len(fails)} mismatching queries, first: {fails[:5]}"
     return near
+
+
+# ---------------------------------------------------------------------------------------------
+# Confidence rule (Sec. 3 heuristic, strict float threshold).  The neighbour lists obey the same
+# near-tie rule as above.  The expected (label, confidence) is the oracle's confidence function
+# applied to the reported indices with the ORACLE's distances of those indices (for a query that
+# is not near-tie these are simply the oracle's own result).  A decision is *ambiguous*, and then
+# either outcome is accepted, when the floating-point margin that decides it is below the
+# tolerance: the two best labels' confidences within `rel` of each other (label), or the
+# confidence within `rel` of the threshold (hit).  The reported confidence must be within `rel`.
+# ---------------------------------------------------------------------------------------------
+def _per_label_confidence(labels, idx, d2, k):
+    """Comparator-only: all labels' C_i, to find the runner-up (the expected values come from the oracle)."""
+    out = {}
+    for c in set(int(labels[j]) for j in idx):
+        m = [dd for j, dd in zip(idx, d2) if int(labels[j]) == c]
+        with np.errstate(divide="ignore"):
+            out[c] = (len(m) / k) * float(np.sum(1.0 / np.sqrt(np.asarray(m, dtype=np.float64))))
+    return out
+
+
+def compare_confidence(got, ref, queries, entries, labels, num_classes, k, conf_threshold, rel=REL):
+    """got: dict(idx, dist, label, conf, hit).  ref: oracle_reference(...) (its vote fields are unused).
+    Returns (near-tie queries, ambiguous decisions, failures)."""
+    b = ref["idx"].shape[0]
+    n = entries.shape[0]
+    thr = np.float32(conf_threshold)
+    fails, near, ambiguous = [], 0, 0
+    for i in range(b):
+        D = ref["sqdist_ext"][i]
+        is_near = bool((_rel(D[1:], D[:-1]) < rel).any()) if D.shape[0] > 1 else False
+        gi = got["idx"][i]
+        gd = got["dist"][i].astype(np.float64)
+        if not is_near:
+            if not np.array_equal(gi, ref["idx"][i]):
+                fails.append(f"q{i}: idx {gi.tolist()} != oracle {ref['idx'][i].tolist()}")
+                continue
+            true_d = ref["sqdist"][i]
+        else:
+            near += 1
+            if len(set(gi.tolist())) != k or gi.min() < 0 or gi.max() >= n:
+                fails.append(f"q{i}: near-tie but indices invalid {gi.tolist()}")
+                continue
+            true_d = exact_sqdist(queries[i], entries, gi)
+            if (true_d > ref["sqdist"][i, k - 1] * (1 + rel)).any():
+                fails.append(f"q{i}: near-tie, reported neighbour farther than D(k)(1+rel)")
+                continue
+        bad = (_rel(gd, true_d) > rel) | ((true_d == 0.0) & (gd != 0.0))
+        if bad.any():
+            fails.append(f"q{i}: dist {gd.tolist()} vs oracle {true_d.tolist()}")
+            continue
+        exp_l, exp_c = fo.confidence(labels, gi[None, :], true_d[None, :], num_classes)
+        exp_l, exp_c = int(exp_l[0]), float(exp_c[0])
+        per = sorted(_per_label_confidence(labels, gi, true_d, k).values(), reverse=True)
+        label_amb = len(per) > 1 and not np.isinf(per[0]) and \
+            (per[0] == per[1] or _rel(np.float64(per[0]), np.float64(per[1])) < rel)
+        gc = float(got["conf"][i])
+        if np.isinf(exp_c):
+            if not (np.isinf(gc) and gc > 0 and int(got["hit"][i]) == 1):
+                fails.append(f"q{i}: zero distance must give +inf confidence and a hit, got {gc}")
+            if int(got["label"][i]) != exp_l:
+                fails.append(f"q{i}: label {got['label'][i]} != {exp_l}")
+            continue
+        if label_amb:
+            ambiguous += 1
+            if _rel(np.float64(gc), np.float64(per[0])) > rel and _rel(np.float64(gc), np.float64(per[1])) > rel:
+                fails.append(f"q{i}: confidence {gc} matches neither of the tied labels {per[:2]}")
+            continue
+        if int(got["label"][i]) != exp_l:
+            fails.append(f"q{i}: label {got['label'][i]} != {exp_l} (C {per[:2]})")
+        if _rel(np.float64(gc), np.float64(exp_c)) > rel:
+            fails.append(f"q{i}: confidence {gc} vs oracle {exp_c}")
+        exp_hit = int(np.float32(exp_c) > thr)
+        if _rel(np.float64(exp_c), np.float64(thr)) < rel:
+            ambiguous += 1                      # the threshold sits inside the rounding margin
+            exp_hit = int(np.float32(gc) > thr)   # then the decision must at least follow the reported value
+        if int(got["hit"][i]) != exp_hit:
+            fails.append(f"q{i}: hit {got['hit'][i]} != {exp_hit} (conf {gc}, oracle {exp_c}, thr {thr})")
+    return near, ambiguous, fails

@@ -83,6 +83,116 @@ def test_hand_example_confidence():
     assert math.isinf(conf[0])
 
 
+def _confidence_by_hand(labels, idx, d2, k):
+    """The heuristic of Sec. 3 written out with dictionaries: an independent restatement used
+    only on tiny inputs."""
+    share, inv = {}, {}
+    for i, dd in zip(idx, d2):
+        c = int(labels[i])
+        share[c] = share.get(c, 0) + 1
+        inv[c] = inv.get(c, 0.0) + (math.inf if dd == 0 else 1.0 / math.sqrt(dd))
+    conf = {c: (share[c] / k) * inv[c] for c in share}
+    best = min(conf, key=lambda c: (-conf[c], c))
+    return best, conf[best]
+
+
+def test_confidence_closed_forms():
+    # k = 1: the confidence is the reciprocal distance of the nearest entry
+    ent = np.array([[3, 4], [6, 8], [0, 10]], dtype=np.float32)
+    lab = np.array([2, 1, 0], dtype=np.int32)
+    r = fo.lookup_confidence(np.zeros((1, 2), np.float32), ent, lab, 3, 1, 0.1)
+    assert int(r["label"][0]) == 2 and r["conf"][0] == np.float32(0.2) and int(r["hit"][0]) == 1
+    # strict comparison: a confidence equal to the threshold is a miss
+    r = fo.lookup_confidence(np.zeros((1, 2), np.float32), ent, lab, 3, 1, float(np.float32(0.2)))
+    assert int(r["hit"][0]) == 0
+    # k neighbours of one label, all at distance rho: C = (k/k) * k / rho
+    rho, k = 4.0, 6
+    ring = np.array([[rho, 0, 0], [-rho, 0, 0], [0, rho, 0], [0, -rho, 0], [0, 0, rho], [0, 0, -rho], [50, 50, 50]],
+                    dtype=np.float32)
+    r = fo.lookup_confidence(np.zeros((1, 3), np.float32), ring, np.array([1] * 6 + [0], np.int32), 2, k, 0.0)
+    assert int(r["label"][0]) == 1 and r["conf"][0] == np.float32(k / rho)
+    # closeness beats plurality: two neighbours of label 0 at distance 1, three of label 1 at 10
+    ent = np.array([[1, 0], [-1, 0], [10, 0], [-10, 0], [0, 10]], dtype=np.float32)
+    lab = np.array([0, 0, 1, 1, 1], dtype=np.int32)
+    r = fo.lookup_confidence(np.zeros((1, 2), np.float32), ent, lab, 2, 5, 0.5)
+    assert int(r["label"][0]) == 0 and r["conf"][0] == pytest.approx(0.8, rel=1e-6)
+    assert fo.lookup(np.zeros((1, 2), np.float32), ent, lab, 2, 5, 3)["label"][0] == 1
+    # equal confidences: the smaller label id
+    ent = np.array([[2, 0], [-2, 0]], dtype=np.float32)
+    r = fo.lookup_confidence(np.zeros((1, 2), np.float32), ent, np.array([5, 3], np.int32), 6, 2, 0.0)
+    assert int(r["label"][0]) == 3 and r["conf"][0] == np.float32(0.25)
+
+
+def test_confidence_scales_inversely_with_distance_and_matches_restatement():
+    rng = np.random.default_rng(11)
+    ent = rng.integers(-9, 10, size=(60, 5)).astype(np.float32)
+    lab = rng.integers(0, 4, size=60).astype(np.int32)
+    q = rng.integers(-9, 10, size=(12, 5)).astype(np.float32) + 0.5   # no zero distances
+    k = 7
+    r1 = fo.lookup_confidence(q, ent, lab, 4, k, 0.0)
+    r2 = fo.lookup_confidence(2 * q, 2 * ent, lab, 4, k, 0.0)            # distances double exactly
+    assert np.array_equal(r1["idx"], r2["idx"]) and np.array_equal(r1["label"], r2["label"])
+    idx, d2, _ = fo.knn(q, ent, k)
+    _, c1 = fo.confidence(lab, idx, d2, 4)
+    _, c2 = fo.confidence(lab, idx, 4 * d2, 4)
+    assert np.array_equal(c1, 2 * c2)
+    for i in range(q.shape[0]):
+        best, conf = _confidence_by_hand(lab, idx[i], d2[i], k)
+        assert int(r1["label"][i]) == best
+        assert r1["conf"][i] == pytest.approx(conf, rel=1e-6)
+
+
+def _threshold_problem(seed):
+    rng = np.random.default_rng(seed)
+    spec = [(40, 6), (40, 4), (40, 3)]
+    ents = [rng.normal(size=(n, d)).astype(np.float32) for n, d in spec]
+    labs = [rng.integers(0, 3, size=n).astype(np.int32) for n, _ in spec]
+    val = [rng.normal(size=(25, d)).astype(np.float32) for _, d in spec]
+    y = rng.integers(0, 3, size=25).astype(np.int32)
+    return ents, labs, val, y
+
+
+def test_compute_thresholds_is_max_confidence_of_wrong_lookups_and_gives_zero_validation_error():
+    ents, labs, val, y = _threshold_problem(5)
+    k = 5
+    thr = fo.compute_thresholds(val, ents, labs, [3, 3, 3], k, y)
+    assert thr.dtype == np.float32 and thr.shape == (3,)
+    for l in range(3):
+        idx, d2, _ = fo.knn(val[l], ents[l], k)
+        wrong = []
+        for i in range(25):
+            best, conf = _confidence_by_hand(labs[l], idx[i], d2[i], k)
+            if best != y[i]:
+                wrong.append(conf)
+        assert wrong, "the random labels must produce wrong look-ups"
+        assert thr[l] == pytest.approx(max(wrong), rel=1e-6)
+    # Sec. 3.1: with these thresholds no validation item is frozen with a label other than the model's
+    out_l, out_x, hits = fo.cascade_confidence(val, ents, labs, [3, 3, 3], k, thr)
+    frozen = out_x >= 0
+    assert np.array_equal(out_l[frozen], y[frozen])
+    assert hits.sum() == frozen.sum()
+    # no wrong look-up anywhere -> thresholds stay at 0
+    own = [labs[l][fo.knn(val[l], ents[l], 1)[0][:, 0]] for l in range(3)]
+    assert fo.compute_thresholds(val[:1], ents[:1], labs[:1], [3], 1, own[0])[0] == 0.0
+
+
+def test_cascade_confidence_exit_is_first_layer_above_threshold():
+    ents, labs, val, _ = _threshold_problem(9)
+    k = 4
+    per = [fo.lookup_confidence(val[l], ents[l], labs[l], 3, k, 0.0) for l in range(3)]
+    thr = [float(np.median(per[l]["conf"])) for l in range(3)]
+    out_l, out_x, hits = fo.cascade_confidence(val, ents, labs, [3, 3, 3], k, thr)
+    seen = set()
+    for i in range(25):
+        above = [l for l in range(3) if per[l]["conf"][i] > np.float32(thr[l])]
+        exp = above[0] if above else -1
+        seen.add(exp)
+        assert out_x[i] == exp
+        assert out_l[i] == (per[exp]["label"][i] if exp >= 0 else -1)
+    assert len(seen) >= 3
+    assert [int(h) for h in hits] == [int((out_x == l).sum()) for l in range(3)]
+
+
 def test_lattice_closed_form():
     # entries c_n = (n, n, ..., n) in d dims, query (x, ..., x): D = d * (x - n)^2 exactly.
     n, d, k = 41, 7, 6

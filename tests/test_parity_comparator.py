@@ -72,3 +72,39 @@ def test_near_tie_clause():
              label=np.array([0], np.int32), votes=np.array([1], np.int32), hit=np.array([1], np.uint8))
     _, fails = parity.compare_lookup(g, ref, q, e, lab, 2, k, 1)
     assert fails
+
+
+def _confidence_case():
+    wl = synth.scaled(synth.WORKLOADS["c1_tiny"], n=300, batch=40)
+    data = synth.make_workload(wl)
+    L = data.layers[0]
+    q, e = data.queries[0].numpy(), L.entries.numpy()
+    lab = synth.random_labels(300, 3, 8).numpy()
+    ref = parity.oracle_reference(q, e, lab, 3, wl.k, 1)
+    res = fo.lookup_confidence(q, e, lab, 3, wl.k, 0.0)
+    thr = float(np.median(res["conf"]))
+    res = fo.lookup_confidence(q, e, lab, 3, wl.k, thr)
+    got = dict(idx=res["idx"].copy(), dist=res["sqdist"].astype(np.float32), label=res["label"].copy(),
+               conf=res["conf"].copy(), hit=res["hit"].copy())
+    return q, e, lab, wl.k, thr, ref, got
+
+
+def test_confidence_comparator_accepts_oracle_and_rejects_planted_mistakes():
+    q, e, lab, k, thr, ref, got = _confidence_case()
+    _, amb, fails = parity.compare_confidence(got, ref, q, e, lab, 3, k, thr, rel=1e-6)
+    assert not fails and amb <= 2
+    assert 0 < got["hit"].sum() < 40
+    for mutate in ("swap", "dist", "label", "hit", "conf"):
+        g = {key: v.copy() for key, v in got.items()}
+        if mutate == "swap":
+            g["idx"][3, [0, 1]] = g["idx"][3, [1, 0]]
+        elif mutate == "dist":
+            g["dist"][5, 2] *= 1.001
+        elif mutate == "label":
+            g["label"][7] = (g["label"][7] + 1) % 3
+        elif mutate == "hit":
+            g["hit"][9] ^= 1
+        else:
+            g["conf"][11] *= np.float32(1.001)
+        _, _, fails = parity.compare_confidence(g, ref, q, e, lab, 3, k, thr, rel=1e-6)
+        assert fails, mutate
