@@ -25,7 +25,10 @@
 // sequential DRAM access) into a ring of NS stages with NS-1 stages in flight.  The
 // chunk swizzle makes the ds_read_b128 fragment reads bank-conflict free.  The loads
 // are issued with inline asm: the compiler would otherwise order every LDS read
-// behind the outstanding direct loads, serialising load and compute.
+// behind the outstanding direct loads, serialising load and compute.  The loop is
+// software-pipelined by hand (one barrier per k-step, placed before its last MFMA
+// layer; loads and the next stage's first fragment reads issued one at a time between
+// MFMAs), with scheduling barriers pinning the order.
 //
 // Epilogue (per tile, in column slabs that reuse the operand LDS): waves write their
 // keys to the slab; thread t scans row t, collecting a bit mask of keys not above the
@@ -73,7 +76,7 @@ __device__ __forceinline__ float from_ordered_bits(uint32_t u)
 template <int BM_, int BK_, int RMAX_, int NS_, int WN_ = 4>
 struct DistCfg {
     static constexpr int BM = BM_, BN = kTileN, BK = BK_, RMAX = RMAX_;
-    static constexpr int NS = NS_;                  // operand stages in LDS (NS - 1 loads in flight)
+    static constexpr int NS = NS_;                  // operand stages in LDS, all in use (NS - 1 in flight)
     static constexpr int WM = 2, WN = WN_;          // wave grid: 2 x 4 (8 waves) or 2 x 2 (4 waves)
     static constexpr int NWAVES = WM * WN, THREADS = 64 * NWAVES;
     static constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
@@ -95,7 +98,8 @@ struct DistCfg {
     static_assert(NI_A >= 1 && NI_B >= 1, "load split");
     static_assert(BM <= THREADS, "one scanning thread per row");
     static constexpr int LPS = NI_A + NI_B;         // direct loads per thread and stage
-    static_assert(NS >= 2 && NS <= 6 && (NS - 2) * LPS <= 63, "vmcnt range");
+    static_assert(NS >= 2 && NS <= 6 && (NS - 1) * LPS <= 63, "vmcnt range");
+    static_assert((BK / 16) % 2 == 0, "fragment buffer parity");
 };
 
 struct DistKernelArgs {
@@ -175,17 +179,15 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     for (int nt = nt0; nt < nt1; ++nt) {
         const int n0 = nt * BN;
         const uint64_t gB = uniform_u64((uint64_t)(uintptr_t)p.c_bf + (size_t)nt * BN * tile_row_bytes);
-        auto issue = [&](int stage, int kt) {
+        // one instruction of a stage's fill: l < NI_A -> A image, else B image
+        auto issue_one = [&](int stage, int kt, int l) {
             const uint32_t sbase = smem_base + stage * C::STAGE_BYTES + w * 1024;
-            const uint64_t a = gA + (size_t)kt * C::A_BYTES;
-            const uint64_t b = gB + (size_t)kt * (BN * BK * 2);
-#pragma unroll
-            for (int i = 0; i < C::NI_A; ++i)
-                load16_global_to_lds(a + i * (C::NWAVES * 1024), lane_off, sbase + i * (C::NWAVES * 1024));
-#pragma unroll
-            for (int i = 0; i < C::NI_B; ++i)
-                load16_global_to_lds(b + i * (C::NWAVES * 1024), lane_off,
-                                     sbase + C::A_BYTES + i * (C::NWAVES * 1024));
+            if (l < C::NI_A)
+                load16_global_to_lds(gA + (size_t)kt * C::A_BYTES + l * (C::NWAVES * 1024), lane_off,
+                                     sbase + l * (C::NWAVES * 1024));
+            else
+                load16_global_to_lds(gB + (size_t)kt * (BN * BK * 2) + (l - C::NI_A) * (C::NWAVES * 1024), lane_off,
+                                     sbase + C::A_BYTES + (l - C::NI_A) * (C::NWAVES * 1024));
         };
 
         f32x16 acc[TM][TN];
@@ -196,49 +198,85 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+        {
+            // Software-pipelined loop.  Invariant at the top of k-step kt: the fragments of its first
+            // sub-step are in (or on their way to) register buffer 0; k-blocks kt+1 .. kt+NS-1 are in
+            // flight or landed in the other stages.  Before the last sub-step every read of the
+            // current stage has been issued, so the step's only barrier goes there: it publishes the
+            // next stage (each wave waited for its own part) and frees the current one.  The MFMAs of
+            // the last sub-step need nothing newer, so the matrix pipe restarts at once, and the next
+            // stage's first fragments and the refill of the freed stage are issued one by one between
+            // them: a wave blocks while the memory pipeline accepts a load, so loads issued back to
+            // back stall the MFMAs behind them.  Past the last k-block the refills repeat it (never
+            // read): the loop body and the count of outstanding loads stay uniform.
+            constexpr int KS = BK / 16;           // sub-steps (one 16-deep MFMA layer each)
+            constexpr int NR = TM + TN;           // fragment reads per sub-step
+            // A stage's LPS loads are issued in two parts: LB of them between the MFMAs of the last
+            // sub-step of the k-step that frees the stage, the rest between the MFMAs of the following
+            // k-step's other sub-steps, so that loads leave at an even rate.
+            constexpr int LB = C::LPS / KS;
+            constexpr int G1 = (KS - 1) * TM;     // MFMA groups (of TN) before the last sub-step
 #pragma unroll
-        for (int ps = 0; ps < C::NS - 1; ++ps)
-            if (ps < nk) issue(ps, ps);
-        int st = 0;
-        for (int kt = 0; kt < nk; ++kt) {
-            // stage `st` must have landed; the (up to NS-2) younger stages may stay in flight
-            const int younger = nk - 1 - kt;
-            switch (younger < C::NS - 2 ? younger : C::NS - 2) {
-            case 0: wait_global_loads_le<0>(); break;
-            case 1: wait_global_loads_le<1 * C::LPS>(); break;
-            case 2: wait_global_loads_le<(C::NS > 3 ? 2 : 0) * C::LPS>(); break;
-            case 3: wait_global_loads_le<(C::NS > 4 ? 3 : 0) * C::LPS>(); break;
-            default: wait_global_loads_le<(C::NS > 5 ? 4 : 0) * C::LPS>(); break;
-            }
-            __syncthreads();   // ... for every wave; and all reads of the stage refilled next are done
-            if (kt + C::NS - 1 < nk) issue((st + C::NS - 1) % C::NS, kt + C::NS - 1);
-            const int baseA = st * (C::STAGE_BYTES / 16) + rdA;
-            const int baseB = st * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB;
-            // Fragments are double buffered in registers: the reads of sub-step kk+1 are issued
-            // before the MFMAs of sub-step kk, so that LDS latency hides behind matrix work.
+            for (int ps = 0; ps < C::NS; ++ps)
+#pragma unroll
+                for (int l = 0; l < (ps == C::NS - 1 ? LB : C::LPS); ++l) issue_one(ps, ps < nk ? ps : nk - 1, l);
+            wait_global_loads_le<(C::NS - 2) * C::LPS + LB>();
+            __syncthreads();
             bf16x8 af[2][TM], bfr[2][TN];
-            auto load_frags = [&](int buf, int kk) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    af[buf][i] = smem16[baseA + (kk >> 1) * (BM * 4) + i * 128 + (((kk & 1) << 1) ^ pcxA)];
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    bfr[buf][j] = smem16[baseB + (kk >> 1) * (BN * 4) + j * 128 + (((kk & 1) << 1) ^ pcxB)];
+            auto read_frag = [&](int buf, int stage, int kk, int rr) {   // rr < TM: A block rr, else B block rr - TM
+                if (rr < TM)
+                    af[buf][rr] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + (kk >> 1) * (BM * 4) + rr * 128 +
+                                         (((kk & 1) << 1) ^ pcxA)];
+                else
+                    bfr[buf][rr - TM] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB +
+                                               (kk >> 1) * (BN * 4) + (rr - TM) * 128 + (((kk & 1) << 1) ^ pcxB)];
             };
-            load_frags(0, 0);
 #pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
-                if (kk + 1 < BK / 16) load_frags((kk + 1) & 1, kk + 1);
+            for (int rr = 0; rr < NR; ++rr) read_frag(0, 0, 0, rr);
+            int st = 0;
+            for (int kt = 0; kt < nk; ++kt) {
+                const int nst = (st + 1 == C::NS) ? 0 : st + 1;
+                const int pst = (st == 0) ? C::NS - 1 : st - 1;
+                const int fill_kt = kt + C::NS < nk ? kt + C::NS : nk - 1;
+                const int pfill_kt = kt + C::NS - 1 < nk ? kt + C::NS - 1 : nk - 1;   // the stage freed one step ago
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                for (int kk = 0; kk < KS - 1; ++kk) {
+#pragma unroll
+                    for (int rr = 0; rr < NR; ++rr) read_frag((kk + 1) & 1, st, kk + 1, rr);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        const int gi = kk * TM + i;
+#pragma unroll
+                        for (int l = LB + gi * (C::LPS - LB) / G1; l < LB + (gi + 1) * (C::LPS - LB) / G1; ++l)
+                            issue_one(pst, pfill_kt, l);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                wait_global_loads_le<(C::NS - 2) * C::LPS>();   // own part of k-block kt+1 has landed
+                __syncthreads();                                // ... everyone's; and stage st is free
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-                // keep the order: next sub-step's LDS reads first, then this sub-step's MFMAs
-                if (kk + 1 < BK / 16) __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[(KS - 1) & 1][i], bfr[(KS - 1) & 1][j],
+                                                                           acc[i][j], 0, 0, 0);
+                    constexpr int RG = TM > 1 ? TM - 1 : 1;   // the reads go with the first TM-1 groups
+#pragma unroll
+                    for (int rr = i * NR / RG; rr < (i + 1) * NR / RG && rr < NR && i < RG; ++rr) read_frag(0, nst, 0, rr);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int l = i * LB / TM; l < (i + 1) * LB / TM; ++l) issue_one(st, fill_kt, l);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                st = nst;
             }
-            st = (st + 1 == C::NS) ? 0 : st + 1;
+            wait_global_loads_le<0>();   // the refills past the last k-block
         }
         __syncthreads();   // operand LDS is free: the slab may overwrite it
 
@@ -430,9 +468,9 @@ hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t
     if (plan.r < 1 || plan.r > kMaxRescore || a.d_pad % kPadD != 0) return hipErrorInvalidValue;
     if (plan.variant == 3 && (!a.keys || !a.bmin)) return hipErrorInvalidValue;
     switch (plan.variant) {
-    case 0: return launch_variant<DistCfg<256, 64, 16, 2>>(plan, a, s);
+    case 0: return launch_variant<DistCfg<256, 32, 16, 4>>(plan, a, s);
     case 1: return launch_variant<DistCfg<256, 32, 32, 3>>(plan, a, s);
-    case 2: return launch_variant<DistCfg<128, 32, 64, 3>>(plan, a, s);
+    case 2: return launch_variant<DistCfg<128, 32, 64, 4>>(plan, a, s);
     default: return launch_variant<DistCfg<256, 32, 0, 5>>(plan, a, s);
     }
 }
