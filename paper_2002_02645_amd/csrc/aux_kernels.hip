@@ -98,25 +98,42 @@ hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t
 // ---------------------------------------------------------------------------------------
 // Query preparation: bf16 copy (round to nearest even) of the live queries for the matrix
 // cores in the tiled layout (tiles of bm rows), gathered through the miss list when there is
-// one; rows up to the next tile boundary are zero filled.  One block per row.
+// one; rows up to the next tile boundary are zero filled.  One block per pair of rows: in the
+// tiled layout the 64-byte pieces of two neighbouring rows share a 128-byte line, so eight
+// consecutive threads (two rows x four 16-byte chunks of one k-block) write a whole line.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, const int32_t *sel, const int32_t *count,
                                                          int b, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf)
 {
     const int nq = count ? *count : b;
-    const int row = blockIdx.x;
+    const int row0 = blockIdx.x * 2;   // bm is even: both rows lie in one tile
     const int live_pad = ((nq + bm - 1) / bm) * bm;
-    if (row >= live_pad) return;
-    const int rit = row % bm;
-    uint4 *tile_base = reinterpret_cast<uint4 *>(q_bf + (int64_t)(row / bm) * bm * d_pad);
+    if (row0 >= live_pad) return;
+    uint4 *tile_base = reinterpret_cast<uint4 *>(q_bf + (int64_t)(row0 / bm) * bm * d_pad);
+    const int rsel = (threadIdx.x >> 2) & 1;
+    const int row = row0 + rsel, rit = row % bm;
     const float *src = (row < nq) ? queries + (int64_t)(sel ? sel[row] : row) * d : nullptr;
-    for (int64_t j = threadIdx.x; j < d_pad / 8; j += 256) {
+    const bool vec = (d % 4) == 0;     // rows are then 16-byte aligned (the batch pointer is)
+    const int64_t pair_chunks = d_pad / 4;   // 16-byte chunks of the two rows together
+    for (int64_t jj = threadIdx.x; jj < pair_chunks; jj += 256) {
+        const int64_t j = (jj >> 3) * 4 + (jj & 3);   // chunk of 8 elements within the row
+        const int64_t i0 = j * 8;
+        float x[8];
+        if (src && vec && i0 + 8 <= d) {
+            const f32x4 v0 = *reinterpret_cast<const f32x4 *>(src + i0);
+            const f32x4 v1 = *reinterpret_cast<const f32x4 *>(src + i0 + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[e] = v0[e];
+                x[4 + e] = v1[e];
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = (src && i0 + e < d) ? src[i0 + e] : 0.f;
+        }
         uint16_t h[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t i = j * 8 + e;
-            h[e] = (src && i < d) ? bf16_rne(src[i]) : (uint16_t)0;
-        }
+        for (int e = 0; e < 8; ++e) h[e] = bf16_rne(x[e]);
         uint4 v;
         v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
         v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
@@ -129,8 +146,9 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
 hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
                              int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, hipStream_t s)
 {
-    hipLaunchKernelGGL(query_prep_kernel, dim3((unsigned)b_pad), dim3(256), 0, s, queries, sel, count, (int)b, bm, d,
-                       d_pad, q_bf);
+    if (bm % 2 != 0 || b_pad % 2 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(query_prep_kernel, dim3((unsigned)(b_pad / 2)), dim3(256), 0, s, queries, sel, count, (int)b, bm,
+                       d, d_pad, q_bf);
     return hipGetLastError();
 }
 

@@ -354,35 +354,46 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                 __syncthreads();
                 if (tid < BM) {
                     const int t = tid;
-                    // which of the slab's columns are real cache entries
-                    uint64_t mask[(C::SLABW + 63) / 64];
+                    // First pass over the row: one bit per group of four columns whose smallest key
+                    // is not above the row's current R-th best (two min instructions and a compare
+                    // per four keys); almost every group fails once the list has filled.
                     const f32x4 *srow = reinterpret_cast<const f32x4 *>(slab + t * C::SLABW);
-                    constexpr int CGM = (C::SLABW < 64 ? C::SLABW : 64) / 4;   // column groups per mask word
-#pragma unroll
-                    for (int m = 0; m < (C::SLABW + 63) / 64; ++m) {
-                        uint64_t mk = 0;
-#pragma unroll 4
-                        for (int cgi = 0; cgi < CGM; ++cgi) {
-                            const int cg = m * 16 + cgi;
-                            const f32x4 v = srow[(cg ^ t) & (C::SLABW / 4 - 1)];
-                            // the four keys share a 32-column segment: one validity limit for all
-                            const int seg0 = (wg * C::WNS + (cg >> 3)) * TN * 32 + bj * 32 + ((cg & 7) << 2);
-                            const int lim = p.n - n0 - seg0;   // columns seg0 .. seg0+3 are valid iff index < lim
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const bool pass = (v[e] <= tau) && (e < lim);
-                                mk |= (uint64_t)pass << (cgi * 4 + e);
-                            }
-                        }
-                        mask[m] = mk;
+                    constexpr int NG = C::SLABW / 4;
+                    static_assert(NG <= 32, "one mask word");
+                    uint32_t gmask = 0;
+#pragma unroll 8
+                    for (int cg = 0; cg < NG; ++cg) {
+                        const f32x4 v = srow[(cg ^ t) & (NG - 1)];
+                        const float m = __builtin_fminf(__builtin_fminf(v[0], v[1]), __builtin_fminf(v[2], v[3]));
+                        gmask |= (uint32_t)(m <= tau) << cg;
                     }
+                    // Second pass: the flagged groups give a bit per key that passes and is a real
+                    // cache entry (padding columns are not).
+                    uint64_t kmask[2] = {0, 0};
+                    while (gmask) {
+                        const int cg = __builtin_ctz(gmask);
+                        gmask &= gmask - 1;
+                        const f32x4 v = srow[(cg ^ t) & (NG - 1)];
+                        // the four keys share a 32-column segment: columns seg0 .. seg0+3 of the tile
+                        const int seg0 = (wg * C::WNS + (cg >> 3)) * TN * 32 + bj * 32 + ((cg & 7) << 2);
+                        const int lim = p.n - n0 - seg0;   // real cache entries iff e < lim
+                        uint64_t bits = 0;
 #pragma unroll
-                    for (int m = 0; m < (C::SLABW + 63) / 64; ++m) {
-                        uint64_t mk = mask[m];
+                        for (int e = 0; e < 4; ++e) bits |= (uint64_t)((v[e] <= tau) && (e < lim)) << e;
+                        bits <<= (cg & 15) * 4;
+                        if (cg < 16)
+                            kmask[0] |= bits;
+                        else
+                            kmask[1] |= bits;
+                    }
+                    // Third pass: one insertion attempt per surviving key, against the threshold as it tightens.
+#pragma unroll
+                    for (int m = 0; m < (NG + 15) / 16; ++m) {
+                        uint64_t mk = kmask[m];
                         while (mk) {
                             const int sc = m * 64 + __builtin_ctzll(mk);
                             mk &= mk - 1;
-                            const float key = slab[t * C::SLABW + ((((sc >> 2) ^ t) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)];
+                            const float key = slab[t * C::SLABW + ((((sc >> 2) ^ t) & (NG - 1)) << 2) + (sc & 3)];
                             const int tilecol = (wg * C::WNS + sc / 32) * TN * 32 + bj * 32 + (sc & 31);
                             const uint64_t ent = ((uint64_t)ordered_bits(key) << 32) | (uint32_t)(n0 + tilecol);
                             if (ent < curmax) {
@@ -391,8 +402,8 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 #pragma unroll
                                 for (int i = 0; i < C::RMAX; ++i) {
                                     if (i < r) {
-                                        const uint64_t v = top[i * BM + t];
-                                        if (v >= curmax) { curmax = v; maxpos = i; }
+                                        const uint64_t u = top[i * BM + t];
+                                        if (u >= curmax) { curmax = u; maxpos = i; }
                                     }
                                 }
                                 tau = (curmax == kSentinel) ? __builtin_inff() : from_ordered_bits((uint32_t)(curmax >> 32));
