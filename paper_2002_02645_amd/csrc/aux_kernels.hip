@@ -2,6 +2,7 @@
 // kernel (merge of per-split candidate lists, exact fp32 re-scoring, final top-k, label
 // vote, hit decision), miss compaction and the cascade's scatter.  gfx950 only.
 #include "freeze_internal.h"
+#include "select_common.h"
 
 namespace fz {
 
@@ -168,15 +169,15 @@ hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int
 //     reported in fp32 and the look-up is a hit iff it is strictly greater than the layer's
 //     threshold (Pseudocode 1, FreezeInference).  A zero distance gives +inf, i.e. a hit.
 // ---------------------------------------------------------------------------------------
-// Exact re-scoring by one wave: candidates c0 .. c0+G-1 (c0 = wave * G, stepping 4 G), the 64
+// Exact re-scoring by one wave of `nwaves`: candidates c0 .. c0+G-1 (c0 = wave * G, stepping nwaves * G), the 64
 // lanes striding over the activation 8 elements at a time; dist = sum (q_i - c_i)^2 in fp32,
 // per-lane partial sums in index order, then a butterfly over the lanes (fixed order).
 template <int G>
 __device__ __forceinline__ void rescore_wave(const FinishArgs &a, const float *qrow, const int32_t *idx_s,
-                                             float *dist_s, int r, int wave, int lane)
+                                             float *dist_s, int r, int wave, int lane, int nwaves = 4)
 {
     const bool vec = (a.d % 8) == 0;
-    for (int c0 = wave * G; c0 < r; c0 += 4 * G) {
+    for (int c0 = wave * G; c0 < r; c0 += nwaves * G) {
         float acc[G];
         int64_t cand[G];
 #pragma unroll
@@ -241,6 +242,85 @@ __device__ __forceinline__ void rescore_wave(const FinishArgs &a, const float *q
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
             if (lane == 0 && c0 + j < r) dist_s[c0 + j] = v;
+        }
+    }
+}
+
+// Exact re-scoring of many candidates against a short activation (d_pad <= 1024, d a multiple
+// of 8) by one wave of `nwaves`: the query stays in registers (a lane owns elements 8 l .. 8 l + 7
+// and 512 + 8 l .. 512 + 8 l + 7), and G candidate rows are fetched at a time, all loads issued
+// before the first is used.  Same per-lane order of additions and the same butterfly as
+// rescore_wave, so the same distances bit for bit.
+template <int G, bool F32>
+__device__ __forceinline__ void rescore_short(const FinishArgs &a, const float *qrow, const int32_t *idx_s,
+                                              float *dist_s, int m, int wave, int lane, int nwaves)
+{
+    const int64_t i0 = (int64_t)lane * 8, i1 = i0 + 512;
+    const bool h0 = i0 < a.d, h1 = i1 < a.d;
+    float qv[2][8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        qv[0][e] = h0 ? qrow[i0 + e] : 0.f;
+        qv[1][e] = h1 ? qrow[i1 + e] : 0.f;
+    }
+    for (int c0 = wave * G; c0 < m; c0 += nwaves * G) {
+        float acc[G];
+        if constexpr (F32) {
+            f32x4 cv[G][2][2];
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                const float *row = a.c_f32 + (int64_t)idx_s[(c0 + j < m) ? c0 + j : m - 1] * a.d_pad;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const bool live = h ? h1 : h0;
+                    const float *src = row + (h ? i1 : i0);
+                    cv[j][h][0] = live ? *reinterpret_cast<const f32x4 *>(src) : f32x4{0.f, 0.f, 0.f, 0.f};
+                    cv[j][h][1] = live ? *reinterpret_cast<const f32x4 *>(src + 4) : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                acc[j] = 0.f;
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float df = qv[h][e] - cv[j][h][e >> 2][e & 3];
+                        acc[j] = __builtin_fmaf(df, df, acc[j]);
+                    }
+            }
+        } else {
+            uint4 cb[G][2];
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                const uint16_t *row = a.c_rows + (int64_t)idx_s[(c0 + j < m) ? c0 + j : m - 1] * a.d_pad;
+                cb[j][0] = h0 ? *reinterpret_cast<const uint4 *>(row + i0) : uint4{0, 0, 0, 0};
+                cb[j][1] = h1 ? *reinterpret_cast<const uint4 *>(row + i1) : uint4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                acc[j] = 0.f;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t wv[4] = {cb[j][h].x, cb[j][h].y, cb[j][h].z, cb[j][h].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float c_lo = __uint_as_float(wv[e] << 16);
+                        const float c_hi = __uint_as_float(wv[e] & 0xffff0000u);
+                        const float d0 = qv[h][2 * e] - c_lo;
+                        acc[j] = __builtin_fmaf(d0, d0, acc[j]);
+                        const float d1 = qv[h][2 * e + 1] - c_hi;
+                        acc[j] = __builtin_fmaf(d1, d1, acc[j]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            float v = acc[j];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == 0 && c0 + j < m) dist_s[c0 + j] = v;
         }
     }
 }
@@ -311,6 +391,63 @@ __device__ __forceinline__ void rescore_block(const FinishArgs &a, const float *
             dist_s[r0 + tid] = t;
         }
         __syncthreads();
+    }
+}
+
+// Label and hit decision from the k nearest neighbours (labels lab_s[k], squared distances
+// dsel_s[k], nearest first), by the first k threads of the block; cnt_s / conf_s are scratch.
+// Plurality rule: occurrences m of each label, winner = most occurrences, smaller label id on
+// equal counts, hit iff m >= vote_threshold.  Distance-weighted rule of Sec. 3: C_i = (m_i / k) *
+// sum_j 1 / d_j in fp64 in neighbour order, winner = largest C_i (smaller id on equality), the
+// confidence rounded once to fp32, hit iff confidence > threshold (Pseudocode 1).
+__device__ __forceinline__ void decide_and_write(const FinishArgs &a, int q, int tid, const int32_t *lab_s,
+                                                 const float *dsel_s, int32_t *cnt_s, double *conf_s)
+{
+    if (tid < a.k) {
+        const int32_t lm = lab_s[tid];
+        int c = 0;
+        for (int j = 0; j < a.k; ++j) c += (lab_s[j] == lm);
+        cnt_s[tid] = c;
+        if (a.weighted) {
+            double inv = 0.0;
+            for (int j = 0; j < a.k; ++j)
+                if (lab_s[j] == lm) inv += 1.0 / __builtin_sqrt((double)dsel_s[j]);
+            conf_s[tid] = ((double)c / (double)a.k) * inv;
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && a.weighted) {
+        double best_conf = -1.0;
+        int best_c = 0;
+        int32_t best_l = 0;
+        for (int j = 0; j < a.k; ++j) {
+            const double cf = conf_s[j];
+            const int32_t l = lab_s[j];
+            if (cf > best_conf || (cf == best_conf && l < best_l)) {
+                best_conf = cf;
+                best_l = l;
+                best_c = cnt_s[j];
+            }
+        }
+        const float conf = (float)best_conf;
+        a.out_labels[q] = best_l;
+        a.out_votes[q] = best_c;
+        a.out_conf[q] = conf;
+        a.out_hit[q] = (uint8_t)(conf > a.conf_threshold);
+    } else if (tid == 0) {
+        int best_c = 0;
+        int32_t best_l = 0;
+        for (int j = 0; j < a.k; ++j) {
+            const int c = cnt_s[j];
+            const int32_t l = lab_s[j];
+            if (c > best_c || (c == best_c && l < best_l)) {
+                best_c = c;
+                best_l = l;
+            }
+        }
+        a.out_labels[q] = best_l;
+        a.out_votes[q] = best_c;
+        a.out_hit[q] = (uint8_t)(best_c >= a.vote_threshold);
     }
 }
 
@@ -410,52 +547,251 @@ __global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
     __syncthreads();
 
     // 4. vote and hit decision
-    if (tid < a.k) {
-        const int32_t lm = lab_s[tid];
-        int c = 0;
-        for (int j = 0; j < a.k; ++j) c += (lab_s[j] == lm);
-        cnt_s[tid] = c;
-        if (a.weighted) {
-            double inv = 0.0;
-            for (int j = 0; j < a.k; ++j)
-                if (lab_s[j] == lm) inv += 1.0 / __builtin_sqrt((double)dsel_s[j]);
-            conf_s[tid] = ((double)c / (double)a.k) * inv;
+    decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s);
+}
+
+// ---------------------------------------------------------------------------------------
+// Finishing kernels of the small-batch path (short activations, at most 16 queries), from the
+// block minima alone:
+//  1. skinny_select_kernel (one workgroup per query): T = the R-th smallest block minimum; the R
+//     blocks whose minimum is <= T hold every entry that is <= T, hence the R best by the
+//     coarse key.  It starts from the per-workgroup minima of the streaming kernel, so it reads
+//     only the block minima of the R groups that can matter.
+//  2. skinny_rescore_kernel (one workgroup per pair of selected blocks and query: the work
+//     would take one CU tens of microseconds): exact fp32 re-scoring of the 64 entries (same
+//     arithmetic as above), then a wave-local sort that passes on the `keep` nearest.
+//  3. skinny_final_kernel (one workgroup per query): the k nearest by (distance, index) of what
+//     was passed on, then the label and hit decision.
+// ---------------------------------------------------------------------------------------
+struct SkinnySelectArgs {
+    const uint64_t *bmin;    // [b, nb] smallest (ordered key, index) of every block of 32 entries
+    const uint64_t *wgmin;   // [b, n_groups] smallest value of each group of blocks
+    int64_t nb;
+    int n_groups, n_tiles;   // group j = the blocks of cache tiles [j n_tiles / n_groups, (j+1) n_tiles / n_groups)
+    int r;                   // blocks to take
+    int32_t *blocks;         // [b, kMaxRescore] out: the selected blocks
+    int32_t *nblk;           // [b] out: how many
+};
+
+// The R-th smallest of list[0..cnt) (distinct values), cnt <= kThrList, by the whole workgroup.
+__device__ inline uint64_t rth_of_list(uint64_t *list, int cnt, int r_sel, uint64_t *sel_s, int tid)
+{
+    if (cnt <= kThrThreads) {
+        select_by_rank_counting(list, cnt, r_sel - 1, tid, sel_s);
+        __syncthreads();
+        return *sel_s;
+    }
+    int n2 = 2;
+    while (n2 < cnt) n2 <<= 1;
+    for (int i = cnt + tid; i < n2; i += kThrThreads) list[i] = kSentinel;
+    __syncthreads();
+    bitonic_sort_lds(list, n2, tid, kThrThreads);
+    return list[r_sel - 1];
+}
+
+__global__ __launch_bounds__(kThrThreads) void skinny_select_kernel(SkinnySelectArgs sa)
+{
+    __shared__ uint64_t list[kThrList];
+    __shared__ uint64_t gm_s[kThrThreads];
+    __shared__ uint64_t sel_s;
+    __shared__ int list_n, blk_n, grp_n;
+    __shared__ int32_t grp_s[kMaxRescore];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const int64_t nb = sa.nb;
+    const int r = sa.r;
+    int32_t *blk = sa.blocks + (size_t)q * kMaxRescore;
+    if (r >= nb) {   // fewer blocks than wanted: take them all
+        if (tid < (int)nb) blk[tid] = tid;
+        if (tid == 0) sa.nblk[q] = (int)nb;
+        return;
+    }
+    // 1a. the groups that can hold one of the r smallest block minima: those whose own minimum
+    //     is among the r smallest group minima (T1 = the r-th of them bounds the answer above)
+    const int ng = sa.n_groups;
+    if (tid == 0) {
+        list_n = 0;
+        blk_n = 0;
+        grp_n = 0;
+    }
+    const uint64_t my_gm = tid < ng ? sa.wgmin[(size_t)q * ng + tid] : kSentinel;
+    gm_s[tid] = my_gm;
+    __syncthreads();
+    uint64_t t1 = kSentinel;
+    if (r < ng) {
+        if (r <= 32) {
+            t1 = smallest_sorted(gm_s, list, ng, r, tid, kThrThreads)[r - 1];
+        } else {
+            select_by_rank_counting(gm_s, ng, r - 1, tid, &sel_s);
+            __syncthreads();
+            t1 = sel_s;
+        }
+        __syncthreads();
+    }
+    if (tid < ng && my_gm <= t1) {
+        const int pos = atomicAdd(&grp_n, 1);
+        if (pos < kMaxRescore) grp_s[pos] = tid;
+    }
+    __syncthreads();
+    const int ngrp = grp_n < kMaxRescore ? grp_n : kMaxRescore;   // min(r, ng) groups
+    // 1b. gather their block minima <= T1: at least r, at most r * (blocks per group)
+    const int bpg = ((sa.n_tiles + ng - 1) / ng) * (kTileN / 32);
+    const uint64_t *src = sa.bmin + (size_t)q * nb;
+    for (int c = tid; c < ngrp * bpg; c += kThrThreads) {
+        const int gidx = grp_s[c / bpg];
+        const int64_t b0 = ((int64_t)gidx * sa.n_tiles / ng) * (kTileN / 32);
+        const int64_t b1 = ((int64_t)(gidx + 1) * sa.n_tiles / ng) * (kTileN / 32);
+        const int64_t bi = b0 + c % bpg;
+        if (bi < b1) {
+            const uint64_t x = src[bi];
+            if (x <= t1) {
+                const int pos = atomicAdd(&list_n, 1);
+                if (pos < kThrList) list[pos] = x;
+            }
         }
     }
     __syncthreads();
-    if (tid == 0 && a.weighted) {
-        double best_conf = -1.0;
-        int best_c = 0;
-        int32_t best_l = 0;
-        for (int j = 0; j < a.k; ++j) {
-            const double cf = conf_s[j];
-            const int32_t l = lab_s[j];
-            if (cf > best_conf || (cf == best_conf && l < best_l)) {
-                best_conf = cf;
-                best_l = l;
-                best_c = cnt_s[j];
+    const int cnt = list_n < kThrList ? list_n : kThrList;
+    // 1c. the r smallest of them are the minima of the blocks to take (distinct values)
+    if (r <= 32 && cnt <= kThrList / 2) {
+        const uint64_t *res = smallest_sorted(list, list + kThrList / 2, cnt, r, tid, kThrThreads);
+        if (tid < r) blk[tid] = (int32_t)((uint32_t)res[tid] >> 5);   // block of the minimum's entry
+        if (tid == 0) sa.nblk[q] = r;
+    } else {
+        const uint64_t t = rth_of_list(list, cnt, r, &sel_s, tid);
+        __syncthreads();
+        for (int i = tid; i < cnt; i += kThrThreads) {
+            const uint64_t x = list[i];
+            if (x <= t) {
+                const int pos = atomicAdd(&blk_n, 1);
+                if (pos < kMaxRescore) blk[pos] = (int32_t)((uint32_t)x >> 5);
             }
         }
-        const float conf = (float)best_conf;
-        a.out_labels[q] = best_l;
-        a.out_votes[q] = best_c;
-        a.out_conf[q] = conf;
-        a.out_hit[q] = (uint8_t)(conf > a.conf_threshold);
-    } else if (tid == 0) {
-        int best_c = 0;
-        int32_t best_l = 0;
-        for (int j = 0; j < a.k; ++j) {
-            const int c = cnt_s[j];
-            const int32_t l = lab_s[j];
-            if (c > best_c || (c == best_c && l < best_l)) {
-                best_c = c;
-                best_l = l;
-            }
-        }
-        a.out_labels[q] = best_l;
-        a.out_votes[q] = best_c;
-        a.out_hit[q] = (uint8_t)(best_c >= a.vote_threshold);
+        __syncthreads();
+        if (tid == 0) sa.nblk[q] = blk_n < r ? blk_n : r;
     }
+}
+
+struct SkinnyRescoreArgs {
+    FinishArgs a;             // queries, cache rows, n, d, d_pad
+    const int32_t *blocks;    // [b, kMaxRescore]
+    const int32_t *nblk;      // [b]
+    uint64_t *cand;           // [b, pairs * keep] out: packed (ordered distance, index), sentinel-padded
+    int keep;                 // entries each workgroup passes on (<= 64)
+    int pairs;                // workgroups per query
+};
+
+// grid (pairs, b), 256 threads: blocks 2 x and 2 x + 1 of the query's selection
+__global__ __launch_bounds__(256) void skinny_rescore_kernel(SkinnyRescoreArgs ra)
+{
+    const FinishArgs &a = ra.a;
+    __shared__ int32_t idx_s[64];
+    __shared__ int32_t row_s[64];
+    __shared__ float dist_s[64];
+    const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int nblk = ra.nblk[q];
+    uint64_t *out = ra.cand + ((size_t)q * ra.pairs + blockIdx.x) * ra.keep;
+    const int first = blockIdx.x * 2;
+    const int here = nblk - first < 2 ? nblk - first : 2;   // blocks of this workgroup
+    if (here <= 0) {
+        if (tid < ra.keep) out[tid] = kSentinel;
+        return;
+    }
+    const int m = here * 32;
+    // entries past the cache (padding rows of the last tile) are re-scored as row 0 and dropped below
+    if (tid < m) {
+        const int e = ra.blocks[(size_t)q * kMaxRescore + first + (tid >> 5)] * 32 + (tid & 31);
+        idx_s[tid] = e < a.n ? e : -1 - e;
+    }
+    __syncthreads();
+    if (tid < m) row_s[tid] = idx_s[tid] < 0 ? 0 : idx_s[tid];
+    __syncthreads();
+    const float *qrow = a.queries + (int64_t)q * a.d;
+    if (a.d % 8 != 0)
+        rescore_wave<4>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);
+    else if (a.c_f32)
+        rescore_short<4, true>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);
+    else
+        rescore_short<8, false>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);
+    __syncthreads();
+    if (tid < 64) {
+        uint64_t x = kSentinel;
+        if (tid < m && idx_s[tid] >= 0) x = ((uint64_t)ordered_bits(dist_s[tid]) << 32) | (uint32_t)idx_s[tid];
+        x = wave_sort64(x, lane);
+        if (lane < ra.keep) out[lane] = x;
+    }
+}
+
+struct SkinnyFinalArgs {
+    FinishArgs a;
+    const uint64_t *cand;   // [b, count]
+    int count;              // <= kThrList / 2
+};
+
+__global__ __launch_bounds__(kThrThreads) void skinny_final_kernel(SkinnyFinalArgs fa)
+{
+    const FinishArgs &a = fa.a;
+    __shared__ uint64_t list[kThrList];
+    __shared__ int32_t lab_s[kMaxK];
+    __shared__ int32_t cnt_s[kMaxK];
+    __shared__ float dsel_s[kMaxK];
+    __shared__ double conf_s[kMaxK];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const int m = fa.count;
+    for (int c = tid; c < m; c += kThrThreads) list[c] = fa.cand[(size_t)q * m + c];
+    __syncthreads();
+    const uint64_t *res;
+    if (a.k <= 32) {
+        res = smallest_sorted(list, list + kThrList / 2, m, a.k, tid, kThrThreads);
+    } else {
+        int n2 = 2;
+        while (n2 < m) n2 <<= 1;
+        for (int c = m + tid; c < n2; c += kThrThreads) list[c] = kSentinel;
+        __syncthreads();
+        bitonic_sort_lds(list, n2, tid, kThrThreads);
+        res = list;
+    }
+    if (tid < a.k) {
+        const uint64_t x = res[tid];
+        // with finite inputs the first k are real entries; a "no entry" marker maps to row 0
+        const int32_t im = x == kSentinel ? 0 : (int32_t)(uint32_t)x;
+        const float dm = from_ordered_bits((uint32_t)(x >> 32));
+        a.out_nbr_idx[(int64_t)q * a.k + tid] = im;
+        a.out_nbr_dist[(int64_t)q * a.k + tid] = dm;
+        lab_s[tid] = a.labels[im];
+        dsel_s[tid] = dm;
+    }
+    __syncthreads();
+    decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s);
+}
+
+size_t skinny_finish_workspace_bytes(int r, size_t align)
+{
+    auto up = [&](size_t x) { return (x + align - 1) / align * align; };
+    const size_t pairs = (size_t)(r + 1) / 2;
+    return up((size_t)kSkinnyRows * kMaxRescore * 4) + up((size_t)kSkinnyRows * 4) + up((size_t)kSkinnyRows * pairs * 64 * 8);
+}
+
+hipError_t launch_skinny_finish(const FinishArgs &a, const uint64_t *bmin, const uint64_t *wgmin, int64_t nb,
+                                int n_groups, int n_tiles, int32_t *blocks, int32_t *nblk, uint64_t *cand, hipStream_t s)
+{
+    if (a.r < 1 || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r || a.b < 1 || a.b > kSkinnyRows || a.sel || a.count)
+        return hipErrorInvalidValue;
+    if (n_groups < 1 || n_groups > kThrThreads || n_groups > n_tiles) return hipErrorInvalidValue;
+    const int64_t bpg = ((int64_t)(n_tiles + n_groups - 1) / n_groups) * (kTileN / 32);
+    if (a.r < nb && bpg * a.r > kThrList) return hipErrorInvalidValue;
+    SkinnySelectArgs sa{bmin, wgmin, nb, n_groups, n_tiles, a.r, blocks, nblk};
+    hipLaunchKernelGGL(skinny_select_kernel, dim3((unsigned)a.b), dim3(kThrThreads), 0, s, sa);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int pairs = (a.r + 1) / 2;   // a.r >= the number of blocks selected
+    const int keep = a.k <= 32 ? a.k : 64;
+    SkinnyRescoreArgs ra{a, blocks, nblk, cand, keep, pairs};
+    hipLaunchKernelGGL(skinny_rescore_kernel, dim3((unsigned)pairs, (unsigned)a.b), dim3(256), 0, s, ra);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    SkinnyFinalArgs fa{a, cand, pairs * keep};
+    hipLaunchKernelGGL(skinny_final_kernel, dim3((unsigned)a.b), dim3(kThrThreads), 0, s, fa);
+    return hipGetLastError();
 }
 
 hipError_t launch_finish(const FinishArgs &a, hipStream_t s)

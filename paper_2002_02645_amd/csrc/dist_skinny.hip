@@ -5,15 +5,21 @@
 // cache from HBM exactly once with many bytes in flight, not around the matrix cores' rate,
 // and nothing in the streaming kernel depends on the data.
 //
-//  1. dist_skinny_kernel streams the cache and writes, per query b and entry n, the ranking key
+//  1. dist_skinny_kernel streams the cache, forms per query b and entry n the ranking key
 //         key(b, n) = |c_n|^2 - 2 * sum_i Q_bf[b,i] * C_bf[n,i]     (bf16 x bf16 -> fp32 MFMA)
-//     (4 bytes per entry and query against 2*d bytes read), and per block of 32 entries the
-//     smallest (key, index) pair of the block.
-//  2. skinny_threshold_kernel finds, per query, the R-th smallest block minimum T.  R blocks
-//     hold an entry <= T, so the R-th smallest entry overall is <= T; and every entry <= T
-//     lies in one of exactly those R blocks, so at most 32 R entries pass.
-//  3. skinny_filter_kernel collects the entries with (key, index) <= T into a candidate list.
-// The finishing kernel sorts the candidates, keeps the best R and re-scores them in fp32.
+//     and writes, per block of 32 entries, only the smallest (key, index) pair of the block
+//     (8 bytes per 32 entries and query against 64 d bytes read): stores share the counter the
+//     kernel waits on for its loads, so every store it does not make keeps the stream running.
+//  2. The finishing kernel of this path (skinny_finish_kernel, with the other finishing code)
+//     finds the R-th smallest block minimum T.  R blocks hold an entry <= T, so the R-th
+//     smallest entry overall is <= T, and every entry <= T lies in one of exactly those R
+//     blocks: their 32 R entries are a superset of the R best.  It re-scores all of them
+//     exactly in fp32 (d <= 1024: one KiB or two per entry) and keeps the k nearest.
+// The threshold and filter kernels at the end of this file serve the keys-out variant of the
+// tiled kernel (long activations, one query tile), where the keys are materialised:
+//  - block_threshold_kernel finds, per query, the R-th smallest block minimum T;
+//  - key_filter_kernel collects the entries with (key, index) <= T (at most 32 R) into a
+//    candidate list, which the general finishing kernel sorts, cuts to R and re-scores.
 //
 // Paper: Sec. 3 (k nearest neighbours of the layer output), Sec. 5 "Cache lookup
 // performance" (look-up latency decides whether freezing pays off).
@@ -28,6 +34,7 @@
 // k.  The tile's squared norms travel the same way (one LDS-direct load per wave and tile), so
 // no ordinary load ever drains the ring.
 #include "freeze_internal.h"
+#include "select_common.h"
 
 namespace fz {
 
@@ -59,12 +66,6 @@ __device__ __forceinline__ void load4_global_to_lds(const void *g, uint32_t lds_
 template <int N>
 __device__ __forceinline__ void wait_global_loads_le() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-__device__ __forceinline__ uint32_t ordered_bits(float x)
-{
-    uint32_t u = __float_as_uint(x);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 constexpr int kQRows = kSkinnyRows;        // query rows held in LDS (the MFMA's rows 16..31 are zero registers)
 constexpr int kStage = kTileN * kKB * 2;   // 16 KiB: one k-block of one cache tile
 constexpr int kNormBuf = 2 * 8 * 256;      // 4 KiB: per tile parity and wave, 64 floats
@@ -83,8 +84,8 @@ struct SkinnyArgs {
     const uint16_t *q_bf;   // 16 x d_pad (rows >= b zero), tiled layout with 16-row tiles
     const uint16_t *c_bf;
     const float *norm;
-    float *keys;            // [b, n_pad]
     uint64_t *bmin;         // [b, n_pad / 32] smallest (ordered key, index) of each block of 32 entries
+    uint64_t *wgmin;        // [b, n_splits] smallest of the block minima each workgroup wrote
     int b, d_pad, n_tiles, n_splits;
     int64_t n_pad;
 };
@@ -93,6 +94,7 @@ template <class C>
 __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[C::LDS_BYTES];
+    __shared__ uint64_t wmin_s[8][kQRows];   // per wave and query row: smallest block minimum so far
     const bf16x8 *smem16 = reinterpret_cast<const bf16x8 *>(smem);
     constexpr int NORMS = C::A_BYTES;                                       // byte offset of the norm buffers
     const float *normbuf = reinterpret_cast<const float *>(smem + NORMS);   // [2][8 waves][64]
@@ -145,6 +147,9 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
     f32x16 acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    uint64_t run_min[8];   // per accumulator row of this half-wave: smallest block minimum so far
+#pragma unroll
+    for (int e = 0; e < 8; ++e) run_min[e] = kSentinel;
     int slot = 0, kb = 0, nt = nt0;
     for (int gs = 0; gs < total; ++gs) {
         // stage gs must have landed; up to NS-2 younger stages may stay in flight
@@ -178,12 +183,11 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
         slot = (slot + 1 == C::NS) ? 0 : slot + 1;
         if (++kb < kblocks) continue;
 
-        // ---- tile finished: emit its keys and block minima ----
+        // ---- tile finished: emit the minimum (key, index) of each block of 32 entries ----
         kb = 0;
         const int n0 = nt * kTileN;
         // With fewer k-blocks than stages in flight the norm load may still be outstanding.
         if (kblocks < C::NS) wait_global_loads_le<0>();
-        const int col = w * 32 + (lane & 31);
         const float nrm = normbuf[((nt & 1) * 8 + w) * 64 + (lane & 31)];
         ++nt;
 #pragma unroll
@@ -193,7 +197,6 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
                 const int row = row_lo + g * 4;
                 const float key = __builtin_fmaf(-2.f, acc[e], nrm);
                 const bool live = row < p.b;
-                if (live) p.keys[(size_t)row * p.n_pad + n0 + col] = key;
                 // block minimum over the 32 lanes of each half-wave (xor offsets < 32 stay inside it)
                 const uint32_t ob = ordered_bits(key);
                 uint32_t mn = ob;
@@ -205,142 +208,53 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
                 const uint64_t eq = __ballot(ob == mn);
                 const uint32_t half = (uint32_t)(g ? (eq >> 32) : (eq & 0xffffffffull));
                 const int first = __builtin_ctz(half);   // lowest column holding the minimum
-                if (live && (lane & 31) == 0)
-                    p.bmin[(size_t)row * (p.n_pad / 32) + (size_t)(n0 / 32) + w] =
-                        ((uint64_t)mn << 32) | (uint32_t)(n0 + w * 32 + first);
+                const uint64_t pr = ((uint64_t)mn << 32) | (uint32_t)(n0 + w * 32 + first);
+                run_min[e] = pr < run_min[e] ? pr : run_min[e];
+                if (live && (lane & 31) == 0) p.bmin[(size_t)row * (p.n_pad / 32) + (size_t)(n0 / 32) + w] = pr;
             }
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
     }
+    // the workgroup's smallest block minimum per query (the finishing kernel starts from these)
+    if ((lane & 31) == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wmin_s[w][(e >> 2) * 8 + (e & 3) + g * 4] = run_min[e];
+    }
+    __syncthreads();
+    if (tid < p.b) {
+        uint64_t m = wmin_s[0][tid];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) m = wmin_s[i][tid] < m ? wmin_s[i][tid] : m;
+        p.wgmin[(size_t)tid * p.n_splits + sp] = m;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
 // Per query: T = the R-th smallest of the NB block minima (pairs (ordered key, index), all
-// distinct).  One workgroup of 1024 threads per query, two rounds of the same argument as in
-// the file header: the minima are dealt into 256 groups (value j belongs to group j mod 256);
-// the R-th smallest group minimum T1 bounds the answer from above, and at most V * R values are
-// <= T1 (V = values per group); those are gathered into LDS and the R-th of them is T.  The
-// R-th smallest of a short list is found by rank counting (each element counts the smaller
-// ones), with a bitonic sort only for an unusually long list.
+// distinct).  One workgroup of 1024 threads per query (rth_smallest_of).
 // ---------------------------------------------------------------------------------------
-constexpr int kThrThreads = 1024;
-constexpr int kThrGroups = 256;
-constexpr int kThrRegs = 32;      // values per thread kept in registers between the two rounds
-constexpr int kThrList = 8192;    // capacity of the gathered list; the launcher checks V * R <= kThrList
-
-__device__ void bitonic_sort_lds(uint64_t *a, int n_pow2, int tid, int nthreads)
-{
-    for (int size = 2; size <= n_pow2; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = tid; i < (n_pow2 >> 1); i += nthreads) {
-                const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));   // stride is a power of two
-                const int hi = lo + stride;
-                const bool up = ((lo & size) == 0);
-                const uint64_t x = a[lo], y = a[hi];
-                if ((x > y) == up) {
-                    a[lo] = y;
-                    a[hi] = x;
-                }
-            }
-            __syncthreads();
-        }
-    }
-}
-
-// The element of a[0..n) with exactly `rank` smaller elements (all distinct), n <= blockDim.x.
-__device__ __forceinline__ void select_by_rank_counting(const uint64_t *a, int n, int rank, int tid, uint64_t *out)
-{
-    if (tid < n) {
-        const uint64_t mine = a[tid];
-        int c = 0;
-        for (int j = 0; j < n; ++j) c += (a[j] < mine);
-        if (c == rank) *out = mine;
-    }
-}
-
-__global__ __launch_bounds__(kThrThreads) void skinny_threshold_kernel(const uint64_t *bmin, int64_t nb, int r_sel,
+__global__ __launch_bounds__(kThrThreads) void block_threshold_kernel(const uint64_t *bmin, int64_t nb, int r_sel,
                                                                       uint64_t *tau, int32_t *cand_count)
 {
     __shared__ uint64_t list[kThrList];
     __shared__ uint64_t sel_s;
     __shared__ int list_n;
     const int q = blockIdx.x, tid = threadIdx.x;
-    const uint64_t *src = bmin + (size_t)q * nb;
-    if (tid == 0) {
-        cand_count[q] = 0;
-        list_n = 0;
-    }
+    if (tid == 0) cand_count[q] = 0;
     if (r_sel >= nb) {   // fewer blocks than wanted entries: everything passes
         if (tid == 0) tau[q] = kSentinel;
         return;
     }
-    // round 1: thread minima -> 256 group minima -> T1 = the r_sel-th smallest group minimum
-    uint64_t v[kThrRegs];
-    uint64_t m = kSentinel;
-#pragma unroll
-    for (int i = 0; i < kThrRegs; ++i) {
-        const int64_t j = (int64_t)i * kThrThreads + tid;
-        v[i] = j < nb ? src[j] : kSentinel;
-        m = v[i] < m ? v[i] : m;
-    }
-    for (int64_t j = (int64_t)kThrRegs * kThrThreads + tid; j < nb; j += kThrThreads) {
-        const uint64_t x = src[j];
-        m = x < m ? x : m;
-    }
-    list[tid] = m;
-    __syncthreads();
-    if (tid < kThrGroups) {
-        uint64_t g = list[tid];
-#pragma unroll
-        for (int i = 1; i < kThrThreads / kThrGroups; ++i) {
-            const uint64_t x = list[tid + i * kThrGroups];
-            g = x < g ? x : g;
-        }
-        list[kThrThreads + tid] = g;   // group minima live in list[1024 .. 1280)
-    }
-    __syncthreads();
-    // sentinels (groups with no value) are equal to each other; they rank last and r_sel < nb real values exist
-    select_by_rank_counting(list + kThrThreads, kThrGroups, r_sel - 1, tid, &sel_s);
-    __syncthreads();
-    const uint64_t t1 = sel_s;
-    __syncthreads();
-    // round 2: gather the values <= T1 (at least r_sel, at most V * r_sel of them)
-#pragma unroll
-    for (int i = 0; i < kThrRegs; ++i) {
-        if (v[i] <= t1 && v[i] != kSentinel) {
-            const int pos = atomicAdd(&list_n, 1);
-            if (pos < kThrList) list[pos] = v[i];
-        }
-    }
-    for (int64_t j = (int64_t)kThrRegs * kThrThreads + tid; j < nb; j += kThrThreads) {
-        const uint64_t x = src[j];
-        if (x <= t1) {
-            const int pos = atomicAdd(&list_n, 1);
-            if (pos < kThrList) list[pos] = x;
-        }
-    }
-    __syncthreads();
-    const int cnt = list_n < kThrList ? list_n : kThrList;
-    if (cnt <= kThrThreads) {
-        select_by_rank_counting(list, cnt, r_sel - 1, tid, &sel_s);
-        __syncthreads();
-        if (tid == 0) tau[q] = sel_s;
-    } else {
-        int n2 = 2;
-        while (n2 < cnt) n2 <<= 1;
-        for (int i = cnt + tid; i < n2; i += kThrThreads) list[i] = kSentinel;
-        __syncthreads();
-        bitonic_sort_lds(list, n2, tid, kThrThreads);
-        if (tid == 0) tau[q] = list[r_sel - 1];
-    }
+    const uint64_t t = rth_smallest_of(bmin + (size_t)q * nb, nb, r_sel, list, &sel_s, &list_n, tid);
+    if (tid == 0) tau[q] = t;
 }
 
 // ---------------------------------------------------------------------------------------
 // Collect, per query, the entries whose (ordered key, index) pair is <= T.  Grid: (chunks, b).
 // At most 32 * R entries pass (see the file header); `cap` >= that bound.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void skinny_filter_kernel(const float *keys, int64_t n_pad, int n, const uint64_t *tau,
+__global__ __launch_bounds__(256) void key_filter_kernel(const float *keys, int64_t n_pad, int n, const uint64_t *tau,
                                                             uint64_t *cand, int32_t *cand_count, int cap)
 {
     const int q = blockIdx.y;
@@ -372,9 +286,15 @@ bool select_supported(int64_t n_pad, int r)
     return ((nb + kThrGroups - 1) / kThrGroups) * r <= kThrList;
 }
 
-bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r)
+bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r, int num_cus)
 {
-    return b >= 1 && b <= kSkinnyRows && d_pad <= kSkinnyMaxD && select_supported(n_pad, r);
+    // The finishing kernel gathers up to r whole groups of block minima into a list of kThrList
+    // entries; a group is what one streaming workgroup wrote, and it reads the group minima with
+    // one thread each.
+    const int64_t n_tiles = n_pad / kTileN;
+    const int64_t groups = plan_skinny_splits(n_pad, num_cus);
+    const int64_t bpg = ((n_tiles + groups - 1) / groups) * (kTileN / 32);
+    return b >= 1 && b <= kSkinnyRows && d_pad <= kSkinnyMaxD && groups <= kThrThreads && bpg * r <= kThrList;
 }
 
 size_t select_workspace_bytes(int64_t rows, int64_t n_pad, int r, size_t align)
@@ -394,7 +314,10 @@ int plan_skinny_splits(int64_t n, int num_cus)
 
 size_t skinny_workspace_bytes(int64_t n_pad, int r, size_t align)
 {
-    return select_workspace_bytes(kSkinnyRows, n_pad, r, align);
+    auto up = [&](size_t x) { return (x + align - 1) / align * align; };
+    // the block minima and the per-workgroup minima (at most one workgroup per tile)
+    return up((size_t)kSkinnyRows * (size_t)(n_pad / 32) * 8) + up((size_t)kSkinnyRows * (size_t)(n_pad / kTileN) * 8) +
+           skinny_finish_workspace_bytes(r, align);
 }
 
 hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
@@ -405,8 +328,8 @@ hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
     k.q_bf = a.q_bf;
     k.c_bf = a.c_bf;
     k.norm = a.norm;
-    k.keys = a.keys;
     k.bmin = a.bmin;
+    k.wgmin = a.wgmin;
     k.b = a.b;
     k.d_pad = a.d_pad;
     k.n_pad = a.n_pad;
@@ -424,20 +347,15 @@ hipError_t launch_select(const float *keys, const uint64_t *bmin, int64_t n_pad,
 {
     const int64_t nb = n_pad / 32;
     if (!select_supported(n_pad, r) || b < 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(skinny_threshold_kernel, dim3(b), dim3(kThrThreads), 0, s, bmin, nb, r, tau, cand_count);
+    hipLaunchKernelGGL(block_threshold_kernel, dim3(b), dim3(kThrThreads), 0, s, bmin, nb, r, tau, cand_count);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     int chunks = (int)((n_pad / 4 + 256 * 16 - 1) / (256 * 16));   // ~16 float4 groups per thread
     if (chunks < 1) chunks = 1;
     if (chunks > 256) chunks = 256;
-    hipLaunchKernelGGL(skinny_filter_kernel, dim3(chunks, b), dim3(256), 0, s, keys, n_pad, n, tau, cand, cand_count,
+    hipLaunchKernelGGL(key_filter_kernel, dim3(chunks, b), dim3(256), 0, s, keys, n_pad, n, tau, cand, cand_count,
                        32 * r);
     return hipGetLastError();
-}
-
-hipError_t launch_skinny_select(const SkinnyLaunch &a, hipStream_t s)
-{
-    return launch_select(a.keys, a.bmin, a.n_pad, a.n, a.b, a.r, a.tau, a.cand_count, a.cand, s);
 }
 
 }  // namespace fz

@@ -35,6 +35,7 @@
 // row's current R-th best, then inserts the survivors into the row's list under the
 // total order (key, index).
 #include "freeze_internal.h"
+#include "select_common.h"
 
 namespace fz {
 
@@ -61,17 +62,6 @@ __device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
 // Wait until at most N of this wave's global loads are outstanding (loads complete in order).
 template <int N>
 __device__ __forceinline__ void wait_global_loads_le() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
-// fp32 -> unsigned with the same order (so that (key, index) packs into one u64)
-__device__ __forceinline__ uint32_t ordered_bits(float x)
-{
-    uint32_t u = __float_as_uint(x);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float from_ordered_bits(uint32_t u)
-{
-    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
-}
 
 template <int BM_, int BK_, int RMAX_, int NS_, int WN_ = 4>
 struct DistCfg {

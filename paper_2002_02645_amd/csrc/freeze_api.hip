@@ -77,7 +77,7 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     if (r < k) r = k;
     if ((int64_t)r > L.n) r = (int)L.n;
     out->r = r;
-    out->skinny = !cascade && skinny_supported(b, L.n_pad, L.d_pad, r);
+    out->skinny = !cascade && skinny_supported(b, L.n_pad, L.d_pad, r, ctx->num_cus);
     out->keys = false;
     if (out->skinny) {
         DistPlan pl{};
@@ -177,16 +177,16 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     FinishArgs fa{};
     marks.mark(1);
     bool marked2 = false;
+    const uint64_t *skinny_bmin = nullptr, *skinny_wgmin = nullptr;
+    int32_t *skinny_blocks = nullptr, *skinny_nblk = nullptr;
+    uint64_t *skinny_cand = nullptr;
     if (sh.skinny) {
         SkinnyLaunch sl{};
         sl.q_bf = q_bf;
         sl.c_bf = L.c_bf;
         sl.norm = L.norm;
-        sl.keys = ws.take<float>((size_t)kSkinnyRows * L.n_pad);
         sl.bmin = ws.take<uint64_t>((size_t)kSkinnyRows * (L.n_pad / 32));
-        sl.tau = ws.take<uint64_t>(kSkinnyRows);
-        sl.cand_count = ws.take<int32_t>(kSkinnyRows);
-        sl.cand = ws.take<uint64_t>((size_t)kSkinnyRows * 32 * sh.r);
+        sl.wgmin = ws.take<uint64_t>((size_t)kSkinnyRows * (L.n_pad / kTileN));
         sl.b = (int)b;
         sl.n = (int)L.n;
         sl.d_pad = (int)L.d_pad;
@@ -194,13 +194,13 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
         sl.n_splits = sh.plan.n_splits;
         sl.n_pad = L.n_pad;
         if (launch_skinny_stream(sl, s) != hipSuccess) return FREEZE_EHIP;
-        marks.mark(2);   // the stage timing counts the selection kernels with the finishing stage
+        marks.mark(2);
         marked2 = true;
-        if (launch_skinny_select(sl, s) != hipSuccess) return FREEZE_EHIP;
-        fa.part = sl.cand;
-        fa.part_count = sl.cand_count;
-        fa.part_stride = 32 * sh.r;
-        fa.n_splits = 1;
+        skinny_bmin = sl.bmin;
+        skinny_wgmin = sl.wgmin;
+        skinny_blocks = ws.take<int32_t>((size_t)kSkinnyRows * kMaxRescore);
+        skinny_nblk = ws.take<int32_t>(kSkinnyRows);
+        skinny_cand = ws.take<uint64_t>((size_t)kSkinnyRows * ((sh.r + 1) / 2) * 64);
     } else {
         DistArgs da{};
         da.q_bf = q_bf;
@@ -263,7 +263,13 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     fa.out_votes = out_votes;
     fa.out_nbr_idx = out_nbr_idx;
     fa.out_nbr_dist = out_nbr_dist;
-    if (launch_finish(fa, s) != hipSuccess) return FREEZE_EHIP;
+    if (skinny_bmin) {
+        if (launch_skinny_finish(fa, skinny_bmin, skinny_wgmin, L.n_pad / 32, sh.plan.n_splits,
+                                 (int)(L.n_pad / kTileN), skinny_blocks, skinny_nblk, skinny_cand, s) != hipSuccess)
+            return FREEZE_EHIP;
+    } else if (launch_finish(fa, s) != hipSuccess) {
+        return FREEZE_EHIP;
+    }
     marks.mark(3);
     marks.done();
     return FREEZE_OK;

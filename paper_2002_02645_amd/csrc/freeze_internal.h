@@ -126,25 +126,21 @@ struct SkinnyLaunch {
     const uint16_t *q_bf;   // 16 x d_pad prepared queries (rows >= b zero), tiled with 16-row tiles
     const uint16_t *c_bf;
     const float *norm;
-    float *keys;            // [b, n_pad] scratch
-    uint64_t *bmin;         // [b, n_pad / 32] scratch
-    uint64_t *tau;          // [b] scratch
-    int32_t *cand_count;    // [b] out: candidates found per query
-    uint64_t *cand;         // [b, 32 * r] out: packed (ordered key, index) candidates, unordered
+    uint64_t *bmin;         // [b, n_pad / 32] out: smallest (ordered key, index) of every block of 32 entries
+    uint64_t *wgmin;        // [b, n_splits] out: smallest block minimum written by each workgroup
     int b, n, d_pad, r, n_splits;
     int64_t n_pad;
 };
-bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r);
-// Selection from materialised keys (shared by the small-batch and the keys-out paths):
-// threshold from the block minima, then the candidate lists.  b queries, rows of n_pad keys.
+bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r, int num_cus);
+// Selection from materialised keys (keys-out variant of the tiled kernel): threshold from the
+// block minima, then the candidate lists.  b queries, rows of n_pad keys.
 bool select_supported(int64_t n_pad, int r);
 size_t select_workspace_bytes(int64_t rows, int64_t n_pad, int r, size_t align);
 hipError_t launch_select(const float *keys, const uint64_t *bmin, int64_t n_pad, int n, int b, int r, uint64_t *tau,
                          int32_t *cand_count, uint64_t *cand, hipStream_t s);
 int plan_skinny_splits(int64_t n, int num_cus);
 size_t skinny_workspace_bytes(int64_t n_pad, int r, size_t align);
-hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s);   // keys + block minima
-hipError_t launch_skinny_select(const SkinnyLaunch &a, hipStream_t s);   // threshold + candidate lists
+hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s);   // block minima
 
 struct FinishArgs {
     const uint64_t *part;   // [b_pad, alloc_splits, r]; or, with part_count, [b, part_stride] candidate lists
@@ -175,6 +171,12 @@ struct FinishArgs {
 };
 
 hipError_t launch_finish(const FinishArgs &a, hipStream_t s);
+// Small-batch path: from the block minima [b, nb] and the per-group minima to the outputs (takes
+// a.r blocks).  blocks [16, kMaxRescore] int32, nblk [16] int32 and cand are scratch
+// (skinny_finish_workspace_bytes covers the three).
+size_t skinny_finish_workspace_bytes(int r, size_t align);
+hipError_t launch_skinny_finish(const FinishArgs &a, const uint64_t *bmin, const uint64_t *wgmin, int64_t nb,
+                                int n_groups, int n_tiles, int32_t *blocks, int32_t *nblk, uint64_t *cand, hipStream_t s);
 
 hipError_t launch_compact(const uint8_t *hit, const int32_t *sel_in, const int32_t *count_in, int64_t count_max,
                           int32_t *sel_out, int32_t *count_out, int64_t *hits_out, hipStream_t s);
