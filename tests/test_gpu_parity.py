@@ -76,6 +76,10 @@ def test_hand_example_on_gpu():
     (20000, 512, 8, 20, 0, torch.bfloat16),    # small-batch kernel, many tiles per workgroup
     (5000, 1024, 16, 10, 0, torch.bfloat16),   # small-batch kernel, longest supported activation
     (3000, 960, 3, 5, 0, torch.float32),       # small-batch kernel, fp32 cache, d not a multiple of 64
+    (5000, 512, 4, 40, 0, torch.bfloat16),     # small-batch kernel, R = 64 and k > 32: the selection's fallbacks
+    (3000, 100, 2, 5, 0, torch.float32),       # small-batch kernel, d not a multiple of 8
+    (2000, 128, 5, 10, 0, torch.bfloat16),     # small-batch kernel, fewer workgroups than blocks to take
+    (70000, 256, 16, 10, 0, torch.bfloat16),   # small-batch kernel, one tile per workgroup
     (3000, 1100, 3, 5, 0, torch.bfloat16),     # d too long for the small-batch kernel -> tiled kernel
     (3000, 2048, 100, 10, 0, torch.bfloat16),  # one query tile, long activation -> keys-out kernel + selection
     (2500, 4160, 200, 10, 64, torch.float32),  # keys-out, R = 64, fp32 cache, ragged everything
