@@ -105,7 +105,69 @@ struct DistKernelArgs {
     float *keys;      // [b_pad, n_pad]
     uint64_t *bmin;   // [b_pad, n_pad / 32]
     int64_t n_pad;
+    // stream-K (keys-out variant, one query tile): workgroup x owns k-steps [x sk_len, (x+1) sk_len)
+    // of the flattened (cache tile, k-step) space and leaves its accumulators, one slot per tile
+    // it touches, in `partial`; 0 = off.
+    float *partial;   // [workgroups * sk_slots] slots of BM x BN fp32 in fragment order
+    int sk_len, sk_slots;
 };
+
+// Epilogue of the keys-out variant: every key of the tile and the minimum of every block of 32
+// entries.  Keys pass through the LDS slab so that the global stores are whole 512-byte row pieces.
+template <class C>
+__device__ __forceinline__ void keys_epilogue(f32x16 (&acc)[C::TM][C::TN], const DistKernelArgs &p, float *slab, int mt,
+                                              int n0, int nq, int w, int wm, int wn, int lane)
+{
+    constexpr int BM = C::BM, TM = C::TM, TN = C::TN;
+    const int g = lane >> 5;
+    static_assert(!C::KEYS || C::WNS == C::WN, "keys-out epilogue: one slab pass covers all wave columns");
+#pragma unroll
+    for (int bj = 0; bj < TN; ++bj) {
+        {
+            const int col = n0 + wn * TN * 32 + bj * 32 + (lane & 31);
+            const float nrm = p.norm[col];   // col < n_pad always
+            const int sc = wn * 32 + (lane & 31);
+#pragma unroll
+            for (int bi = 0; bi < TM; ++bi) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                    slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] =
+                        __builtin_fmaf(-2.f, acc[bi][bj][e], nrm);
+                }
+            }
+        }
+        __syncthreads();
+        // half-wave h of wave w copies row it*2*NWAVES + 2w + h: 32 lanes x 4 keys = the slab's 128 columns
+        const int l32 = lane & 31;
+        const int seg = l32 >> 3;                                   // wave column the 4 keys came from
+        const int gcol = n0 + seg * TN * 32 + bj * 32 + (l32 & 7) * 4;   // entry index of the first key
+#pragma unroll 2
+        for (int it = 0; it < BM / (2 * C::NWAVES); ++it) {
+            const int row = it * 2 * C::NWAVES + w * 2 + g;
+            const int grow = mt * BM + row;
+            const f32x4 v = reinterpret_cast<const f32x4 *>(slab + row * C::SLABW)[(l32 ^ row) & (C::SLABW / 4 - 1)];
+            const bool live = grow < nq;
+            if (live) *reinterpret_cast<f32x4 *>(p.keys + (size_t)grow * p.n_pad + gcol) = v;
+            // minimum (key, index) pair of the 32-entry block: 4 own keys, then the 8 lanes of the block
+            uint64_t mn = ((uint64_t)ordered_bits(v[0]) << 32) | (uint32_t)gcol;
+#pragma unroll
+            for (int e = 1; e < 4; ++e) {
+                const uint64_t pr = ((uint64_t)ordered_bits(v[e]) << 32) | (uint32_t)(gcol + e);
+                mn = pr < mn ? pr : mn;
+            }
+#pragma unroll
+            for (int off = 4; off >= 1; off >>= 1) {
+                const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)mn, off, 64);
+                const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(mn >> 32), off, 64);
+                const uint64_t o = ((uint64_t)hi << 32) | lo;
+                mn = o < mn ? o : mn;
+            }
+            if (live && (l32 & 7) == 0) p.bmin[(size_t)grow * (p.n_pad / 32) + (gcol >> 5)] = mn;
+        }
+        __syncthreads();
+    }
+}
 
 template <class C>
 __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
@@ -125,7 +187,8 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     const int nq = p.count ? *p.count : p.b;
     const int live_mt = (nq + BM - 1) / BM;
     const int n_splits = p.count ? splits_for(live_mt, p.n_tiles, p.num_cus, p.max_splits) : p.n_splits;
-    const int units = live_mt * n_splits;
+    const bool stream_k = C::KEYS && p.sk_len > 0;
+    const int units = stream_k ? (int)gridDim.x : live_mt * n_splits;
     if ((int)blockIdx.x >= units) return;   // uniform per workgroup, before any barrier
     // XCD-aware unit numbering: blocks with equal (id % 8) run on one XCD; give them a contiguous
     // range of units.  units = 8a + rem: XCD x owns a (+1 if x < rem) consecutive units.
@@ -135,7 +198,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
         unit = x * a + (x < rem ? x : rem) + j;
     }
-    const int mt = unit / n_splits, sp = unit % n_splits;
+    const int mt = stream_k ? 0 : unit / n_splits, sp = stream_k ? 0 : unit % n_splits;
     const int nt0 = (int)(((int64_t)sp * p.n_tiles) / n_splits);
     const int nt1 = (int)(((int64_t)(sp + 1) * p.n_tiles) / n_splits);
     const int r = p.r;
@@ -166,7 +229,19 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     const int rdB = rowB * 4, pcxB = g ^ tiled_chunk_swizzle(rowB);
     const int nk = p.d_pad / BK;
 
-    for (int nt = nt0; nt < nt1; ++nt) {
+    // The workgroup walks segments (cache tile, range of k-steps) of the flattened space: whole
+    // tiles nt0 .. nt1-1, or under stream-K the k-steps [x sk_len, (x+1) sk_len) whatever tiles
+    // they fall in.
+    const int64_t g_end = stream_k ? ((int64_t)(blockIdx.x + 1) * p.sk_len < (int64_t)p.n_tiles * nk
+                                          ? (int64_t)(blockIdx.x + 1) * p.sk_len
+                                          : (int64_t)p.n_tiles * nk)
+                                   : (int64_t)nt1 * nk;
+    int seg = 0;
+    for (int64_t gk = stream_k ? (int64_t)blockIdx.x * p.sk_len : (int64_t)nt0 * nk; gk < g_end; ++seg) {
+        const int nt = (int)(gk / nk);
+        const int ka = (int)(gk - (int64_t)nt * nk);                               // first k-step of the segment
+        const int kb = (g_end - gk < nk - ka) ? ka + (int)(g_end - gk) : nk;     // one past its last
+        gk += kb - ka;
         const int n0 = nt * BN;
         const uint64_t gB = uniform_u64((uint64_t)(uintptr_t)p.c_bf + (size_t)nt * BN * tile_row_bytes);
         // one instruction of a stage's fill: l < NI_A -> A image, else B image
@@ -209,7 +284,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 #pragma unroll
             for (int ps = 0; ps < C::NS; ++ps)
 #pragma unroll
-                for (int l = 0; l < (ps == C::NS - 1 ? LB : C::LPS); ++l) issue_one(ps, ps < nk ? ps : nk - 1, l);
+                for (int l = 0; l < (ps == C::NS - 1 ? LB : C::LPS); ++l) issue_one(ps, ka + ps < kb ? ka + ps : kb - 1, l);
             wait_global_loads_le<(C::NS - 2) * C::LPS + LB>();
             __syncthreads();
             bf16x8 af[2][TM], bfr[2][TN];
@@ -224,11 +299,11 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 #pragma unroll
             for (int rr = 0; rr < NR; ++rr) read_frag(0, 0, 0, rr);
             int st = 0;
-            for (int kt = 0; kt < nk; ++kt) {
+            for (int kt = ka; kt < kb; ++kt) {
                 const int nst = (st + 1 == C::NS) ? 0 : st + 1;
                 const int pst = (st == 0) ? C::NS - 1 : st - 1;
-                const int fill_kt = kt + C::NS < nk ? kt + C::NS : nk - 1;
-                const int pfill_kt = kt + C::NS - 1 < nk ? kt + C::NS - 1 : nk - 1;   // the stage freed one step ago
+                const int fill_kt = kt + C::NS < kb ? kt + C::NS : kb - 1;
+                const int pfill_kt = kt + C::NS - 1 < kb ? kt + C::NS - 1 : kb - 1;   // the stage freed one step ago
 #pragma unroll
                 for (int kk = 0; kk < KS - 1; ++kk) {
 #pragma unroll
@@ -271,55 +346,21 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         __syncthreads();   // operand LDS is free: the slab may overwrite it
 
         if constexpr (C::KEYS) {
-            // ---- epilogue (keys-out): every key and the minimum of every block of 32 entries ----
-            // Keys pass through the LDS slab so that the global stores are whole 512-byte row pieces.
-            static_assert(!C::KEYS || C::WNS == C::WN, "keys-out epilogue: one slab pass covers all wave columns");
+            if (p.sk_len > 0) {
+                // stream-K: leave the accumulators of this (tile, k-range) in the workgroup's next slot
+                f32x4 *dst = reinterpret_cast<f32x4 *>(p.partial) +
+                             ((size_t)blockIdx.x * p.sk_slots + seg) * (size_t)(BM * BN / 4);
 #pragma unroll
-            for (int bj = 0; bj < TN; ++bj) {
-                {
-                    const int col = n0 + wn * TN * 32 + bj * 32 + (lane & 31);
-                    const float nrm = p.norm[col];   // col < n_pad always
-                    const int sc = wn * 32 + (lane & 31);
+                for (int bi = 0; bi < TM; ++bi)
 #pragma unroll
-                    for (int bi = 0; bi < TM; ++bi) {
+                    for (int bj = 0; bj < TN; ++bj)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) {
-                            const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-                            slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] =
-                                __builtin_fmaf(-2.f, acc[bi][bj][e], nrm);
-                        }
-                    }
-                }
-                __syncthreads();
-                // half-wave h of wave w copies row it*2*NWAVES + 2w + h: 32 lanes x 4 keys = the slab's 128 columns
-                const int l32 = lane & 31;
-                const int seg = l32 >> 3;                                   // wave column the 4 keys came from
-                const int gcol = n0 + seg * TN * 32 + bj * 32 + (l32 & 7) * 4;   // entry index of the first key
-#pragma unroll 2
-                for (int it = 0; it < BM / (2 * C::NWAVES); ++it) {
-                    const int row = it * 2 * C::NWAVES + w * 2 + g;
-                    const int grow = mt * BM + row;
-                    const f32x4 v = reinterpret_cast<const f32x4 *>(slab + row * C::SLABW)[(l32 ^ row) & (C::SLABW / 4 - 1)];
-                    const bool live = grow < nq;
-                    if (live) *reinterpret_cast<f32x4 *>(p.keys + (size_t)grow * p.n_pad + gcol) = v;
-                    // minimum (key, index) pair of the 32-entry block: 4 own keys, then the 8 lanes of the block
-                    uint64_t mn = ((uint64_t)ordered_bits(v[0]) << 32) | (uint32_t)gcol;
-#pragma unroll
-                    for (int e = 1; e < 4; ++e) {
-                        const uint64_t pr = ((uint64_t)ordered_bits(v[e]) << 32) | (uint32_t)(gcol + e);
-                        mn = pr < mn ? pr : mn;
-                    }
-#pragma unroll
-                    for (int off = 4; off >= 1; off >>= 1) {
-                        const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)mn, off, 64);
-                        const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(mn >> 32), off, 64);
-                        const uint64_t o = ((uint64_t)hi << 32) | lo;
-                        mn = o < mn ? o : mn;
-                    }
-                    if (live && (l32 & 7) == 0) p.bmin[(size_t)grow * (p.n_pad / 32) + (gcol >> 5)] = mn;
-                }
-                __syncthreads();
+                        for (int e4 = 0; e4 < 4; ++e4)
+                            dst[(((w * TM + bi) * TN + bj) * 4 + e4) * 64 + lane] =
+                                f32x4{acc[bi][bj][4 * e4], acc[bi][bj][4 * e4 + 1], acc[bi][bj][4 * e4 + 2], acc[bi][bj][4 * e4 + 3]};
+                continue;
             }
+            keys_epilogue<C>(acc, p, slab, mt, n0, nq, w, wm, wn, lane);
             continue;
         }
         // ---- epilogue: fold this tile into the per-row top-R lists ----
@@ -414,7 +455,48 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     }
 }
 
-DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out)
+// Stream-K second pass (keys-out variant): per cache tile, add up the accumulators the
+// workgroups of the first pass left for it (in workgroup order: a fixed order of additions), then
+// the usual epilogue.  One workgroup per tile, same wave layout as the first pass.
+template <class C>
+__global__ __launch_bounds__(C::THREADS) void keys_fixup_kernel(DistKernelArgs p)
+{
+    constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[BM * C::SLABW * 4];
+    float *slab = reinterpret_cast<float *>(smem);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w / C::WN, wn = w % C::WN;
+    const int nt = blockIdx.x;
+    const int nk = p.d_pad / C::BK;
+    const int64_t g0 = (int64_t)nt * nk, g1 = g0 + nk;
+    const int w_first = (int)(g0 / p.sk_len), w_last = (int)((g1 - 1) / p.sk_len);
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    for (int x = w_first; x <= w_last; ++x) {
+        const int seg = nt - (int)(((int64_t)x * p.sk_len) / nk);   // tiles workgroup x touched before this one
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(p.partial) + ((size_t)x * p.sk_slots + seg) * (size_t)(BM * BN / 4);
+#pragma unroll
+        for (int bi = 0; bi < TM; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < TN; ++bj)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const f32x4 v = src[(((w * TM + bi) * TN + bj) * 4 + e4) * 64 + lane];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[bi][bj][4 * e4 + e] += v[e];
+                }
+    }
+    const int nq = p.count ? *p.count : p.b;
+    keys_epilogue<C>(acc, p, slab, 0, nt * BN, nq, w, wm, wn, lane);
+}
+
+DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out, int64_t d_pad)
 {
     DistPlan pl{};
     pl.variant = keys_out ? 3 : (r <= 16 ? 0 : (r <= 32 ? 1 : 2));
@@ -435,7 +517,26 @@ DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out)
         if (s > pl.alloc_splits) pl.alloc_splits = s;
         if (live * s > pl.grid_units) pl.grid_units = live * s;
     }
+    // Stream-K for the keys-out variant when whole tiles fill the CUs badly (196 tiles on 256 CUs
+    // leave a quarter of the chip idle) and a tile is long enough to be worth cutting.
+    pl.sk_wgs = pl.sk_len = pl.sk_slots = 0;
+    if (keys_out && pl.m_tiles == 1 && d_pad >= 64 * 32) {
+        const int nk = (int)(d_pad / 32);   // k-steps per tile of the keys-out variant
+        const int rounds = (pl.n_tiles + num_cus - 1) / num_cus;
+        const double fill = (double)pl.n_tiles / ((double)rounds * num_cus);
+        if (fill < 0.9 && rounds <= 4 && pl.n_tiles * 2 > num_cus) {
+            const int64_t total = (int64_t)pl.n_tiles * nk;
+            pl.sk_wgs = num_cus;
+            pl.sk_len = (int)((total + num_cus - 1) / num_cus);
+            pl.sk_slots = (pl.sk_len - 1) / nk + 2;
+        }
+    }
     return pl;
+}
+
+size_t dist_partial_bytes(const DistPlan &plan)
+{
+    return (size_t)plan.sk_wgs * plan.sk_slots * (size_t)plan.bm * kTileN * 4;
 }
 
 template <class C>
@@ -460,6 +561,19 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
     k.keys = a.keys;
     k.bmin = a.bmin;
     k.n_pad = (int64_t)plan.n_tiles * kTileN;
+    if constexpr (C::KEYS) {
+        if (plan.sk_wgs > 0) {
+            if (!a.partial || a.count || plan.m_tiles != 1) return hipErrorInvalidValue;
+            k.partial = a.partial;
+            k.sk_len = plan.sk_len;
+            k.sk_slots = plan.sk_slots;
+            hipLaunchKernelGGL((dist_topr_kernel<C>), dim3(plan.sk_wgs), dim3(C::THREADS), 0, s, k);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL((keys_fixup_kernel<C>), dim3(plan.n_tiles), dim3(C::THREADS), 0, s, k);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL((dist_topr_kernel<C>), dim3(grid), dim3(C::THREADS), 0, s, k);
     return hipGetLastError();
 }

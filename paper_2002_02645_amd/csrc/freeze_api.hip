@@ -95,10 +95,11 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
         // is cheap next to the cache stream (2 d B per entry), lets the tile be 256 queries wide for
         // any R, and keeps the selection out of the streaming kernel.
         out->keys = !cascade && b <= 256 && b * 20 <= L.d_pad && select_supported(L.n_pad, r);
-        out->plan = plan_dist(b, L.n, r, ctx->num_cus, out->keys);
+        out->plan = plan_dist(b, L.n, r, ctx->num_cus, out->keys, L.d_pad);
         out->ws_bytes = align_up((size_t)out->plan.b_pad * L.d_pad * 2);
         if (out->keys)
-            out->ws_bytes += select_workspace_bytes(out->plan.b_pad, L.n_pad, r, kAlign);
+            out->ws_bytes += select_workspace_bytes(out->plan.b_pad, L.n_pad, r, kAlign) +
+                             align_up(dist_partial_bytes(out->plan));
         else
             out->ws_bytes += align_up((size_t)out->plan.b_pad * (cascade ? out->plan.alloc_splits : out->plan.n_splits) * r * 8);
     }
@@ -217,6 +218,7 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
             uint64_t *tau = ws.take<uint64_t>(rows);
             int32_t *cand_count = ws.take<int32_t>(rows);
             uint64_t *cand = ws.take<uint64_t>(rows * 32 * sh.r);
+            da.partial = sh.plan.sk_wgs > 0 ? ws.take<float>(dist_partial_bytes(sh.plan) / 4) : nullptr;
             if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
             marks.mark(2);
             marked2 = true;

@@ -94,9 +94,16 @@ struct DistPlan {
     int max_splits;     // cap on n_splits (merge capacity)
     int num_cus;
     int64_t b_pad;  // m_tiles * bm
+    // stream-K (keys-out variant, one query tile, cache tiles that fill the CUs badly): sk_wgs
+    // workgroups each take sk_len consecutive k-steps of the flattened (cache tile, k-step) space
+    // and leave their accumulators in up to sk_slots slots; a second kernel adds them up per
+    // tile and emits the keys.  sk_wgs == 0: off.
+    int sk_wgs, sk_len, sk_slots;
 };
 
-DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out);
+// d_pad decides stream-K for the keys-out variant (pass 0 to leave it off).
+DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out, int64_t d_pad = 0);
+size_t dist_partial_bytes(const DistPlan &plan);   // stream-K accumulator slots (0 when off)
 
 struct DistArgs {
     const uint16_t *q_bf;   // b_pad x d_pad, tiled layout (tiles of plan.bm rows)
@@ -105,6 +112,7 @@ struct DistArgs {
     uint64_t *part;         // [b_pad, alloc_splits, r] packed (ordered key, index) (fused variants)
     float *keys;            // [b_pad, n_pad] every key (keys-out variant)
     uint64_t *bmin;         // [b_pad, n_pad / 32] block minima (keys-out variant)
+    float *partial;         // dist_partial_bytes(plan) bytes of scratch (keys-out variant under stream-K)
     const int32_t *count;   // device: number of live queries, or null (= b)
     int b;
     int n;

@@ -84,6 +84,8 @@ def test_hand_example_on_gpu():
     (3000, 2048, 100, 10, 0, torch.bfloat16),  # one query tile, long activation -> keys-out kernel + selection
     (2500, 4160, 200, 10, 64, torch.float32),  # keys-out, R = 64, fp32 cache, ragged everything
     (1000, 640, 20, 5, 0, torch.bfloat16),     # keys-out with few cache tiles
+    (50000, 2048, 64, 10, 0, torch.bfloat16),  # keys-out, 196 cache tiles on 256 CUs: stream-K over (tile, k-step)
+    (36000, 2080, 100, 10, 64, torch.float32), # stream-K, ragged d, workgroup ranges that span three tiles' parts
     (600, 16384, 40, 10, 0, torch.bfloat16),   # long activation, few queries: 1024-thread finishing blocks
     (600, 16392, 300, 10, 0, torch.float32),   # fused kernel, fp32 cache, long activation, d not a multiple of 64
 ])
