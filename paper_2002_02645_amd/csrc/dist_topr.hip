@@ -110,6 +110,10 @@ struct DistKernelArgs {
     // it touches, in `partial`; 0 = off.
     float *partial;   // [workgroups * sk_slots] slots of BM x BN fp32 in fragment order
     int sk_len, sk_slots;
+    // balanced decomposition (fused variants, host-side count): bal_f workgroups per query tile
+    // share cache tiles [0, bal_nfull) and the remaining workgroups of the grid share what is
+    // left of all query tiles; 0 = off.
+    int bal_f, bal_nfull;
 };
 
 // Epilogue of the keys-out variant: every key of the tile and the minimum of every block of 32
@@ -188,8 +192,9 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
     const int live_mt = (nq + BM - 1) / BM;
     const int n_splits = p.count ? splits_for(live_mt, p.n_tiles, p.num_cus, p.max_splits) : p.n_splits;
     const bool stream_k = C::KEYS && p.sk_len > 0;
-    const int units = stream_k ? (int)gridDim.x : live_mt * n_splits;
-    if ((int)blockIdx.x >= units) return;   // uniform per workgroup, before any barrier
+    const bool balanced = !C::KEYS && p.bal_f > 0;
+    const int units = stream_k ? (int)gridDim.x : (balanced ? live_mt * p.bal_f : live_mt * n_splits);
+    if (!balanced && (int)blockIdx.x >= units) return;   // uniform per workgroup, before any barrier
     // XCD-aware unit numbering: blocks with equal (id % 8) run on one XCD; give them a contiguous
     // range of units.  units = 8a + rem: XCD x owns a (+1 if x < rem) consecutive units.
     int unit;
@@ -198,261 +203,307 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
         unit = x * a + (x < rem ? x : rem) + j;
     }
-    const int mt = stream_k ? 0 : unit / n_splits, sp = stream_k ? 0 : unit % n_splits;
-    const int nt0 = (int)(((int64_t)sp * p.n_tiles) / n_splits);
-    const int nt1 = (int)(((int64_t)(sp + 1) * p.n_tiles) / n_splits);
     const int r = p.r;
-
-    // per-row selection state lives with thread t (< BM)
-    uint64_t curmax = kSentinel;
-    int maxpos = 0;
-    float tau = __builtin_inff();
-    if constexpr (!C::KEYS) {
-        if (tid < BM) {
-#pragma unroll
-            for (int i = 0; i < C::RMAX; ++i) top[i * BM + tid] = kSentinel;
-        }
-    }
-
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void_ptr)smem;
     const size_t tile_row_bytes = (size_t)p.d_pad * 2;   // bytes of one row; a tile of T rows holds T * this
-
-    // Direct loads copy a stage linearly: wave w, instruction i moves the 1 KiB at offset
-    // (i * NWAVES + w) * 1024 of the stage's A (or B) image; lane l moves 16 bytes at + 16 l.
-    const uint64_t gA = uniform_u64((uint64_t)(uintptr_t)p.q_bf + (size_t)mt * BM * tile_row_bytes);
     const uint32_t lane_off = w * 1024 + lane * 16;
-    // fragment read addresses, in 16-byte units relative to the stage's A / B image
-    const int g = lane >> 5;
-    const int rowA = wm * TM * 32 + (lane & 31);
-    const int rowB = wn * TN * 32 + (lane & 31);
-    const int rdA = rowA * 4, pcxA = g ^ tiled_chunk_swizzle(rowA);
-    const int rdB = rowB * 4, pcxB = g ^ tiled_chunk_swizzle(rowB);
-    const int nk = p.d_pad / BK;
 
-    // The workgroup walks segments (cache tile, range of k-steps) of the flattened space: whole
-    // tiles nt0 .. nt1-1, or under stream-K the k-steps [x sk_len, (x+1) sk_len) whatever tiles
-    // they fall in.
-    const int64_t g_end = stream_k ? ((int64_t)(blockIdx.x + 1) * p.sk_len < (int64_t)p.n_tiles * nk
-                                          ? (int64_t)(blockIdx.x + 1) * p.sk_len
-                                          : (int64_t)p.n_tiles * nk)
-                                   : (int64_t)nt1 * nk;
-    int seg = 0;
-    for (int64_t gk = stream_k ? (int64_t)blockIdx.x * p.sk_len : (int64_t)nt0 * nk; gk < g_end; ++seg) {
-        const int nt = (int)(gk / nk);
-        const int ka = (int)(gk - (int64_t)nt * nk);                               // first k-step of the segment
-        const int kb = (g_end - gk < nk - ka) ? ka + (int)(g_end - gk) : nk;     // one past its last
-        gk += kb - ka;
-        const int n0 = nt * BN;
-        const uint64_t gB = uniform_u64((uint64_t)(uintptr_t)p.c_bf + (size_t)nt * BN * tile_row_bytes);
-        // one instruction of a stage's fill: l < NI_A -> A image, else B image
-        auto issue_one = [&](int stage, int kt, int l) {
-            const uint32_t sbase = smem_base + stage * C::STAGE_BYTES + w * 1024;
-            if (l < C::NI_A)
-                load16_global_to_lds(gA + (size_t)kt * C::A_BYTES + l * (C::NWAVES * 1024), lane_off,
-                                     sbase + l * (C::NWAVES * 1024));
-            else
-                load16_global_to_lds(gB + (size_t)kt * (BN * BK * 2) + (l - C::NI_A) * (C::NWAVES * 1024), lane_off,
-                                     sbase + C::A_BYTES + (l - C::NI_A) * (C::NWAVES * 1024));
-        };
+    // A workgroup handles one part (query tile, range of cache tiles, output list slot), except
+    // under the balanced decomposition: there bal_f workgroups per query tile cut cache tiles
+    // [0, bal_nfull) evenly, and the grid's remaining workgroups cut the flattened remainder
+    // (query tile, cache tile >= bal_nfull) evenly, so that one of them may serve the tail of one
+    // query tile and the head of the next.  A query tile's remainder lies in at most two of them:
+    // the first writes list slot bal_f, the second bal_f + 1 (filled with "no entry" by the first
+    // when there is no second).
+    const int w_full = live_mt * p.bal_f;
+    const int lo = p.n_tiles - p.bal_nfull;   // remainder tiles per query tile (balanced only)
+    int rem_c = 0, rem_end = 0;               // this workgroup's range of the flattened remainder
+    if (balanced && (int)blockIdx.x >= w_full) {
+        const int64_t total_lo = (int64_t)live_mt * lo;
+        const int lw = (int)gridDim.x - w_full, i = (int)blockIdx.x - w_full;
+        rem_c = (int)(total_lo * i / lw);
+        rem_end = (int)(total_lo * (i + 1) / lw);
+    }
+    bool first_part = true;
+    while (true) {
+        int mt, nt0, nt1, slot;
+        bool clear_next_slot = false;
+        if (balanced && (int)blockIdx.x >= w_full) {
+            if (rem_c >= rem_end) break;
+            mt = rem_c / lo;
+            const int off = rem_c - mt * lo;
+            const int len = (lo - off < rem_end - rem_c) ? lo - off : rem_end - rem_c;
+            nt0 = p.bal_nfull + off;
+            nt1 = nt0 + len;
+            slot = p.bal_f + (off == 0 ? 0 : 1);
+            clear_next_slot = (off == 0 && len == lo);
+            rem_c += len;
+        } else {
+            if (!first_part) break;
+            if (balanced) {
+                mt = unit / p.bal_f;
+                slot = unit % p.bal_f;
+                nt0 = (int)(((int64_t)slot * p.bal_nfull) / p.bal_f);
+                nt1 = (int)(((int64_t)(slot + 1) * p.bal_nfull) / p.bal_f);
+            } else {
+                mt = stream_k ? 0 : unit / n_splits;
+                slot = stream_k ? 0 : unit % n_splits;
+                nt0 = (int)(((int64_t)slot * p.n_tiles) / n_splits);
+                nt1 = (int)(((int64_t)(slot + 1) * p.n_tiles) / n_splits);
+            }
+        }
+        first_part = false;
 
-        f32x16 acc[TM][TN];
+        // per-row selection state lives with thread t (< BM)
+        uint64_t curmax = kSentinel;
+        int maxpos = 0;
+        float tau = __builtin_inff();
+        if constexpr (!C::KEYS) {
+            if (tid < BM) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                for (int i = 0; i < C::RMAX; ++i) top[i * BM + tid] = kSentinel;
+            }
+        }
 
-        {
-            // Software-pipelined loop.  Invariant at the top of k-step kt: the fragments of its first
-            // sub-step are in (or on their way to) register buffer 0; k-blocks kt+1 .. kt+NS-1 are in
-            // flight or landed in the other stages.  Before the last sub-step every read of the
-            // current stage has been issued, so the step's only barrier goes there: it publishes the
-            // next stage (each wave waited for its own part) and frees the current one.  The MFMAs of
-            // the last sub-step need nothing newer, so the matrix pipe restarts at once, and the next
-            // stage's first fragments and the refill of the freed stage are issued one by one between
-            // them: a wave blocks while the memory pipeline accepts a load, so loads issued back to
-            // back stall the MFMAs behind them.  Past the last k-block the refills repeat it (never
-            // read): the loop body and the count of outstanding loads stay uniform.
-            constexpr int KS = BK / 16;           // sub-steps (one 16-deep MFMA layer each)
-            constexpr int NR = TM + TN;           // fragment reads per sub-step
-            // A stage's LPS loads are issued in two parts: LB of them between the MFMAs of the last
-            // sub-step of the k-step that frees the stage, the rest between the MFMAs of the following
-            // k-step's other sub-steps, so that loads leave at an even rate.
-            constexpr int LB = C::LPS / KS;
-            constexpr int G1 = (KS - 1) * TM;     // MFMA groups (of TN) before the last sub-step
-#pragma unroll
-            for (int ps = 0; ps < C::NS; ++ps)
-#pragma unroll
-                for (int l = 0; l < (ps == C::NS - 1 ? LB : C::LPS); ++l) issue_one(ps, ka + ps < kb ? ka + ps : kb - 1, l);
-            wait_global_loads_le<(C::NS - 2) * C::LPS + LB>();
-            __syncthreads();
-            bf16x8 af[2][TM], bfr[2][TN];
-            auto read_frag = [&](int buf, int stage, int kk, int rr) {   // rr < TM: A block rr, else B block rr - TM
-                if (rr < TM)
-                    af[buf][rr] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + (kk >> 1) * (BM * 4) + rr * 128 +
-                                         (((kk & 1) << 1) ^ pcxA)];
+        // Direct loads copy a stage linearly: wave w, instruction i moves the 1 KiB at offset
+        // (i * NWAVES + w) * 1024 of the stage's A (or B) image; lane l moves 16 bytes at + 16 l.
+        const uint64_t gA = uniform_u64((uint64_t)(uintptr_t)p.q_bf + (size_t)mt * BM * tile_row_bytes);
+        // fragment read addresses, in 16-byte units relative to the stage's A / B image
+        const int g = lane >> 5;
+        const int rowA = wm * TM * 32 + (lane & 31);
+        const int rowB = wn * TN * 32 + (lane & 31);
+        const int rdA = rowA * 4, pcxA = g ^ tiled_chunk_swizzle(rowA);
+        const int rdB = rowB * 4, pcxB = g ^ tiled_chunk_swizzle(rowB);
+        const int nk = p.d_pad / BK;
+
+        // The workgroup walks segments (cache tile, range of k-steps) of the flattened space: whole
+        // tiles nt0 .. nt1-1, or under stream-K the k-steps [x sk_len, (x+1) sk_len) whatever tiles
+        // they fall in.
+        const int64_t g_end = stream_k ? ((int64_t)(blockIdx.x + 1) * p.sk_len < (int64_t)p.n_tiles * nk
+                                              ? (int64_t)(blockIdx.x + 1) * p.sk_len
+                                              : (int64_t)p.n_tiles * nk)
+                                       : (int64_t)nt1 * nk;
+        int seg = 0;
+        for (int64_t gk = stream_k ? (int64_t)blockIdx.x * p.sk_len : (int64_t)nt0 * nk; gk < g_end; ++seg) {
+            const int nt = (int)(gk / nk);
+            const int ka = (int)(gk - (int64_t)nt * nk);                               // first k-step of the segment
+            const int kb = (g_end - gk < nk - ka) ? ka + (int)(g_end - gk) : nk;     // one past its last
+            gk += kb - ka;
+            const int n0 = nt * BN;
+            const uint64_t gB = uniform_u64((uint64_t)(uintptr_t)p.c_bf + (size_t)nt * BN * tile_row_bytes);
+            // one instruction of a stage's fill: l < NI_A -> A image, else B image
+            auto issue_one = [&](int stage, int kt, int l) {
+                const uint32_t sbase = smem_base + stage * C::STAGE_BYTES + w * 1024;
+                if (l < C::NI_A)
+                    load16_global_to_lds(gA + (size_t)kt * C::A_BYTES + l * (C::NWAVES * 1024), lane_off,
+                                         sbase + l * (C::NWAVES * 1024));
                 else
-                    bfr[buf][rr - TM] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB +
-                                               (kk >> 1) * (BN * 4) + (rr - TM) * 128 + (((kk & 1) << 1) ^ pcxB)];
+                    load16_global_to_lds(gB + (size_t)kt * (BN * BK * 2) + (l - C::NI_A) * (C::NWAVES * 1024), lane_off,
+                                         sbase + C::A_BYTES + (l - C::NI_A) * (C::NWAVES * 1024));
             };
+
+            f32x16 acc[TM][TN];
 #pragma unroll
-            for (int rr = 0; rr < NR; ++rr) read_frag(0, 0, 0, rr);
-            int st = 0;
-            for (int kt = ka; kt < kb; ++kt) {
-                const int nst = (st + 1 == C::NS) ? 0 : st + 1;
-                const int pst = (st == 0) ? C::NS - 1 : st - 1;
-                const int fill_kt = kt + C::NS < kb ? kt + C::NS : kb - 1;
-                const int pfill_kt = kt + C::NS - 1 < kb ? kt + C::NS - 1 : kb - 1;   // the stage freed one step ago
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int kk = 0; kk < KS - 1; ++kk) {
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int rr = 0; rr < NR; ++rr) read_frag((kk + 1) & 1, st, kk + 1, rr);
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+            {
+                // Software-pipelined loop.  Invariant at the top of k-step kt: the fragments of its first
+                // sub-step are in (or on their way to) register buffer 0; k-blocks kt+1 .. kt+NS-1 are in
+                // flight or landed in the other stages.  Before the last sub-step every read of the
+                // current stage has been issued, so the step's only barrier goes there: it publishes the
+                // next stage (each wave waited for its own part) and frees the current one.  The MFMAs of
+                // the last sub-step need nothing newer, so the matrix pipe restarts at once, and the next
+                // stage's first fragments and the refill of the freed stage are issued one by one between
+                // them: a wave blocks while the memory pipeline accepts a load, so loads issued back to
+                // back stall the MFMAs behind them.  Past the last k-block the refills repeat it (never
+                // read): the loop body and the count of outstanding loads stay uniform.
+                constexpr int KS = BK / 16;           // sub-steps (one 16-deep MFMA layer each)
+                constexpr int NR = TM + TN;           // fragment reads per sub-step
+                // A stage's LPS loads are issued in two parts: LB of them between the MFMAs of the last
+                // sub-step of the k-step that frees the stage, the rest between the MFMAs of the following
+                // k-step's other sub-steps, so that loads leave at an even rate.
+                constexpr int LB = C::LPS / KS;
+                constexpr int G1 = (KS - 1) * TM;     // MFMA groups (of TN) before the last sub-step
+#pragma unroll
+                for (int ps = 0; ps < C::NS; ++ps)
+#pragma unroll
+                    for (int l = 0; l < (ps == C::NS - 1 ? LB : C::LPS); ++l) issue_one(ps, ka + ps < kb ? ka + ps : kb - 1, l);
+                wait_global_loads_le<(C::NS - 2) * C::LPS + LB>();
+                __syncthreads();
+                bf16x8 af[2][TM], bfr[2][TN];
+                auto read_frag = [&](int buf, int stage, int kk, int rr) {   // rr < TM: A block rr, else B block rr - TM
+                    if (rr < TM)
+                        af[buf][rr] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + (kk >> 1) * (BM * 4) + rr * 128 +
+                                             (((kk & 1) << 1) ^ pcxA)];
+                    else
+                        bfr[buf][rr - TM] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB +
+                                                   (kk >> 1) * (BN * 4) + (rr - TM) * 128 + (((kk & 1) << 1) ^ pcxB)];
+                };
+#pragma unroll
+                for (int rr = 0; rr < NR; ++rr) read_frag(0, 0, 0, rr);
+                int st = 0;
+                for (int kt = ka; kt < kb; ++kt) {
+                    const int nst = (st + 1 == C::NS) ? 0 : st + 1;
+                    const int pst = (st == 0) ? C::NS - 1 : st - 1;
+                    const int fill_kt = kt + C::NS < kb ? kt + C::NS : kb - 1;
+                    const int pfill_kt = kt + C::NS - 1 < kb ? kt + C::NS - 1 : kb - 1;   // the stage freed one step ago
+#pragma unroll
+                    for (int kk = 0; kk < KS - 1; ++kk) {
+#pragma unroll
+                        for (int rr = 0; rr < NR; ++rr) read_frag((kk + 1) & 1, st, kk + 1, rr);
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                            for (int j = 0; j < TN; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+                            __builtin_amdgcn_sched_barrier(0);
+                            const int gi = kk * TM + i;
+#pragma unroll
+                            for (int l = LB + gi * (C::LPS - LB) / G1; l < LB + (gi + 1) * (C::LPS - LB) / G1; ++l)
+                                issue_one(pst, pfill_kt, l);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                    wait_global_loads_le<(C::NS - 2) * C::LPS>();   // own part of k-block kt+1 has landed
+                    __syncthreads();                                // ... everyone's; and stage st is free
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int i = 0; i < TM; ++i) {
 #pragma unroll
                         for (int j = 0; j < TN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-                        __builtin_amdgcn_sched_barrier(0);
-                        const int gi = kk * TM + i;
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[(KS - 1) & 1][i], bfr[(KS - 1) & 1][j],
+                                                                               acc[i][j], 0, 0, 0);
+                        constexpr int RG = TM > 1 ? TM - 1 : 1;   // the reads go with the first TM-1 groups
 #pragma unroll
-                        for (int l = LB + gi * (C::LPS - LB) / G1; l < LB + (gi + 1) * (C::LPS - LB) / G1; ++l)
-                            issue_one(pst, pfill_kt, l);
+                        for (int rr = i * NR / RG; rr < (i + 1) * NR / RG && rr < NR && i < RG; ++rr) read_frag(0, nst, 0, rr);
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int l = i * LB / TM; l < (i + 1) * LB / TM; ++l) issue_one(st, fill_kt, l);
                         __builtin_amdgcn_sched_barrier(0);
                     }
+                    st = nst;
                 }
-                wait_global_loads_le<(C::NS - 2) * C::LPS>();   // own part of k-block kt+1 has landed
-                __syncthreads();                                // ... everyone's; and stage st is free
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[(KS - 1) & 1][i], bfr[(KS - 1) & 1][j],
-                                                                           acc[i][j], 0, 0, 0);
-                    constexpr int RG = TM > 1 ? TM - 1 : 1;   // the reads go with the first TM-1 groups
-#pragma unroll
-                    for (int rr = i * NR / RG; rr < (i + 1) * NR / RG && rr < NR && i < RG; ++rr) read_frag(0, nst, 0, rr);
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int l = i * LB / TM; l < (i + 1) * LB / TM; ++l) issue_one(st, fill_kt, l);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                st = nst;
+                wait_global_loads_le<0>();   // the refills past the last k-block
             }
-            wait_global_loads_le<0>();   // the refills past the last k-block
-        }
-        __syncthreads();   // operand LDS is free: the slab may overwrite it
+            __syncthreads();   // operand LDS is free: the slab may overwrite it
 
-        if constexpr (C::KEYS) {
-            if (p.sk_len > 0) {
-                // stream-K: leave the accumulators of this (tile, k-range) in the workgroup's next slot
-                f32x4 *dst = reinterpret_cast<f32x4 *>(p.partial) +
-                             ((size_t)blockIdx.x * p.sk_slots + seg) * (size_t)(BM * BN / 4);
+            if constexpr (C::KEYS) {
+                if (p.sk_len > 0) {
+                    // stream-K: leave the accumulators of this (tile, k-range) in the workgroup's next slot
+                    f32x4 *dst = reinterpret_cast<f32x4 *>(p.partial) +
+                                 ((size_t)blockIdx.x * p.sk_slots + seg) * (size_t)(BM * BN / 4);
 #pragma unroll
-                for (int bi = 0; bi < TM; ++bi)
+                    for (int bi = 0; bi < TM; ++bi)
 #pragma unroll
-                    for (int bj = 0; bj < TN; ++bj)
+                        for (int bj = 0; bj < TN; ++bj)
 #pragma unroll
-                        for (int e4 = 0; e4 < 4; ++e4)
-                            dst[(((w * TM + bi) * TN + bj) * 4 + e4) * 64 + lane] =
-                                f32x4{acc[bi][bj][4 * e4], acc[bi][bj][4 * e4 + 1], acc[bi][bj][4 * e4 + 2], acc[bi][bj][4 * e4 + 3]};
+                            for (int e4 = 0; e4 < 4; ++e4)
+                                dst[(((w * TM + bi) * TN + bj) * 4 + e4) * 64 + lane] =
+                                    f32x4{acc[bi][bj][4 * e4], acc[bi][bj][4 * e4 + 1], acc[bi][bj][4 * e4 + 2], acc[bi][bj][4 * e4 + 3]};
+                    continue;
+                }
+                keys_epilogue<C>(acc, p, slab, mt, n0, nq, w, wm, wn, lane);
                 continue;
             }
-            keys_epilogue<C>(acc, p, slab, mt, n0, nq, w, wm, wn, lane);
-            continue;
-        }
-        // ---- epilogue: fold this tile into the per-row top-R lists ----
+            // ---- epilogue: fold this tile into the per-row top-R lists ----
 #pragma unroll
-        for (int bj = 0; bj < TN; ++bj) {
+            for (int bj = 0; bj < TN; ++bj) {
 #pragma unroll 1
-            for (int wg = 0; wg < C::WN / C::WNS; ++wg) {
-                if (wn / C::WNS == wg) {
-                    const int col = n0 + wn * TN * 32 + bj * 32 + (lane & 31);
-                    const float nrm = p.norm[col];   // col < n_pad always
-                    const int sc = (wn % C::WNS) * 32 + (lane & 31);
+                for (int wg = 0; wg < C::WN / C::WNS; ++wg) {
+                    if (wn / C::WNS == wg) {
+                        const int col = n0 + wn * TN * 32 + bj * 32 + (lane & 31);
+                        const float nrm = p.norm[col];   // col < n_pad always
+                        const int sc = (wn % C::WNS) * 32 + (lane & 31);
 #pragma unroll
-                    for (int bi = 0; bi < TM; ++bi) {
+                        for (int bi = 0; bi < TM; ++bi) {
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) {
-                            const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-                            const float key = __builtin_fmaf(-2.f, acc[bi][bj][e], nrm);
-                            slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = key;
-                        }
-                    }
-                }
-                __syncthreads();
-                if (tid < BM) {
-                    const int t = tid;
-                    // First pass over the row: one bit per group of four columns whose smallest key
-                    // is not above the row's current R-th best (two min instructions and a compare
-                    // per four keys); almost every group fails once the list has filled.
-                    const f32x4 *srow = reinterpret_cast<const f32x4 *>(slab + t * C::SLABW);
-                    constexpr int NG = C::SLABW / 4;
-                    static_assert(NG <= 32, "one mask word");
-                    uint32_t gmask = 0;
-#pragma unroll 8
-                    for (int cg = 0; cg < NG; ++cg) {
-                        const f32x4 v = srow[(cg ^ t) & (NG - 1)];
-                        const float m = __builtin_fminf(__builtin_fminf(v[0], v[1]), __builtin_fminf(v[2], v[3]));
-                        gmask |= (uint32_t)(m <= tau) << cg;
-                    }
-                    // Second pass: the flagged groups give a bit per key that passes and is a real
-                    // cache entry (padding columns are not).
-                    uint64_t kmask[2] = {0, 0};
-                    while (gmask) {
-                        const int cg = __builtin_ctz(gmask);
-                        gmask &= gmask - 1;
-                        const f32x4 v = srow[(cg ^ t) & (NG - 1)];
-                        // the four keys share a 32-column segment: columns seg0 .. seg0+3 of the tile
-                        const int seg0 = (wg * C::WNS + (cg >> 3)) * TN * 32 + bj * 32 + ((cg & 7) << 2);
-                        const int lim = p.n - n0 - seg0;   // real cache entries iff e < lim
-                        uint64_t bits = 0;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) bits |= (uint64_t)((v[e] <= tau) && (e < lim)) << e;
-                        bits <<= (cg & 15) * 4;
-                        if (cg < 16)
-                            kmask[0] |= bits;
-                        else
-                            kmask[1] |= bits;
-                    }
-                    // Third pass: one insertion attempt per surviving key, against the threshold as it tightens.
-#pragma unroll
-                    for (int m = 0; m < (NG + 15) / 16; ++m) {
-                        uint64_t mk = kmask[m];
-                        while (mk) {
-                            const int sc = m * 64 + __builtin_ctzll(mk);
-                            mk &= mk - 1;
-                            const float key = slab[t * C::SLABW + ((((sc >> 2) ^ t) & (NG - 1)) << 2) + (sc & 3)];
-                            const int tilecol = (wg * C::WNS + sc / 32) * TN * 32 + bj * 32 + (sc & 31);
-                            const uint64_t ent = ((uint64_t)ordered_bits(key) << 32) | (uint32_t)(n0 + tilecol);
-                            if (ent < curmax) {
-                                top[maxpos * BM + t] = ent;
-                                curmax = 0;
-#pragma unroll
-                                for (int i = 0; i < C::RMAX; ++i) {
-                                    if (i < r) {
-                                        const uint64_t u = top[i * BM + t];
-                                        if (u >= curmax) { curmax = u; maxpos = i; }
-                                    }
-                                }
-                                tau = (curmax == kSentinel) ? __builtin_inff() : from_ordered_bits((uint32_t)(curmax >> 32));
+                            for (int e = 0; e < 16; ++e) {
+                                const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                                const float key = __builtin_fmaf(-2.f, acc[bi][bj][e], nrm);
+                                slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = key;
                             }
                         }
                     }
+                    __syncthreads();
+                    if (tid < BM) {
+                        const int t = tid;
+                        // First pass over the row: one bit per group of four columns whose smallest key
+                        // is not above the row's current R-th best (two min instructions and a compare
+                        // per four keys); almost every group fails once the list has filled.
+                        const f32x4 *srow = reinterpret_cast<const f32x4 *>(slab + t * C::SLABW);
+                        constexpr int NG = C::SLABW / 4;
+                        static_assert(NG <= 32, "one mask word");
+                        uint32_t gmask = 0;
+#pragma unroll 8
+                        for (int cg = 0; cg < NG; ++cg) {
+                            const f32x4 v = srow[(cg ^ t) & (NG - 1)];
+                            const float m = __builtin_fminf(__builtin_fminf(v[0], v[1]), __builtin_fminf(v[2], v[3]));
+                            gmask |= (uint32_t)(m <= tau) << cg;
+                        }
+                        // Second pass: the flagged groups give a bit per key that passes and is a real
+                        // cache entry (padding columns are not).
+                        uint64_t kmask[2] = {0, 0};
+                        while (gmask) {
+                            const int cg = __builtin_ctz(gmask);
+                            gmask &= gmask - 1;
+                            const f32x4 v = srow[(cg ^ t) & (NG - 1)];
+                            // the four keys share a 32-column segment: columns seg0 .. seg0+3 of the tile
+                            const int seg0 = (wg * C::WNS + (cg >> 3)) * TN * 32 + bj * 32 + ((cg & 7) << 2);
+                            const int lim = p.n - n0 - seg0;   // real cache entries iff e < lim
+                            uint64_t bits = 0;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) bits |= (uint64_t)((v[e] <= tau) && (e < lim)) << e;
+                            bits <<= (cg & 15) * 4;
+                            if (cg < 16)
+                                kmask[0] |= bits;
+                            else
+                                kmask[1] |= bits;
+                        }
+                        // Third pass: one insertion attempt per surviving key, against the threshold as it tightens.
+#pragma unroll
+                        for (int m = 0; m < (NG + 15) / 16; ++m) {
+                            uint64_t mk = kmask[m];
+                            while (mk) {
+                                const int sc = m * 64 + __builtin_ctzll(mk);
+                                mk &= mk - 1;
+                                const float key = slab[t * C::SLABW + ((((sc >> 2) ^ t) & (NG - 1)) << 2) + (sc & 3)];
+                                const int tilecol = (wg * C::WNS + sc / 32) * TN * 32 + bj * 32 + (sc & 31);
+                                const uint64_t ent = ((uint64_t)ordered_bits(key) << 32) | (uint32_t)(n0 + tilecol);
+                                if (ent < curmax) {
+                                    top[maxpos * BM + t] = ent;
+                                    curmax = 0;
+#pragma unroll
+                                    for (int i = 0; i < C::RMAX; ++i) {
+                                        if (i < r) {
+                                            const uint64_t u = top[i * BM + t];
+                                            if (u >= curmax) { curmax = u; maxpos = i; }
+                                        }
+                                    }
+                                    tau = (curmax == kSentinel) ? __builtin_inff() : from_ordered_bits((uint32_t)(curmax >> 32));
+                                }
+                            }
+                        }
+                    }
+                    __syncthreads();
                 }
-                __syncthreads();
             }
         }
-    }
 
-    if (!C::KEYS && tid < BM) {
-        uint64_t *dst = p.part + (((size_t)mt * BM + tid) * p.alloc_splits + sp) * r;
+        if (!C::KEYS && tid < BM) {
+            uint64_t *dst = p.part + (((size_t)mt * BM + tid) * p.alloc_splits + slot) * r;
 #pragma unroll
-        for (int i = 0; i < C::RMAX; ++i)
-            if (i < r) dst[i] = top[i * BM + tid];
-    }
+            for (int i = 0; i < C::RMAX; ++i)
+                if (i < r) {
+                    dst[i] = top[i * BM + tid];
+                    if (clear_next_slot) dst[r + i] = kSentinel;
+                }
+        }
+    }   // parts
 }
 
 // Stream-K second pass (keys-out variant): per cache tile, add up the accumulators the
@@ -517,6 +568,37 @@ DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out, int6
         if (s > pl.alloc_splits) pl.alloc_splits = s;
         if (live * s > pl.grid_units) pl.grid_units = live * s;
     }
+    // Balanced decomposition: with s equal splits per query tile the slowest workgroup has
+    // ceil(n_tiles / s) tiles and m_tiles * s of the CUs work; cutting the flattened space evenly
+    // over all CUs brings that down to about m_tiles * n_tiles / CUs + 1.
+    pl.bal_f = pl.bal_nfull = pl.bal_wgs = pl.bal_lists = 0;
+    if (!keys_out && pl.m_tiles <= num_cus && (int64_t)pl.m_tiles * pl.n_tiles >= 4 * (int64_t)num_cus) {
+        const int f = num_cus / pl.m_tiles;
+        const int lw = num_cus - f * pl.m_tiles;
+        if (lw > 0 && f + 2 <= pl.max_splits) {
+            // tiles [0, nfull) go to the f workgroups of each query tile, the rest to the lw others:
+            // the nfull near the even share that makes the slowest workgroup fastest (ties: larger)
+            const int share = (int)((int64_t)f * pl.m_tiles * pl.n_tiles / num_cus);
+            int nfull = 0, new_max = pl.n_tiles + 1;
+            for (int cand = std::max(1, share - f); cand <= std::min(pl.n_tiles - 1, share + f); ++cand) {
+                const int64_t rest = (int64_t)pl.m_tiles * (pl.n_tiles - cand);
+                const int mx = (int)std::max<int64_t>((cand + f - 1) / f, (rest + lw - 1) / lw);
+                if (mx <= new_max) {
+                    new_max = mx;
+                    nfull = cand;
+                }
+            }
+            const int lo = pl.n_tiles - nfull;
+            const int64_t total_lo = (int64_t)pl.m_tiles * lo;
+            const int old_max = (pl.n_tiles + pl.n_splits - 1) / pl.n_splits;
+            if (nfull > 0 && lo > 0 && lo <= total_lo / lw && new_max < old_max) {
+                pl.bal_f = f;
+                pl.bal_nfull = nfull;
+                pl.bal_wgs = num_cus;
+                pl.bal_lists = f + 2;
+            }
+        }
+    }
     // Stream-K for the keys-out variant when whole tiles fill the CUs badly (196 tiles on 256 CUs
     // leave a quarter of the chip idle) and a tile is long enough to be worth cutting.
     pl.sk_wgs = pl.sk_len = pl.sk_slots = 0;
@@ -554,10 +636,13 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
     k.n_tiles = plan.n_tiles;
     k.n_splits = plan.n_splits;
     k.r = plan.r;
-    k.alloc_splits = a.count ? plan.alloc_splits : plan.n_splits;
+    k.alloc_splits = a.lists;
     k.max_splits = plan.max_splits;
     k.num_cus = plan.num_cus;
     const int grid = a.count ? plan.grid_units : plan.m_tiles * plan.n_splits;
+    if constexpr (!C::KEYS) {
+        if (!a.part || a.lists < (a.count ? plan.alloc_splits : plan.n_splits)) return hipErrorInvalidValue;
+    }
     k.keys = a.keys;
     k.bmin = a.bmin;
     k.n_pad = (int64_t)plan.n_tiles * kTileN;
@@ -571,6 +656,15 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL((keys_fixup_kernel<C>), dim3(plan.n_tiles), dim3(C::THREADS), 0, s, k);
+            return hipGetLastError();
+        }
+    }
+    if constexpr (!C::KEYS) {
+        if (a.balanced) {
+            if (plan.bal_f <= 0 || a.count || a.lists < plan.bal_lists) return hipErrorInvalidValue;
+            k.bal_f = plan.bal_f;
+            k.bal_nfull = plan.bal_nfull;
+            hipLaunchKernelGGL((dist_topr_kernel<C>), dim3(plan.bal_wgs), dim3(C::THREADS), 0, s, k);
             return hipGetLastError();
         }
     }

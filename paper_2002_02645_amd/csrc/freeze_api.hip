@@ -64,9 +64,17 @@ struct LookupShape {
     int r;
     bool skinny;   // small-batch bandwidth-bound kernel instead of the tiled matrix-core kernel
     bool keys;     // tiled kernel writes every key; selection by the threshold / filter kernels
+    bool cascade;  // sized for a look-up whose live count may sit on the device
     DistPlan plan;
     size_t ws_bytes;
 };
+
+// Candidate lists per query the distance pass writes (and their stride), by decomposition.
+int lists_per_query(const DistPlan &pl, bool device_count)
+{
+    if (device_count) return pl.alloc_splits;
+    return pl.bal_f > 0 ? pl.bal_lists : pl.n_splits;
+}
 
 bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, int rescore_r, bool cascade,
                   LookupShape *out)
@@ -77,6 +85,7 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     if (r < k) r = k;
     if ((int64_t)r > L.n) r = (int)L.n;
     out->r = r;
+    out->cascade = cascade;
     out->skinny = !cascade && skinny_supported(b, L.n_pad, L.d_pad, r, ctx->num_cus);
     out->keys = false;
     if (out->skinny) {
@@ -101,7 +110,7 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
             out->ws_bytes += select_workspace_bytes(out->plan.b_pad, L.n_pad, r, kAlign) +
                              align_up(dist_partial_bytes(out->plan));
         else
-            out->ws_bytes += align_up((size_t)out->plan.b_pad * (cascade ? out->plan.alloc_splits : out->plan.n_splits) * r * 8);
+            out->ws_bytes += align_up((size_t)out->plan.b_pad * lists_per_query(out->plan, cascade) * r * 8);
     }
     return true;
 }
@@ -229,12 +238,16 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
             fa.part_stride = 32 * sh.r;
             fa.n_splits = 1;
         } else {
-            const int alloc = count ? sh.plan.alloc_splits : sh.plan.n_splits;
+            // the workspace was sized by sh.cascade; the balanced decomposition only goes with it off
+            const int alloc = lists_per_query(sh.plan, sh.cascade);
+            const bool balanced = !sh.cascade && sh.plan.bal_f > 0;
             uint64_t *part = ws.take<uint64_t>((size_t)sh.plan.b_pad * alloc * sh.r);
             da.part = part;
+            da.balanced = balanced;
+            da.lists = alloc;
             if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
             fa.part = part;
-            fa.n_splits = sh.plan.n_splits;
+            fa.n_splits = balanced ? alloc : sh.plan.n_splits;
             fa.alloc_splits = alloc;
             fa.bm = sh.plan.bm;
             fa.n_tiles = sh.plan.n_tiles;

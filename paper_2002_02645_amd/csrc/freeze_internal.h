@@ -99,6 +99,11 @@ struct DistPlan {
     // and leave their accumulators in up to sk_slots slots; a second kernel adds them up per
     // tile and emits the keys.  sk_wgs == 0: off.
     int sk_wgs, sk_len, sk_slots;
+    // Balanced decomposition (fused variants; only when the live count is known on the host):
+    // bal_f workgroups per query tile cut cache tiles [0, bal_nfull) evenly and bal_wgs - m_tiles *
+    // bal_f more cut the flattened remainder of all query tiles, so every CU gets the same number of
+    // tiles (+-1); a query then has bal_lists candidate lists.  bal_f == 0: off.
+    int bal_f, bal_nfull, bal_wgs, bal_lists;
 };
 
 // d_pad decides stream-K for the keys-out variant (pass 0 to leave it off).
@@ -113,6 +118,8 @@ struct DistArgs {
     float *keys;            // [b_pad, n_pad] every key (keys-out variant)
     uint64_t *bmin;         // [b_pad, n_pad / 32] block minima (keys-out variant)
     float *partial;         // dist_partial_bytes(plan) bytes of scratch (keys-out variant under stream-K)
+    bool balanced;          // use the plan's balanced decomposition (needs lists >= plan.bal_lists)
+    int lists;              // candidate lists per query `part` has room for (their stride); fused variants
     const int32_t *count;   // device: number of live queries, or null (= b)
     int b;
     int n;
