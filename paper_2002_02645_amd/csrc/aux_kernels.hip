@@ -8,14 +8,6 @@ namespace fz {
 
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-// fp32 -> bf16, round to nearest even (inputs are finite by contract; NaN stays NaN)
-__device__ __forceinline__ uint16_t bf16_rne(float x)
-{
-    uint32_t u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // Sum over the 256 threads of a block in a fixed order; result valid in every thread.
@@ -711,7 +703,7 @@ __global__ __launch_bounds__(256) void skinny_rescore_kernel(SkinnyRescoreArgs r
     else if (a.c_f32)
         rescore_short<4, true>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);
     else
-        rescore_short<8, false>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);
+        rescore_short<16, false>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);   // every row of the pair in one round of loads
     __syncthreads();
     if (tid < 64) {
         uint64_t x = kSentinel;

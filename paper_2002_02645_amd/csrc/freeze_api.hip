@@ -181,7 +181,9 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     StageMarks marks(ctx, s);
 
     marks.mark(0);
-    if (launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf, s) != hipSuccess)
+    // (the small-batch streaming kernel converts its few queries itself)
+    if (!sh.skinny &&
+        launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf, s) != hipSuccess)
         return FREEZE_EHIP;
 
     FinishArgs fa{};
@@ -192,7 +194,8 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     uint64_t *skinny_cand = nullptr;
     if (sh.skinny) {
         SkinnyLaunch sl{};
-        sl.q_bf = q_bf;
+        sl.queries = queries;
+        sl.d = L.d;
         sl.c_bf = L.c_bf;
         sl.norm = L.norm;
         sl.bmin = ws.take<uint64_t>((size_t)kSkinnyRows * (L.n_pad / 32));

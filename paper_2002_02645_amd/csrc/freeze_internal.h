@@ -30,6 +30,14 @@ __host__ __device__ inline int64_t tiled_chunk_offset(int row_in_tile, int64_t j
     const int c = (int)(j & 3);
     return (kb * tile_rows + row_in_tile) * 4 + (c ^ tiled_chunk_swizzle(row_in_tile));
 }
+// fp32 -> bf16, round to nearest even (inputs are finite by contract; NaN stays NaN)
+__device__ __forceinline__ uint16_t bf16_rne(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
 constexpr int kMaxRescore = 64;  // largest re-scoring width R
 constexpr int kMaxK = 64;
 constexpr int kMaxMergeEntries = 8192;  // n_splits * R gathered per query in the finishing kernel
@@ -138,7 +146,8 @@ hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t
 // Small-batch (bandwidth-bound) path: streaming kernel + threshold + filter; the result is a
 // candidate list per query for the finishing kernel.
 struct SkinnyLaunch {
-    const uint16_t *q_bf;   // 16 x d_pad prepared queries (rows >= b zero), tiled with 16-row tiles
+    const float *queries;   // [b, d] fp32: converted to bf16 by every workgroup as it starts
+    int64_t d;
     const uint16_t *c_bf;
     const float *norm;
     uint64_t *bmin;         // [b, n_pad / 32] out: smallest (ordered key, index) of every block of 32 entries
