@@ -2,7 +2,9 @@
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
 benchmark's cpu_baseline leg, never by the library's product path.  It takes
-and returns numpy arrays; all arithmetic is in the C file.
+and returns numpy arrays; the k-NN look-up arithmetic is in the C file, and the
+heuristics built on it (confidence thresholds, the k-means cache) are plain
+numpy / Python loops below.
 """
 from __future__ import annotations
 
@@ -214,3 +216,78 @@ def compute_thresholds(val_queries: Sequence[np.ndarray], entries: Sequence[np.n
             if res["label"][i] != y[i]:
                 thr[l] = max(thr[l], res["conf"][i])
     return thr
+
+
+# ---------------------------------------------------------------------------------------------
+# k-means cache (Sec. 4, "k-means": intermediate points of a layer are clustered and each
+# cluster is represented by its centre; a cache item is the centre, the majority label of the
+# cluster and the fraction of the cluster that carries it; a look-up returns the majority label
+# of the closest centre, with confidence = that fraction / the distance to the centre; thresholds
+# work as for k-NN).  Readings where the paper is silent: Lloyd's iterations from given initial
+# centres for a fixed number of rounds; a point goes to the nearest centre by Euclidean distance
+# (equal distances -> the lower centre index); a centre becomes the mean of its points, summed in
+# index order in double and rounded once to fp32; a cluster that loses all its points keeps its
+# centre (majority label 0, fraction 0, so it never hits); equal label counts -> the smaller
+# label; the distance in the confidence is the square root of the squared distance, a zero
+# distance gives +inf; the confidence is rounded once to fp32 and compared with `>` in fp32.
+# ---------------------------------------------------------------------------------------------
+def kmeans_assign(points: np.ndarray, centers: np.ndarray, nthreads: int = 0):
+    """Index of the nearest centre of every point and the squared distance to it (double)."""
+    idx, dist, _ = knn(points, np.ascontiguousarray(centers, dtype=np.float32), 1, nthreads)
+    return idx[:, 0].copy(), dist[:, 0].copy()
+
+
+def kmeans_build(points: np.ndarray, labels: np.ndarray, num_classes: int, init_centers: np.ndarray,
+                 iters: int, nthreads: int = 0):
+    """Returns dict(centers float32 [K,d], majority int32 [K], fraction float32 [K], sizes int64 [K],
+    assign int32 [n]) after `iters` rounds of (assign, update); labels and fractions come from a
+    final assignment to the final centres."""
+    pts = np.ascontiguousarray(points, dtype=np.float32)
+    lab = np.asarray(labels)
+    centers = np.array(init_centers, dtype=np.float32, copy=True)
+    K = centers.shape[0]
+
+    def update(assign):
+        new = centers.copy()
+        for c in range(K):
+            members = np.nonzero(assign == c)[0]          # ascending point index
+            if members.size:
+                acc = np.zeros(pts.shape[1], dtype=np.float64)
+                for i in members:
+                    acc += pts[i].astype(np.float64)
+                new[c] = (acc / float(members.size)).astype(np.float32)
+        return new
+
+    for _ in range(iters):
+        assign, _ = kmeans_assign(pts, centers, nthreads)
+        centers = update(assign)
+    assign, _ = kmeans_assign(pts, centers, nthreads)
+    majority = np.zeros(K, dtype=np.int32)
+    fraction = np.zeros(K, dtype=np.float32)
+    sizes = np.zeros(K, dtype=np.int64)
+    for c in range(K):
+        members = np.nonzero(assign == c)[0]
+        sizes[c] = members.size
+        if members.size:
+            counts = np.zeros(num_classes, dtype=np.int64)
+            for i in members:
+                counts[int(lab[i])] += 1
+            best = 0
+            for l in range(num_classes):
+                if counts[l] > counts[best]:
+                    best = l
+            majority[c] = best
+            fraction[c] = np.float32(float(counts[best]) / float(members.size))
+    return dict(centers=centers, majority=majority, fraction=fraction, sizes=sizes, assign=assign.astype(np.int32))
+
+
+def kmeans_lookup(queries: np.ndarray, centers: np.ndarray, majority: np.ndarray, fraction: np.ndarray,
+                  conf_threshold: float, nthreads: int = 0):
+    """Returns dict(idx [b] nearest centre, sqdist [b] double, label, conf float32, hit)."""
+    idx, dist = kmeans_assign(queries, centers, nthreads)
+    frac = np.asarray(fraction, dtype=np.float64)[idx]
+    with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
+        conf = np.where(dist > 0, frac / np.sqrt(dist), np.where(frac > 0, np.inf, 0.0)).astype(np.float32)
+    hit = (conf > np.float32(conf_threshold)).astype(np.uint8)
+    return dict(idx=idx.astype(np.int32), sqdist=dist, label=np.asarray(majority, dtype=np.int32)[idx], conf=conf,
+                hit=hit)

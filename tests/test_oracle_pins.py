@@ -393,3 +393,62 @@ def test_table1_arithmetic_gives_the_layer_sizes():
     assert mib == vals["knn_without_dimensionality_reduction_MB"]
     dims = {l.d for l in synth.WORKLOADS["c4_cascade"].layers} | {synth.WORKLOADS["c2_batched"].layers[0].d}
     assert {65536, 32768, 16384, 8192} <= dims
+
+
+# ---------------------------------------------------------------------------------------------
+# k-means cache (Sec. 4): the oracle's Lloyd iterations, majority labels / fractions and look-up
+# ---------------------------------------------------------------------------------------------
+def test_kmeans_hand_example():
+    # 1-D points 0, 1, 10, 11, 12 with labels a a b b a; initial centres 0 and 10
+    pts = np.array([[0.0], [1.0], [10.0], [11.0], [12.0]], dtype=np.float32)
+    lab = np.array([0, 0, 1, 1, 0], dtype=np.int32)
+    res = fo.kmeans_build(pts, lab, 2, np.array([[0.0], [10.0]], np.float32), iters=1)
+    assert res["centers"][:, 0].tolist() == [0.5, 11.0]
+    assert res["assign"].tolist() == [0, 0, 1, 1, 1]
+    assert res["majority"].tolist() == [0, 1] and res["sizes"].tolist() == [2, 3]
+    assert res["fraction"].tolist() == [1.0, np.float32(2.0 / 3.0)]
+    # look-up: query 2.5 is 2 away from centre 0.5 -> confidence 1 / 2; query 9 is 2 from 11 -> (2/3) / 2
+    out = fo.kmeans_lookup(np.array([[2.5], [9.0], [11.0]], np.float32), res["centers"], res["majority"],
+                           res["fraction"], 0.4)
+    assert out["idx"].tolist() == [0, 1, 1] and out["label"].tolist() == [0, 1, 1]
+    assert out["conf"][0] == np.float32(0.5) and out["conf"][1] == np.float32((2.0 / 3.0) / 2.0)
+    assert np.isposinf(out["conf"][2])            # a query on a centre: always a hit
+    assert out["hit"].tolist() == [1, 0, 1]
+    # equidistant centres: the lower index; equal label counts: the smaller label
+    res = fo.kmeans_build(np.array([[5.0], [5.0]], np.float32), np.array([3, 1], np.int32), 4,
+                          np.array([[0.0], [10.0]], np.float32), iters=0)
+    assert res["assign"].tolist() == [0, 0] and res["majority"].tolist() == [1, 0]
+    assert res["fraction"].tolist() == [0.5, 0.0] and res["sizes"].tolist() == [2, 0]   # an empty cluster never hits
+
+
+def test_kmeans_against_library_lloyd_and_invariants():
+    from sklearn.cluster import KMeans
+    rng = np.random.default_rng(3)
+    K, d = 6, 5
+    true = rng.normal(scale=6.0, size=(K, d))
+    pts = (true[rng.integers(0, K, size=400)] + rng.normal(size=(400, d))).astype(np.float32)
+    lab = rng.integers(0, 3, size=400).astype(np.int32)
+    init = pts[:K].copy()
+    prev_inertia = None
+    for iters in (1, 2, 5):
+        res = fo.kmeans_build(pts, lab, 3, init, iters)
+        km = KMeans(n_clusters=K, init=init.astype(np.float64), n_init=1, max_iter=iters, tol=0.0,
+                    algorithm="lloyd").fit(pts.astype(np.float64))
+        assert (res["sizes"] > 0).all()
+        assert np.allclose(res["centers"], km.cluster_centers_, rtol=1e-5, atol=1e-6), iters
+        # every point sits with its nearest centre, and the inertia never grows from round to round
+        d2 = ((pts[:, None, :].astype(np.float64) - res["centers"][None].astype(np.float64)) ** 2).sum(-1)
+        assert np.array_equal(res["assign"], d2.argmin(axis=1))
+        inertia = d2.min(axis=1).sum()
+        assert prev_inertia is None or inertia <= prev_inertia * (1 + 1e-12)
+        prev_inertia = inertia
+        # majority label and fraction by an independent count
+        for c in range(K):
+            cnt = np.bincount(lab[res["assign"] == c], minlength=3)
+            assert res["majority"][c] == cnt.argmax() and res["fraction"][c] == np.float32(cnt.max() / cnt.sum())
+    # relabelling the points by a permutation gives the same clustering
+    perm = rng.permutation(400)
+    res_p = fo.kmeans_build(pts[perm], lab[perm], 3, init, 2)
+    res_0 = fo.kmeans_build(pts, lab, 3, init, 2)
+    assert np.allclose(res_p["centers"], res_0["centers"], rtol=1e-6)
+    assert np.array_equal(res_p["assign"], res_0["assign"][perm])
