@@ -181,6 +181,35 @@ int freeze_compute_thresholds(freeze_ctx *ctx, int num_layers, const int *layers
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * k-means cache (Sec. 4, "k-means"): the points of a layer are clustered and a cache item is
+ * a cluster centre with the majority label of its cluster and the share of the cluster that
+ * carries it.  freeze_kmeans_build runs `iters` rounds of Lloyd's iterations from the given
+ * centres (assignment = the batched look-up of every point against the centres with k = 1,
+ * equal distances -> the lower centre; update = mean of the assigned points, summed in point
+ * order in fp64 and rounded once to fp32; a cluster that loses all its points keeps its
+ * centre, gets label 0 and share 0), then assigns once more for the labels and shares, and
+ * leaves `layer` holding that cache.  No host synchronisation.
+ *   points        [n, d] fp32 row-major, 16-byte aligned; labels [n] int32 in [0, num_classes),
+ *                 num_classes <= 8192.
+ *   init_centers  [num_centers, d] fp32; 1 <= num_centers <= n.
+ *   storage       >= freeze_kmeans_storage_bytes() bytes, 256-byte aligned; must outlive the
+ *                 look-ups on this layer.   workspace  >= freeze_kmeans_workspace_bytes().
+ * On such a layer freeze_lookup (k = 1) returns the nearest centre and its majority label, and
+ * the confidence entry points (freeze_lookup_confidence, freeze_lookup_cascade_confidence,
+ * freeze_compute_thresholds; k must be 1) use the paper's k-means confidence: the majority
+ * share over the distance to the centre (zero distance: +inf; an empty cluster: 0).
+ * freeze_kmeans_read copies the centres [num_centers, d], majority labels and shares out.
+ */
+size_t freeze_kmeans_storage_bytes(int64_t num_centers, int64_t d);
+size_t freeze_kmeans_workspace_bytes(const freeze_ctx *ctx, int64_t n, int64_t d, int64_t num_centers);
+int freeze_kmeans_build(freeze_ctx *ctx, int layer, const float *points, int64_t n, int64_t d,
+                        const int32_t *labels, int32_t num_classes, const float *init_centers,
+                        int64_t num_centers, int iters, void *storage, size_t storage_bytes,
+                        void *workspace, size_t workspace_bytes, void *stream);
+int freeze_kmeans_read(freeze_ctx *ctx, int layer, float *out_centers, int32_t *out_majority,
+                       float *out_fraction, void *stream);
+
+/*
  * Batch reconstruction on its own (Sec. 5): writes to sel_out the entries
  * sel_in[j] (or j itself when sel_in is NULL) with hit[j] == 0, j < count, in
  * order, and their number to *out_count.

@@ -60,6 +60,14 @@ def lib():
     L.freeze_lookup_confidence.argtypes = [p, i32, p, i64, i32, ctypes.c_float, i32, p, p, p, p, p, p, p, sz, p]
     L.freeze_lookup_cascade_confidence.restype = i32
     L.freeze_lookup_cascade_confidence.argtypes = [p, i32, p, p, i64, i32, p, i32, p, p, p, p, sz, p]
+    L.freeze_kmeans_storage_bytes.restype = sz
+    L.freeze_kmeans_storage_bytes.argtypes = [i64, i64]
+    L.freeze_kmeans_workspace_bytes.restype = sz
+    L.freeze_kmeans_workspace_bytes.argtypes = [p, i64, i64, i64]
+    L.freeze_kmeans_build.restype = i32
+    L.freeze_kmeans_build.argtypes = [p, i32, p, i64, i64, p, ctypes.c_int32, p, i64, i32, p, sz, p, sz, p]
+    L.freeze_kmeans_read.restype = i32
+    L.freeze_kmeans_read.argtypes = [p, i32, p, p, p, p]
     L.freeze_compute_thresholds.restype = i32
     L.freeze_compute_thresholds.argtypes = [p, i32, p, p, i64, i32, i32, p, p, p, sz, p]
     L.freeze_profile_enable.restype = i32
@@ -209,6 +217,35 @@ def freeze_compute_thresholds(ctx, layers: Sequence[int], queries_per_layer: Seq
                                            _ptr(out_thresholds), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream(stream)),
            "freeze_compute_thresholds")
+
+
+def freeze_kmeans_storage_bytes(num_centers: int, d: int) -> int:
+    return int(lib().freeze_kmeans_storage_bytes(num_centers, d))
+
+
+def freeze_kmeans_workspace_bytes(ctx, n: int, d: int, num_centers: int) -> int:
+    return int(lib().freeze_kmeans_workspace_bytes(ctx, n, d, num_centers))
+
+
+def freeze_kmeans_build(ctx, layer: int, points: torch.Tensor, labels: torch.Tensor, num_classes: int,
+                        init_centers: torch.Tensor, iters: int, storage: torch.Tensor, workspace: torch.Tensor,
+                        stream=None) -> None:
+    assert points.is_cuda and points.dtype == torch.float32 and points.is_contiguous() and points.dim() == 2
+    assert init_centers.is_cuda and init_centers.dtype == torch.float32 and init_centers.is_contiguous()
+    assert init_centers.shape[1] == points.shape[1]
+    assert labels.is_cuda and labels.dtype == torch.int32 and labels.numel() == points.shape[0]
+    n, d = points.shape
+    _check(lib().freeze_kmeans_build(ctx, layer, _ptr(points), n, d, _ptr(labels), num_classes, _ptr(init_centers),
+                                     init_centers.shape[0], iters, _ptr(storage),
+                                     storage.numel() * storage.element_size(), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)),
+           "freeze_kmeans_build")
+
+
+def freeze_kmeans_read(ctx, layer: int, out_centers: torch.Tensor, out_majority: torch.Tensor,
+                       out_fraction: torch.Tensor, stream=None) -> None:
+    _check(lib().freeze_kmeans_read(ctx, layer, _ptr(out_centers), _ptr(out_majority), _ptr(out_fraction),
+                                    _stream(stream)), "freeze_kmeans_read")
 
 
 def freeze_compact_misses(hit: torch.Tensor, sel_in: Optional[torch.Tensor], sel_out: torch.Tensor,
@@ -361,3 +398,25 @@ class FreezeCache:
         ws = self._workspace(nbytes)
         freeze_compute_thresholds(self.ctx, layers, queries_per_layer, k, rescore_r, model_labels, thr, ws)
         return thr
+
+    def build_kmeans_layer(self, layer: int, points: torch.Tensor, labels: torch.Tensor, num_classes: int,
+                           init_centers: torch.Tensor, iters: int) -> dict:
+        """k-means cache of `points` (Sec. 4); returns the centres, majority labels and shares."""
+        n, d = points.shape
+        kc = init_centers.shape[0]
+        nbytes = freeze_kmeans_storage_bytes(kc, d)
+        if nbytes == 0:
+            raise FreezeError(FREEZE_EINVAL, "freeze_kmeans_storage_bytes")
+        st = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        wbytes = freeze_kmeans_workspace_bytes(self.ctx, n, d, kc)
+        if wbytes == 0:
+            raise FreezeError(FREEZE_EINVAL, "freeze_kmeans_workspace_bytes")
+        ws = self._workspace(wbytes)
+        freeze_kmeans_build(self.ctx, layer, points, labels, num_classes, init_centers, iters, st, ws)
+        self.storage[layer] = st
+        self.meta[layer] = (kc, d, num_classes)
+        out = dict(centers=torch.empty((kc, d), dtype=torch.float32, device=self.device),
+                   majority=torch.empty(kc, dtype=torch.int32, device=self.device),
+                   fraction=torch.empty(kc, dtype=torch.float32, device=self.device))
+        freeze_kmeans_read(self.ctx, layer, out["centers"], out["majority"], out["fraction"])
+        return out

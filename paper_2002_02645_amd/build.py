@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIBDIR = os.path.join(PKG, "_lib")
 LIB = os.path.join(LIBDIR, "libfreeze_hip.so")
-SOURCES = ["dist_topr.hip", "dist_skinny.hip", "aux_kernels.hip", "freeze_api.hip", "calibrate.hip"]
+SOURCES = ["dist_topr.hip", "dist_skinny.hip", "aux_kernels.hip", "kmeans.hip", "freeze_api.hip", "calibrate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

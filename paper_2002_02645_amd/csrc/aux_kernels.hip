@@ -392,15 +392,28 @@ __device__ __forceinline__ void rescore_block(const FinishArgs &a, const float *
 // equal counts, hit iff m >= vote_threshold.  Distance-weighted rule of Sec. 3: C_i = (m_i / k) *
 // sum_j 1 / d_j in fp64 in neighbour order, winner = largest C_i (smaller id on equality), the
 // confidence rounded once to fp32, hit iff confidence > threshold (Pseudocode 1).
+// k-means cache (Sec. 4; k = 1): the label is the nearest centre's majority label and the
+// confidence its majority share over the distance (zero distance: +inf, or 0 for an empty cluster).
 __device__ __forceinline__ void decide_and_write(const FinishArgs &a, int q, int tid, const int32_t *lab_s,
-                                                 const float *dsel_s, int32_t *cnt_s, double *conf_s)
+                                                 const float *dsel_s, int32_t *cnt_s, double *conf_s, int32_t nearest)
 {
+    if (a.weighted == 2) {
+        if (tid == 0) {
+            const double fr = (double)a.fraction[nearest], dd = (double)dsel_s[0];
+            const float conf = dd > 0.0 ? (float)(fr / __builtin_sqrt(dd)) : (fr > 0.0 ? __builtin_inff() : 0.f);
+            a.out_labels[q] = lab_s[0];
+            a.out_votes[q] = 1;
+            a.out_conf[q] = conf;
+            a.out_hit[q] = (uint8_t)(conf > a.conf_threshold);
+        }
+        return;
+    }
     if (tid < a.k) {
         const int32_t lm = lab_s[tid];
         int c = 0;
         for (int j = 0; j < a.k; ++j) c += (lab_s[j] == lm);
         cnt_s[tid] = c;
-        if (a.weighted) {
+        if (a.weighted == 1) {
             double inv = 0.0;
             for (int j = 0; j < a.k; ++j)
                 if (lab_s[j] == lm) inv += 1.0 / __builtin_sqrt((double)dsel_s[j]);
@@ -408,7 +421,7 @@ __device__ __forceinline__ void decide_and_write(const FinishArgs &a, int q, int
         }
     }
     __syncthreads();
-    if (tid == 0 && a.weighted) {
+    if (tid == 0 && a.weighted == 1) {
         double best_conf = -1.0;
         int best_c = 0;
         int32_t best_l = 0;
@@ -460,6 +473,7 @@ __global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
     __shared__ int32_t cnt_s[kMaxK];
     __shared__ float dsel_s[kMaxK];
     __shared__ double conf_s[kMaxK];
+    __shared__ int32_t nearest_s;
 
     const int nq = a.count ? *a.count : a.b;
     const int q = blockIdx.x;
@@ -534,12 +548,13 @@ __global__ __launch_bounds__(NT) void finish_kernel(FinishKernelArgs fa)
             a.out_nbr_dist[(int64_t)q * a.k + rank] = dm;
             lab_s[rank] = a.labels[im];
             dsel_s[rank] = dm;
+            if (rank == 0) nearest_s = im;
         }
     }
     __syncthreads();
 
     // 4. vote and hit decision
-    decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s);
+    decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s, nearest_s);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -727,6 +742,7 @@ __global__ __launch_bounds__(kThrThreads) void skinny_final_kernel(SkinnyFinalAr
     __shared__ int32_t cnt_s[kMaxK];
     __shared__ float dsel_s[kMaxK];
     __shared__ double conf_s[kMaxK];
+    __shared__ int32_t nearest_s;
     const int q = blockIdx.x, tid = threadIdx.x;
     const int m = fa.count;
     for (int c = tid; c < m; c += kThrThreads) list[c] = fa.cand[(size_t)q * m + c];
@@ -751,9 +767,10 @@ __global__ __launch_bounds__(kThrThreads) void skinny_final_kernel(SkinnyFinalAr
         a.out_nbr_dist[(int64_t)q * a.k + tid] = dm;
         lab_s[tid] = a.labels[im];
         dsel_s[tid] = dm;
+        if (tid == 0) nearest_s = im;
     }
     __syncthreads();
-    decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s);
+    decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s, nearest_s);
 }
 
 size_t skinny_finish_workspace_bytes(int r, size_t align)

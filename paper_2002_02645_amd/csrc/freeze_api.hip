@@ -274,6 +274,7 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     fa.k = k;
     fa.vote_threshold = rule.vote_threshold;
     fa.weighted = rule.weighted;
+    fa.fraction = L.fraction;
     fa.conf_threshold = rule.conf_threshold;
     fa.out_conf = rule.out_conf;
     fa.out_labels = out_labels;
@@ -323,6 +324,18 @@ bool cascade_layout(const freeze_ctx *ctx, int num_layers, const int *layers, in
                  2 * align_up(4);
     *err = FREEZE_OK;
     return true;
+}
+
+// Which confidence applies on a layer: the distance-weighted heuristic of Sec. 3 on a k-NN cache,
+// majority share over distance on a k-means cache (Sec. 4), which is defined for k = 1 only.
+int confidence_rule_for(const freeze_ctx *ctx, int layer, int k, int *kind)
+{
+    int err;
+    const LayerCache *L = get_layer(ctx, layer, &err);
+    if (!L) return err;
+    *kind = L->fraction ? 2 : 1;
+    if (L->fraction && k != 1) return FREEZE_EINVAL;
+    return FREEZE_OK;
 }
 
 int lookup_checked(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k, const HitRule &rule,
@@ -476,6 +489,7 @@ int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entr
     L.labels = lab;
     L.c_f32 = c_f32;
     L.c_rows = c_rows;
+    L.fraction = nullptr;
     L.built = true;
     return FREEZE_OK;
 }
@@ -506,7 +520,9 @@ int freeze_lookup_confidence(freeze_ctx *ctx, int layer, const float *queries, i
 {
     if (!(conf_threshold >= 0.f)) return FREEZE_EINVAL;   // also rejects NaN
     if (b > 0 && !out_conf) return FREEZE_EINVAL;
-    const HitRule rule{1, 1, conf_threshold, out_conf};
+    int kind = 1;
+    if (int rc = confidence_rule_for(ctx, layer, k, &kind)) return rc;
+    const HitRule rule{kind, 1, conf_threshold, out_conf};
     return lookup_checked(ctx, layer, queries, b, k, rule, rescore_r, out_labels, out_hit, out_votes, out_nbr_idx,
                           out_nbr_dist, workspace, workspace_bytes, stream);
 }
@@ -543,8 +559,10 @@ int freeze_lookup_cascade_confidence(freeze_ctx *ctx, int num_layers, const int 
     if (!conf_thresholds || num_layers < 1 || num_layers > 1024) return FREEZE_EINVAL;
     std::vector<HitRule> rules((size_t)num_layers);
     for (int l = 0; l < num_layers; ++l) {
-        if (!(conf_thresholds[l] >= 0.f)) return FREEZE_EINVAL;
-        rules[(size_t)l] = HitRule{1, 1, conf_thresholds[l], nullptr};
+        if (!(conf_thresholds[l] >= 0.f) || !layers) return FREEZE_EINVAL;
+        int kind = 1;
+        if (int rc = confidence_rule_for(ctx, layers[l], k, &kind)) return rc;
+        rules[(size_t)l] = HitRule{kind, 1, conf_thresholds[l], nullptr};
     }
     return cascade_checked(ctx, num_layers, layers, queries_per_layer, b, k, rules, rescore_r, out_labels,
                            out_exit_layer, out_hits_per_layer, workspace, workspace_bytes, stream);
@@ -584,13 +602,127 @@ int freeze_compute_thresholds(freeze_ctx *ctx, int num_layers, const int *layers
         const LayerCache &L = ctx->layers[layers[l]];
         LookupShape sh;
         lookup_shape(ctx, L, b, k, rescore_r, true, &sh);
-        const HitRule rule{1, 1, 0.f, t_conf};
+        int kind = 1;
+        if (int rck = confidence_rule_for(ctx, layers[l], k, &kind)) return rck;
+        const HitRule rule{kind, 1, 0.f, t_conf};
         int rc = enqueue_lookup(ctx, L, sh, queries_per_layer[l], nullptr, nullptr, b, k, rule, t_labels, t_hit, t_votes,
                                 t_idx, t_dist, lookup_ws, s);
         if (rc != FREEZE_OK) return rc;
         if (launch_threshold_max(t_labels, t_conf, model_labels, b, out_thresholds + l, s) != hipSuccess)
             return FREEZE_EHIP;
     }
+    return FREEZE_OK;
+}
+
+size_t freeze_kmeans_storage_bytes(int64_t num_centers, int64_t d)
+{
+    CacheLayout cl;
+    if (!cache_layout(num_centers, d, FREEZE_F32, &cl)) return 0;
+    return cl.bytes + align_up((size_t)num_centers * 4);
+}
+
+namespace {
+struct KmeansLayout {
+    size_t lookup_ws;
+    size_t bytes;
+};
+// workspace: two centre buffers, dummy labels, the look-up's outputs for n points and its workspace
+bool kmeans_layout(const freeze_ctx *ctx, int64_t n, int64_t d, int64_t kc, KmeansLayout *out)
+{
+    CacheLayout cl;
+    if (!ctx || n < 1 || n > (int64_t)1 << 30 || kc < 1 || kc > n || !cache_layout(kc, d, FREEZE_F32, &cl)) return false;
+    LayerCache tmp;   // shape of the centres as a cache
+    tmp.n = kc;
+    tmp.d = d;
+    tmp.n_pad = cl.n_pad;
+    tmp.d_pad = cl.d_pad;
+    LookupShape sh;
+    if (!lookup_shape(ctx, tmp, n, 1, 0, false, &sh)) return false;
+    out->lookup_ws = sh.ws_bytes;
+    out->bytes = sh.ws_bytes + 2 * align_up((size_t)kc * d * 4) + align_up((size_t)kc * 4) + 3 * align_up((size_t)n * 4) +
+                 align_up((size_t)n) + 2 * align_up((size_t)n * 4);
+    return true;
+}
+}  // namespace
+
+size_t freeze_kmeans_workspace_bytes(const freeze_ctx *ctx, int64_t n, int64_t d, int64_t num_centers)
+{
+    KmeansLayout kl;
+    return kmeans_layout(ctx, n, d, num_centers, &kl) ? kl.bytes : 0;
+}
+
+int freeze_kmeans_build(freeze_ctx *ctx, int layer, const float *points, int64_t n, int64_t d, const int32_t *labels,
+                        int32_t num_classes, const float *init_centers, int64_t num_centers, int iters, void *storage,
+                        size_t storage_bytes, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || !points || !labels || !init_centers || !storage || !workspace || iters < 0 || iters > 1000 ||
+        num_classes < 1 || num_classes > 8192)
+        return FREEZE_EINVAL;
+    if (layer < 0 || layer >= (int)ctx->layers.size()) return FREEZE_ELAYER;
+    KmeansLayout kl;
+    if (!kmeans_layout(ctx, n, d, num_centers, &kl)) return FREEZE_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(points) % 16) != 0) return FREEZE_EINVAL;
+    const size_t st_bytes = freeze_kmeans_storage_bytes(num_centers, d);
+    if (storage_bytes < st_bytes || (reinterpret_cast<uintptr_t>(storage) % kAlign) != 0) return FREEZE_EWORKSPACE;
+    if (workspace_bytes < kl.bytes || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0) return FREEZE_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t kc = num_centers;
+
+    Carver ws(workspace);
+    unsigned char *lookup_ws = ws.take<unsigned char>(kl.lookup_ws);
+    float *cen[2] = {ws.take<float>((size_t)kc * d), ws.take<float>((size_t)kc * d)};
+    int32_t *zero_labels = ws.take<int32_t>((size_t)kc);
+    int32_t *t_labels = ws.take<int32_t>((size_t)n);
+    int32_t *t_votes = ws.take<int32_t>((size_t)n);
+    int32_t *assign = ws.take<int32_t>((size_t)n);
+    uint8_t *t_hit = ws.take<uint8_t>((size_t)n);
+    float *t_dist = ws.take<float>((size_t)n);
+    float *t_conf = ws.take<float>((size_t)n);
+    (void)t_conf;
+
+    CacheLayout cl;
+    cache_layout(kc, d, FREEZE_F32, &cl);
+    float *fraction = reinterpret_cast<float *>(static_cast<unsigned char *>(storage) + cl.bytes);
+
+    if (launch_copy_rows_f32(init_centers, d, cen[0], kc, d, s) != hipSuccess) return FREEZE_EHIP;
+    if (launch_fill_i32(zero_labels, 0, kc, s) != hipSuccess) return FREEZE_EHIP;
+    // rounds of (centres -> cache, every point looked up with k = 1, centres <- means); a last
+    // assignment to the final centres gives the majority labels and their shares
+    const HitRule rule{0, 1, 0.f, nullptr};
+    for (int it = 0; it <= iters; ++it) {
+        const float *cur = cen[it & 1];
+        int rc = freeze_cache_build(ctx, layer, cur, FREEZE_F32, kc, d, zero_labels, num_classes, storage, cl.bytes, stream);
+        if (rc != FREEZE_OK) return rc;
+        const LayerCache &L = ctx->layers[layer];
+        LookupShape sh;
+        if (!lookup_shape(ctx, L, n, 1, 0, false, &sh)) return FREEZE_EINVAL;
+        rc = enqueue_lookup(ctx, L, sh, points, nullptr, nullptr, n, 1, rule, t_labels, t_hit, t_votes, assign, t_dist,
+                            lookup_ws, s);
+        if (rc != FREEZE_OK) return rc;
+        if (it < iters &&
+            launch_kmeans_update(points, assign, n, d, kc, cur, cen[(it + 1) & 1], s) != hipSuccess)
+            return FREEZE_EHIP;
+    }
+    LayerCache &L = ctx->layers[layer];
+    // the cache's label array becomes the majority labels, the shares go behind the cache
+    if (launch_kmeans_majority(assign, labels, n, num_classes, kc, const_cast<int32_t *>(L.labels), fraction, nullptr, s) !=
+        hipSuccess)
+        return FREEZE_EHIP;
+    L.fraction = fraction;
+    return FREEZE_OK;
+}
+
+int freeze_kmeans_read(freeze_ctx *ctx, int layer, float *out_centers, int32_t *out_majority, float *out_fraction,
+                       void *stream)
+{
+    int err;
+    const LayerCache *L = get_layer(ctx, layer, &err);
+    if (!L) return err;
+    if (!L->fraction || !L->c_f32 || !out_centers || !out_majority || !out_fraction) return FREEZE_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (launch_copy_rows_f32(L->c_f32, L->d_pad, out_centers, L->n, L->d, s) != hipSuccess) return FREEZE_EHIP;
+    if (launch_copy_rows_f32(L->fraction, 1, out_fraction, L->n, 1, s) != hipSuccess) return FREEZE_EHIP;
+    if (launch_copy_i32(L->labels, out_majority, L->n, s) != hipSuccess) return FREEZE_EHIP;
     return FREEZE_OK;
 }
 

@@ -57,6 +57,8 @@ struct LayerCache {
     const int32_t *labels = nullptr;  // [n]
     const float *c_f32 = nullptr;     // [n, d_pad] fp32 rows when the cache was given in fp32, else null
     const uint16_t *c_rows = nullptr; // [n, d_pad] row-major bf16 rows when the cache was given in bf16, else null
+    // k-means cache: the entries are cluster centres, labels their majority labels, and
+    const float *fraction = nullptr;  // [n] the share of each cluster that carries its majority label (else null)
 };
 
 // Number of splits of the cache tiles for `live_mt` live query tiles.  Units (query tile, split)
@@ -184,7 +186,9 @@ struct FinishArgs {
     const float *c_f32;     // non-null: re-score against the fp32 rows (cache given in fp32)
     const int32_t *labels;
     int k, vote_threshold;
-    int weighted;           // 0: plurality count and vote_threshold; 1: distance-weighted confidence
+    int weighted;           // 0: plurality count and vote_threshold; 1: distance-weighted confidence;
+                            // 2: k-means cache (k = 1): confidence = fraction[nearest centre] / distance
+    const float *fraction;  // [n] (rule 2)
     float conf_threshold;   // weighted rule: hit iff confidence > conf_threshold
     float *out_conf;        // [b] (compact order), weighted rule only
     int32_t *out_labels;    // [b] (compact order)
@@ -210,6 +214,15 @@ hipError_t launch_cascade_init(int32_t *out_labels, int32_t *out_exit, int64_t b
 hipError_t launch_cascade_scatter(const int32_t *labels, const uint8_t *hit, const int32_t *sel,
                                   const int32_t *count, int64_t b, int layer_pos, int32_t *out_labels,
                                   int32_t *out_exit, hipStream_t s);
+
+// k-means cache build (the assignment step is the look-up itself)
+hipError_t launch_kmeans_update(const float *points, const int32_t *assign, int64_t n, int64_t d, int64_t k,
+                                const float *old_centers, float *new_centers, hipStream_t s);
+hipError_t launch_kmeans_majority(const int32_t *assign, const int32_t *labels, int64_t n, int num_classes, int64_t k,
+                                  int32_t *majority, float *fraction, int64_t *sizes, hipStream_t s);
+hipError_t launch_copy_rows_f32(const float *src, int64_t src_stride, float *dst, int64_t rows, int64_t d, hipStream_t s);
+hipError_t launch_fill_i32(int32_t *dst, int32_t v, int64_t n, hipStream_t s);
+hipError_t launch_copy_i32(const int32_t *src, int32_t *dst, int64_t n, hipStream_t s);
 
 hipError_t launch_threshold_init(float *thr, int n, hipStream_t s);
 hipError_t launch_threshold_max(const int32_t *pred, const float *conf, const int32_t *model_labels, int64_t b,
