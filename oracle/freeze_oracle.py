@@ -291,3 +291,34 @@ def kmeans_lookup(queries: np.ndarray, centers: np.ndarray, majority: np.ndarray
     hit = (conf > np.float32(conf_threshold)).astype(np.uint8)
     return dict(idx=idx.astype(np.int32), sqdist=dist, label=np.asarray(majority, dtype=np.int32)[idx], conf=conf,
                 hit=hit)
+
+
+# ---------------------------------------------------------------------------------------------
+# Dimensionality reduction in front of the look-up (Sec. 3: a one-layer network whose hidden
+# layer has 1,024 nodes projects the layer output before it is cached and looked up).  The paper
+# gives no activation and no precision.  Reading: y = W x + b, optionally through ReLU; the
+# operation is defined on bf16 operands (x and W rounded to nearest even; a W given in bf16 is
+# taken as it is), exact products, wide accumulation: here fp64, rounded once to fp32.
+# ---------------------------------------------------------------------------------------------
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> the nearest bf16 value (ties to even), returned widened to fp32."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return (r.astype(np.uint32) << 16).view(np.float32).reshape(np.shape(x))
+
+
+def project(x: np.ndarray, weights: np.ndarray, bias: np.ndarray, relu: bool) -> np.ndarray:
+    """x [b, d] fp32, weights [m, d] fp32 or bf16 bit patterns (uint16), bias [m] -> [b, m] float32."""
+    xr = round_to_bf16(x).astype(np.float64)
+    if weights.dtype == np.uint16:
+        wr = (weights.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    else:
+        wr = round_to_bf16(weights).astype(np.float64)
+    b, m = xr.shape[0], wr.shape[0]
+    out = np.empty((b, m), dtype=np.float64)
+    for i in range(b):
+        for j in range(m):
+            out[i, j] = float(np.dot(xr[i], wr[j])) + float(bias[j])
+    if relu:
+        out = np.maximum(out, 0.0)
+    return out.astype(np.float32)

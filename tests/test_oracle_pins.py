@@ -452,3 +452,38 @@ def test_kmeans_against_library_lloyd_and_invariants():
     res_0 = fo.kmeans_build(pts, lab, 3, init, 2)
     assert np.allclose(res_p["centers"], res_0["centers"], rtol=1e-6)
     assert np.array_equal(res_p["assign"], res_0["assign"][perm])
+
+
+# ---------------------------------------------------------------------------------------------
+# projection in front of the look-up (Sec. 3: one-layer dimensionality reduction)
+# ---------------------------------------------------------------------------------------------
+def test_bf16_rounding_matches_library_conversion_and_ties_go_to_even():
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.normal(size=5000).astype(np.float32) * 10.0 ** rng.integers(-20, 20, size=5000),
+                        np.array([0.0, -0.0, 1.0, -1.0, 3.3895314e38, 1e-40], np.float32)]).astype(np.float32)
+    assert np.array_equal(fo.round_to_bf16(x), torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy())
+    # halfway cases: 1 + 2^-8 lies between the bf16 neighbours 1 and 1 + 2^-7 -> even mantissa (1);
+    # 1 + 3 * 2^-8 lies between 1 + 2^-7 and 1 + 2^-6 -> even mantissa (1 + 2^-6)
+    assert fo.round_to_bf16(np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8], np.float32)).tolist() == [1.0, 1 + 2.0 ** -6]
+
+
+def test_projection_closed_forms_and_library_matmul():
+    rng = np.random.default_rng(2)
+    x = rng.normal(size=(7, 48)).astype(np.float32)
+    bias = rng.normal(size=48).astype(np.float32)
+    # identity weights: y = bf16(x) + b; with ReLU the negative part is cut
+    y = fo.project(x, np.eye(48, dtype=np.float32), bias, relu=False)
+    assert np.array_equal(y, (fo.round_to_bf16(x).astype(np.float64) + bias.astype(np.float64)).astype(np.float32))
+    yr = fo.project(x, np.eye(48, dtype=np.float32), bias, relu=True)
+    assert np.array_equal(yr, np.maximum(y, 0)) and (y < 0).any()
+    # general weights against a float64 library matmul on operands rounded by the library
+    w = rng.normal(size=(20, 48)).astype(np.float32)
+    xb = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64)
+    wb = torch.from_numpy(w).to(torch.bfloat16).to(torch.float64)
+    ref = (xb @ wb.T + torch.from_numpy(bias[:20]).to(torch.float64)).to(torch.float32).numpy()
+    got = fo.project(x, w, bias[:20], relu=False)
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6)
+    # weights handed over in bf16 are taken as they are, and a transposed operand would not pass
+    wbits = synth.bf16_bits(torch.from_numpy(w).to(torch.bfloat16))
+    assert np.array_equal(fo.project(x, wbits, bias[:20], relu=False), got)
+    assert got.shape == (7, 20)
