@@ -210,6 +210,28 @@ int freeze_kmeans_read(freeze_ctx *ctx, int layer, float *out_centers, int32_t *
                        float *out_fraction, void *stream);
 
 /*
+ * Dimensionality reduction in front of the look-up (Sec. 3: a one-layer network with a hidden
+ * layer of 1,024 nodes projects a layer's output before it is cached and looked up):
+ * y = W x + bias, optionally through ReLU.  The product runs on the matrix cores in bf16 (x and W
+ * rounded to nearest even; a W given in bf16 is taken as it is) with fp32 accumulation.
+ * A projection occupies one of the context's slots (look-ups on that slot fail with
+ * FREEZE_ENOTBUILT).
+ *   weights  [m, d] row-major, fp32 or bf16 (weights_dtype); bias [m] fp32.
+ *   storage  >= freeze_projection_storage_bytes() bytes, 256-byte aligned, must outlive the
+ *            calls of freeze_project on the slot; build workspace: >= 256 + 4 m bytes.
+ *   x        [b, d] fp32, 16-byte aligned;  out [b, m] fp32, 16-byte aligned.
+ *   workspace of freeze_project: >= freeze_project_workspace_bytes() bytes.
+ * b == 0 is a no-op.
+ */
+size_t freeze_projection_storage_bytes(int64_t m, int64_t d, int weights_dtype);
+int freeze_projection_build(freeze_ctx *ctx, int slot, const void *weights, int weights_dtype, int64_t m,
+                            int64_t d, const float *bias, void *storage, size_t storage_bytes,
+                            void *workspace, size_t workspace_bytes, void *stream);
+size_t freeze_project_workspace_bytes(const freeze_ctx *ctx, int slot, int64_t b);
+int freeze_project(freeze_ctx *ctx, int slot, const float *x, int64_t b, int relu, float *out,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Batch reconstruction on its own (Sec. 5): writes to sel_out the entries
  * sel_in[j] (or j itself when sel_in is NULL) with hit[j] == 0, j < count, in
  * order, and their number to *out_count.
@@ -219,6 +241,16 @@ int freeze_kmeans_read(freeze_ctx *ctx, int layer, float *out_centers, int32_t *
  */
 int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t count, int32_t *sel_out,
                           int32_t *out_count, void *stream);
+
+/*
+ * Batch reconstruction of a tensor (Sec. 5, "Freeze Inference on GPUs": the batch is rebuilt
+ * after a layer without the frozen items): out[j, :] = x[sel[j], :] for j < *count (or
+ * j < max_count when count is NULL), i.e. the next layer's input for the missed requests in
+ * miss-list order, as produced by freeze_compact_misses.  No host synchronisation.
+ *   x [*, d] fp32;  sel [max_count] int32;  count device int32 or NULL;  out [max_count, d].
+ */
+int freeze_gather_rows(const float *x, int64_t d, const int32_t *sel, const int32_t *count,
+                       int64_t max_count, float *out, void *stream);
 
 /*
  * Stage timing for benchmarks (measurement aid; the look-up results do not depend on it).

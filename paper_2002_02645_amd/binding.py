@@ -68,6 +68,16 @@ def lib():
     L.freeze_kmeans_build.argtypes = [p, i32, p, i64, i64, p, ctypes.c_int32, p, i64, i32, p, sz, p, sz, p]
     L.freeze_kmeans_read.restype = i32
     L.freeze_kmeans_read.argtypes = [p, i32, p, p, p, p]
+    L.freeze_projection_storage_bytes.restype = sz
+    L.freeze_projection_storage_bytes.argtypes = [i64, i64, i32]
+    L.freeze_projection_build.restype = i32
+    L.freeze_projection_build.argtypes = [p, i32, p, i32, i64, i64, p, p, sz, p, sz, p]
+    L.freeze_project_workspace_bytes.restype = sz
+    L.freeze_project_workspace_bytes.argtypes = [p, i32, i64]
+    L.freeze_project.restype = i32
+    L.freeze_project.argtypes = [p, i32, p, i64, i32, p, p, sz, p]
+    L.freeze_gather_rows.restype = i32
+    L.freeze_gather_rows.argtypes = [p, i64, p, p, i64, p, p]
     L.freeze_compute_thresholds.restype = i32
     L.freeze_compute_thresholds.argtypes = [p, i32, p, p, i64, i32, i32, p, p, p, sz, p]
     L.freeze_profile_enable.restype = i32
@@ -248,6 +258,42 @@ def freeze_kmeans_read(ctx, layer: int, out_centers: torch.Tensor, out_majority:
                                     _stream(stream)), "freeze_kmeans_read")
 
 
+def freeze_projection_storage_bytes(m: int, d: int, weights_dtype: int) -> int:
+    return int(lib().freeze_projection_storage_bytes(m, d, weights_dtype))
+
+
+def freeze_projection_build(ctx, slot: int, weights: torch.Tensor, bias: torch.Tensor, storage: torch.Tensor,
+                            workspace: torch.Tensor, stream=None) -> None:
+    assert weights.is_cuda and weights.is_contiguous() and weights.dim() == 2
+    assert bias.is_cuda and bias.dtype == torch.float32 and bias.numel() == weights.shape[0]
+    dtype = {torch.float32: FREEZE_F32, torch.bfloat16: FREEZE_BF16}[weights.dtype]
+    _check(lib().freeze_projection_build(ctx, slot, _ptr(weights), dtype, weights.shape[0], weights.shape[1], _ptr(bias),
+                                         _ptr(storage), storage.numel() * storage.element_size(), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "freeze_projection_build")
+
+
+def freeze_project_workspace_bytes(ctx, slot: int, b: int) -> int:
+    return int(lib().freeze_project_workspace_bytes(ctx, slot, b))
+
+
+def freeze_project(ctx, slot: int, x: torch.Tensor, relu: bool, out: torch.Tensor, workspace: torch.Tensor,
+                   stream=None) -> None:
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 2
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape[0] == x.shape[0]
+    _check(lib().freeze_project(ctx, slot, _ptr(x), x.shape[0], int(relu), _ptr(out), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)), "freeze_project")
+
+
+def freeze_gather_rows(x: torch.Tensor, sel: torch.Tensor, count: Optional[torch.Tensor], out: torch.Tensor,
+                       stream=None) -> None:
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 2
+    assert sel.dtype == torch.int32 and out.dtype == torch.float32 and out.is_contiguous()
+    assert out.shape[0] >= sel.numel() and out.shape[1] == x.shape[1]
+    _check(lib().freeze_gather_rows(_ptr(x), x.shape[1], _ptr(sel), _ptr(count), sel.numel(), _ptr(out),
+                                    _stream(stream)), "freeze_gather_rows")
+
+
 def freeze_compact_misses(hit: torch.Tensor, sel_in: Optional[torch.Tensor], sel_out: torch.Tensor,
                           out_count: torch.Tensor, stream=None) -> None:
     assert hit.is_cuda and hit.dtype == torch.uint8
@@ -419,4 +465,26 @@ class FreezeCache:
                    majority=torch.empty(kc, dtype=torch.int32, device=self.device),
                    fraction=torch.empty(kc, dtype=torch.float32, device=self.device))
         freeze_kmeans_read(self.ctx, layer, out["centers"], out["majority"], out["fraction"])
+        return out
+
+    def build_projection(self, slot: int, weights: torch.Tensor, bias: torch.Tensor):
+        """A dense layer y = W x + bias in front of a look-up (Sec. 3); occupies one slot of the context."""
+        m, d = weights.shape
+        dtype = FREEZE_BF16 if weights.dtype == torch.bfloat16 else FREEZE_F32
+        nbytes = freeze_projection_storage_bytes(m, d, dtype)
+        if nbytes == 0:
+            raise FreezeError(FREEZE_EINVAL, "freeze_projection_storage_bytes")
+        st = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        ws = self._workspace(256 + 4 * m)
+        freeze_projection_build(self.ctx, slot, weights, bias, st, ws)
+        self.storage[slot] = st
+        self.meta[slot] = (m, d, 0)
+
+    def project(self, slot: int, x: torch.Tensor, relu: bool = False) -> torch.Tensor:
+        m = self.meta[slot][0]
+        out = torch.empty((x.shape[0], m), dtype=torch.float32, device=self.device)
+        nbytes = freeze_project_workspace_bytes(self.ctx, slot, x.shape[0])
+        if nbytes == 0:
+            raise FreezeError(FREEZE_EINVAL, "freeze_project_workspace_bytes")
+        freeze_project(self.ctx, slot, x, relu, out, self._workspace(nbytes))
         return out

@@ -906,6 +906,35 @@ hipError_t launch_cascade_scatter(const int32_t *labels, const uint8_t *hit, con
 }
 
 // ---------------------------------------------------------------------------------------
+// Batch reconstruction of a tensor (Sec. 5, "Freeze Inference on GPUs"): the rows of the missed
+// requests, in miss-list order, so that the next layer of the model runs on a dense smaller
+// batch.  One block per output row; nothing is done past the device-side count.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float *x, int64_t d, const int32_t *sel, const int32_t *count,
+                                                          int64_t max_count, float *out)
+{
+    const int64_t nq = count ? *count : max_count;
+    const int64_t j = blockIdx.x;
+    if (j >= nq) return;
+    const float *src = x + (int64_t)sel[j] * d;
+    float *dst = out + j * d;
+    if ((d % 4) == 0 && (reinterpret_cast<uintptr_t>(x) % 16) == 0 && (reinterpret_cast<uintptr_t>(out) % 16) == 0) {
+        for (int64_t i = threadIdx.x; i < d / 4; i += 256)
+            reinterpret_cast<f32x4 *>(dst)[i] = reinterpret_cast<const f32x4 *>(src)[i];
+    } else {
+        for (int64_t i = threadIdx.x; i < d; i += 256) dst[i] = src[i];
+    }
+}
+
+hipError_t launch_gather_rows(const float *x, int64_t d, const int32_t *sel, const int32_t *count, int64_t max_count,
+                              float *out, hipStream_t s)
+{
+    if (max_count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)max_count), dim3(256), 0, s, x, d, sel, count, max_count, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // Per-layer threshold (Pseudocode 1, ComputeThresholds): the largest confidence among the
 // validation items whose look-up disagrees with the model's label; 0 when none disagrees.
 // Confidences are >= 0 (or +inf), so their fp32 bit patterns order like unsigned integers.

@@ -114,6 +114,9 @@ struct DistKernelArgs {
     // share cache tiles [0, bal_nfull) and the remaining workgroups of the grid share what is
     // left of all query tiles; 0 = off.
     int bal_f, bal_nfull;
+    // keys-out variant as a plain projection: out = acc + norm[col] (the bias), optionally through
+    // ReLU, no block minima
+    int projection, relu;
 };
 
 // Epilogue of the keys-out variant: every key of the tile and the minimum of every block of 32
@@ -124,6 +127,7 @@ __device__ __forceinline__ void keys_epilogue(f32x16 (&acc)[C::TM][C::TN], const
 {
     constexpr int BM = C::BM, TM = C::TM, TN = C::TN;
     const int g = lane >> 5;
+    const float scale = p.projection ? 1.f : -2.f;
     static_assert(!C::KEYS || C::WNS == C::WN, "keys-out epilogue: one slab pass covers all wave columns");
 #pragma unroll
     for (int bj = 0; bj < TN; ++bj) {
@@ -136,8 +140,9 @@ __device__ __forceinline__ void keys_epilogue(f32x16 (&acc)[C::TM][C::TN], const
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-                    slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] =
-                        __builtin_fmaf(-2.f, acc[bi][bj][e], nrm);
+                    float v = __builtin_fmaf(scale, acc[bi][bj][e], nrm);
+                    if (p.relu) v = __builtin_fmaxf(v, 0.f);
+                    slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = v;
                 }
             }
         }
@@ -167,7 +172,7 @@ __device__ __forceinline__ void keys_epilogue(f32x16 (&acc)[C::TM][C::TN], const
                 const uint64_t o = ((uint64_t)hi << 32) | lo;
                 mn = o < mn ? o : mn;
             }
-            if (live && (l32 & 7) == 0) p.bmin[(size_t)grow * (p.n_pad / 32) + (gcol >> 5)] = mn;
+            if (live && (l32 & 7) == 0 && !p.projection) p.bmin[(size_t)grow * (p.n_pad / 32) + (gcol >> 5)] = mn;
         }
         __syncthreads();
     }
@@ -267,7 +272,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 
         // Direct loads copy a stage linearly: wave w, instruction i moves the 1 KiB at offset
         // (i * NWAVES + w) * 1024 of the stage's A (or B) image; lane l moves 16 bytes at + 16 l.
-        const uint64_t gA = uniform_u64((uint64_t)(uintptr_t)p.q_bf + (size_t)mt * BM * tile_row_bytes);
+        const uint64_t gA_part = uniform_u64((uint64_t)(uintptr_t)p.q_bf + (size_t)mt * BM * tile_row_bytes);
         // fragment read addresses, in 16-byte units relative to the stage's A / B image
         const int g = lane >> 5;
         const int rowA = wm * TM * 32 + (lane & 31);
@@ -279,17 +284,23 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         // The workgroup walks segments (cache tile, range of k-steps) of the flattened space: whole
         // tiles nt0 .. nt1-1, or under stream-K the k-steps [x sk_len, (x+1) sk_len) whatever tiles
         // they fall in.
-        const int64_t g_end = stream_k ? ((int64_t)(blockIdx.x + 1) * p.sk_len < (int64_t)p.n_tiles * nk
+        const int64_t sk_total = (int64_t)live_mt * p.n_tiles * nk;   // stream-K: (query tile, cache tile, k-step)
+        const int64_t g_end = stream_k ? ((int64_t)(blockIdx.x + 1) * p.sk_len < sk_total
                                               ? (int64_t)(blockIdx.x + 1) * p.sk_len
-                                              : (int64_t)p.n_tiles * nk)
+                                              : sk_total)
                                        : (int64_t)nt1 * nk;
         int seg = 0;
         for (int64_t gk = stream_k ? (int64_t)blockIdx.x * p.sk_len : (int64_t)nt0 * nk; gk < g_end; ++seg) {
-            const int nt = (int)(gk / nk);
-            const int ka = (int)(gk - (int64_t)nt * nk);                               // first k-step of the segment
+            const int tile = (int)(gk / nk);                  // under stream-K: query tile * n_tiles + cache tile
+            const int nt = stream_k ? tile % p.n_tiles : tile;
+            const int smt = stream_k ? tile / p.n_tiles : mt;   // the segment's query tile
+            const int ka = (int)(gk - (int64_t)tile * nk);                             // first k-step of the segment
             const int kb = (g_end - gk < nk - ka) ? ka + (int)(g_end - gk) : nk;     // one past its last
             gk += kb - ka;
             const int n0 = nt * BN;
+            const uint64_t gA = stream_k
+                                    ? uniform_u64((uint64_t)(uintptr_t)p.q_bf + (size_t)smt * BM * tile_row_bytes)
+                                    : gA_part;
             const uint64_t gB = uniform_u64((uint64_t)(uintptr_t)p.c_bf + (size_t)nt * BN * tile_row_bytes);
             // one instruction of a stage's fill: l < NI_A -> A image, else B image
             auto issue_one = [&](int stage, int kt, int l) {
@@ -407,7 +418,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                                     f32x4{acc[bi][bj][4 * e4], acc[bi][bj][4 * e4 + 1], acc[bi][bj][4 * e4 + 2], acc[bi][bj][4 * e4 + 3]};
                     continue;
                 }
-                keys_epilogue<C>(acc, p, slab, mt, n0, nq, w, wm, wn, lane);
+                keys_epilogue<C>(acc, p, slab, smt, n0, nq, w, wm, wn, lane);
                 continue;
             }
             // ---- epilogue: fold this tile into the per-row top-R lists ----
@@ -518,9 +529,10 @@ __global__ __launch_bounds__(C::THREADS) void keys_fixup_kernel(DistKernelArgs p
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = w / C::WN, wn = w % C::WN;
-    const int nt = blockIdx.x;
+    const int tile = blockIdx.x;                       // query tile * n_tiles + cache tile
+    const int nt = tile % p.n_tiles, mt = tile / p.n_tiles;
     const int nk = p.d_pad / C::BK;
-    const int64_t g0 = (int64_t)nt * nk, g1 = g0 + nk;
+    const int64_t g0 = (int64_t)tile * nk, g1 = g0 + nk;
     const int w_first = (int)(g0 / p.sk_len), w_last = (int)((g1 - 1) / p.sk_len);
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -530,7 +542,7 @@ __global__ __launch_bounds__(C::THREADS) void keys_fixup_kernel(DistKernelArgs p
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     for (int x = w_first; x <= w_last; ++x) {
-        const int seg = nt - (int)(((int64_t)x * p.sk_len) / nk);   // tiles workgroup x touched before this one
+        const int seg = tile - (int)(((int64_t)x * p.sk_len) / nk);   // tiles workgroup x touched before this one
         const f32x4 *src = reinterpret_cast<const f32x4 *>(p.partial) + ((size_t)x * p.sk_slots + seg) * (size_t)(BM * BN / 4);
 #pragma unroll
         for (int bi = 0; bi < TM; ++bi)
@@ -544,7 +556,7 @@ __global__ __launch_bounds__(C::THREADS) void keys_fixup_kernel(DistKernelArgs p
                 }
     }
     const int nq = p.count ? *p.count : p.b;
-    keys_epilogue<C>(acc, p, slab, 0, nt * BN, nq, w, wm, wn, lane);
+    keys_epilogue<C>(acc, p, slab, mt, nt * BN, nq, w, wm, wn, lane);
 }
 
 DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out, int64_t d_pad)
@@ -599,21 +611,27 @@ DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out, int6
             }
         }
     }
-    // Stream-K for the keys-out variant when whole tiles fill the CUs badly (196 tiles on 256 CUs
-    // leave a quarter of the chip idle) and a tile is long enough to be worth cutting.
     pl.sk_wgs = pl.sk_len = pl.sk_slots = 0;
-    if (keys_out && pl.m_tiles == 1 && d_pad >= 64 * 32) {
-        const int nk = (int)(d_pad / 32);   // k-steps per tile of the keys-out variant
-        const int rounds = (pl.n_tiles + num_cus - 1) / num_cus;
-        const double fill = (double)pl.n_tiles / ((double)rounds * num_cus);
-        if (fill < 0.9 && rounds <= 4 && pl.n_tiles * 2 > num_cus) {
-            const int64_t total = (int64_t)pl.n_tiles * nk;
-            pl.sk_wgs = num_cus;
-            pl.sk_len = (int)((total + num_cus - 1) / num_cus);
-            pl.sk_slots = (pl.sk_len - 1) / nk + 2;
-        }
-    }
+    if (keys_out) plan_stream_k(pl, num_cus, d_pad);
     return pl;
+}
+
+// Stream-K for the keys-out variant when whole (query tile, cache tile) units fill the CUs badly
+// (196 units on 256 CUs leave a quarter of the chip idle; 4 units nearly all of it) and the depth
+// is long enough to be worth cutting.
+void plan_stream_k(DistPlan &pl, int num_cus, int64_t d_pad)
+{
+    pl.sk_wgs = pl.sk_len = pl.sk_slots = 0;
+    const int nk = (int)(d_pad / 32);   // k-steps per tile of the keys-out variant
+    const int64_t tiles = (int64_t)pl.m_tiles * pl.n_tiles;
+    const int64_t rounds = (tiles + num_cus - 1) / num_cus;
+    const double fill = (double)tiles / ((double)rounds * num_cus);
+    const int64_t total = tiles * nk;
+    if (fill < 0.9 && rounds <= 4 && nk >= 64 && total >= 16 * (int64_t)num_cus) {
+        pl.sk_wgs = num_cus;
+        pl.sk_len = (int)((total + num_cus - 1) / num_cus);
+        pl.sk_slots = (pl.sk_len - 1) / nk + 2;
+    }
 }
 
 size_t dist_partial_bytes(const DistPlan &plan)
@@ -645,17 +663,19 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
     }
     k.keys = a.keys;
     k.bmin = a.bmin;
+    k.projection = a.projection ? 1 : 0;
+    k.relu = a.relu ? 1 : 0;
     k.n_pad = (int64_t)plan.n_tiles * kTileN;
     if constexpr (C::KEYS) {
         if (plan.sk_wgs > 0) {
-            if (!a.partial || a.count || plan.m_tiles != 1) return hipErrorInvalidValue;
+            if (!a.partial || a.count) return hipErrorInvalidValue;
             k.partial = a.partial;
             k.sk_len = plan.sk_len;
             k.sk_slots = plan.sk_slots;
             hipLaunchKernelGGL((dist_topr_kernel<C>), dim3(plan.sk_wgs), dim3(C::THREADS), 0, s, k);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL((keys_fixup_kernel<C>), dim3(plan.n_tiles), dim3(C::THREADS), 0, s, k);
+            hipLaunchKernelGGL((keys_fixup_kernel<C>), dim3(plan.m_tiles * plan.n_tiles), dim3(C::THREADS), 0, s, k);
             return hipGetLastError();
         }
     }
@@ -675,7 +695,7 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
 hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t s)
 {
     if (plan.r < 1 || plan.r > kMaxRescore || a.d_pad % kPadD != 0) return hipErrorInvalidValue;
-    if (plan.variant == 3 && (!a.keys || !a.bmin)) return hipErrorInvalidValue;
+    if (plan.variant == 3 && (!a.keys || (!a.bmin && !a.projection))) return hipErrorInvalidValue;
     switch (plan.variant) {
     case 0: return launch_variant<DistCfg<256, 32, 16, 4>>(plan, a, s);
     case 1: return launch_variant<DistCfg<256, 32, 32, 3>>(plan, a, s);

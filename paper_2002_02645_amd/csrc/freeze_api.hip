@@ -125,7 +125,7 @@ const LayerCache *get_layer(const freeze_ctx *ctx, int layer, int *err)
         *err = FREEZE_ELAYER;
         return nullptr;
     }
-    if (!ctx->layers[layer].built) {
+    if (!ctx->layers[layer].built || ctx->layers[layer].bias) {   // a projection is not a cache
         *err = FREEZE_ENOTBUILT;
         return nullptr;
     }
@@ -490,6 +490,7 @@ int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entr
     L.c_f32 = c_f32;
     L.c_rows = c_rows;
     L.fraction = nullptr;
+    L.bias = nullptr;
     L.built = true;
     return FREEZE_OK;
 }
@@ -726,6 +727,125 @@ int freeze_kmeans_read(freeze_ctx *ctx, int layer, float *out_centers, int32_t *
     return FREEZE_OK;
 }
 
+size_t freeze_projection_storage_bytes(int64_t m, int64_t d, int weights_dtype)
+{
+    CacheLayout cl;
+    if (!cache_layout(m, d, weights_dtype, &cl)) return 0;
+    return cl.bytes + align_up((size_t)cl.n_pad * 4);
+}
+
+int freeze_projection_build(freeze_ctx *ctx, int slot, const void *weights, int weights_dtype, int64_t m, int64_t d,
+                            const float *bias, void *storage, size_t storage_bytes, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    if (!ctx || !weights || !bias || !storage || !workspace) return FREEZE_EINVAL;
+    if (slot < 0 || slot >= (int)ctx->layers.size()) return FREEZE_ELAYER;
+    CacheLayout cl;
+    if (!cache_layout(m, d, weights_dtype, &cl)) return FREEZE_EINVAL;
+    if (storage_bytes < cl.bytes + align_up((size_t)cl.n_pad * 4) || (reinterpret_cast<uintptr_t>(storage) % kAlign) != 0)
+        return FREEZE_EWORKSPACE;
+    if (workspace_bytes < align_up((size_t)m * 4) || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return FREEZE_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the rows of W go through the cache ingest (bf16, tiled); its labels are not used
+    int32_t *dummy_labels = static_cast<int32_t *>(workspace);
+    if (launch_fill_i32(dummy_labels, 0, m, s) != hipSuccess) return FREEZE_EHIP;
+    int rc = freeze_cache_build(ctx, slot, weights, weights_dtype, m, d, dummy_labels, 1, storage, cl.bytes, stream);
+    if (rc != FREEZE_OK) return rc;
+    float *bias_pad = reinterpret_cast<float *>(static_cast<unsigned char *>(storage) + cl.bytes);
+    if (launch_fill_i32(reinterpret_cast<int32_t *>(bias_pad), 0, cl.n_pad, s) != hipSuccess) return FREEZE_EHIP;
+    if (launch_copy_rows_f32(bias, 1, bias_pad, m, 1, s) != hipSuccess) return FREEZE_EHIP;
+    ctx->layers[slot].bias = bias_pad;
+    return FREEZE_OK;
+}
+
+namespace {
+const LayerCache *get_projection(const freeze_ctx *ctx, int slot, int *err)
+{
+    if (!ctx) {
+        *err = FREEZE_EINVAL;
+        return nullptr;
+    }
+    if (slot < 0 || slot >= (int)ctx->layers.size()) {
+        *err = FREEZE_ELAYER;
+        return nullptr;
+    }
+    if (!ctx->layers[slot].built || !ctx->layers[slot].bias) {
+        *err = FREEZE_ENOTBUILT;
+        return nullptr;
+    }
+    *err = FREEZE_OK;
+    return &ctx->layers[slot];
+}
+// one workgroup per (tile of 256 inputs, tile of 256 outputs), whole depth
+DistPlan projection_plan(const freeze_ctx *ctx, const LayerCache &P, int64_t b)
+{
+    DistPlan pl{};
+    pl.variant = 3;
+    pl.bm = 256;
+    pl.r = 1;
+    pl.m_tiles = (int)((b + 255) / 256);
+    if (pl.m_tiles < 1) pl.m_tiles = 1;
+    pl.n_tiles = (int)(P.n_pad / kTileN);
+    pl.n_splits = pl.alloc_splits = pl.n_tiles;
+    pl.max_splits = pl.n_tiles;
+    pl.grid_units = pl.m_tiles * pl.n_tiles;
+    pl.num_cus = ctx->num_cus;
+    pl.b_pad = (int64_t)pl.m_tiles * 256;
+    plan_stream_k(pl, ctx->num_cus, P.d_pad);
+    return pl;
+}
+}  // namespace
+
+size_t freeze_project_workspace_bytes(const freeze_ctx *ctx, int slot, int64_t b)
+{
+    int err;
+    const LayerCache *P = get_projection(ctx, slot, &err);
+    if (!P || b < 0 || b > (int64_t)1 << 30) return 0;
+    const int64_t b_pad = (b + 255) / 256 * 256 + (b == 0 ? 256 : 0);
+    const DistPlan pl = projection_plan(ctx, *P, b);
+    return align_up((size_t)b_pad * P->d_pad * 2) + align_up((size_t)(b > 0 ? b : 1) * P->n_pad * 4) +
+           align_up(dist_partial_bytes(pl));
+}
+
+int freeze_project(freeze_ctx *ctx, int slot, const float *x, int64_t b, int relu, float *out, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    int err;
+    const LayerCache *P = get_projection(ctx, slot, &err);
+    if (!P) return err;
+    if (b < 0 || b > (int64_t)1 << 30) return FREEZE_EINVAL;
+    if (b == 0) return FREEZE_OK;
+    if (!x || !out || !workspace || (reinterpret_cast<uintptr_t>(x) % 16) != 0 ||
+        (reinterpret_cast<uintptr_t>(out) % 16) != 0)
+        return FREEZE_EINVAL;
+    if (workspace_bytes < freeze_project_workspace_bytes(ctx, slot, b) || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0)
+        return FREEZE_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const DistPlan pl = projection_plan(ctx, *P, b);
+    Carver ws(workspace);
+    uint16_t *x_bf = ws.take<uint16_t>((size_t)pl.b_pad * P->d_pad);
+    float *tmp = ws.take<float>((size_t)b * P->n_pad);
+    float *partial = pl.sk_wgs > 0 ? ws.take<float>(dist_partial_bytes(pl) / 4) : nullptr;
+    if (launch_query_prep(x, nullptr, nullptr, b, pl.b_pad, pl.bm, P->d, P->d_pad, x_bf, s) != hipSuccess)
+        return FREEZE_EHIP;
+    const bool direct = P->n == P->n_pad;   // the output rows are then exactly what the kernel writes
+    DistArgs da{};
+    da.q_bf = x_bf;
+    da.c_bf = P->c_bf;
+    da.norm = P->bias;
+    da.keys = direct ? out : tmp;
+    da.b = (int)b;
+    da.n = (int)P->n;
+    da.d_pad = (int)P->d_pad;
+    da.projection = true;
+    da.relu = relu != 0;
+    da.partial = partial;
+    if (launch_dist_topr(pl, da, s) != hipSuccess) return FREEZE_EHIP;
+    if (!direct && launch_copy_rows_f32(tmp, P->n_pad, out, b, P->n, s) != hipSuccess) return FREEZE_EHIP;
+    return FREEZE_OK;
+}
+
 int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t count, int32_t *sel_out,
                           int32_t *out_count, void *stream)
 {
@@ -733,6 +853,16 @@ int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t cou
     if (count > 0 && (!hit || !sel_out)) return FREEZE_EINVAL;
     if (launch_compact(hit, sel_in, nullptr, count, sel_out, out_count, nullptr, static_cast<hipStream_t>(stream)) !=
         hipSuccess)
+        return FREEZE_EHIP;
+    return FREEZE_OK;
+}
+
+int freeze_gather_rows(const float *x, int64_t d, const int32_t *sel, const int32_t *count, int64_t max_count,
+                       float *out, void *stream)
+{
+    if (d < 1 || max_count < 0 || max_count > (int64_t)1 << 30) return FREEZE_EINVAL;
+    if (max_count > 0 && (!x || !sel || !out)) return FREEZE_EINVAL;
+    if (launch_gather_rows(x, d, sel, count, max_count, out, static_cast<hipStream_t>(stream)) != hipSuccess)
         return FREEZE_EHIP;
     return FREEZE_OK;
 }

@@ -59,6 +59,8 @@ struct LayerCache {
     const uint16_t *c_rows = nullptr; // [n, d_pad] row-major bf16 rows when the cache was given in bf16, else null
     // k-means cache: the entries are cluster centres, labels their majority labels, and
     const float *fraction = nullptr;  // [n] the share of each cluster that carries its majority label (else null)
+    // projection (a dense layer in front of the look-up): the entries are the rows of W and
+    const float *bias = nullptr;      // [n_pad] its bias, zero padded (else null); not a cache: look-ups reject it
 };
 
 // Number of splits of the cache tiles for `live_mt` live query tiles.  Units (query tile, split)
@@ -118,6 +120,7 @@ struct DistPlan {
 
 // d_pad decides stream-K for the keys-out variant (pass 0 to leave it off).
 DistPlan plan_dist(int64_t b, int64_t n, int r, int num_cus, bool keys_out, int64_t d_pad = 0);
+void plan_stream_k(DistPlan &pl, int num_cus, int64_t d_pad);   // sets the sk_* fields of a keys-out plan
 size_t dist_partial_bytes(const DistPlan &plan);   // stream-K accumulator slots (0 when off)
 
 struct DistArgs {
@@ -128,6 +131,8 @@ struct DistArgs {
     float *keys;            // [b_pad, n_pad] every key (keys-out variant)
     uint64_t *bmin;         // [b_pad, n_pad / 32] block minima (keys-out variant)
     float *partial;         // dist_partial_bytes(plan) bytes of scratch (keys-out variant under stream-K)
+    bool projection;        // keys-out variant as a projection: keys = acc + norm[col] (norm holds the bias), no bmin
+    bool relu;              // ... through max(., 0)
     bool balanced;          // use the plan's balanced decomposition (needs lists >= plan.bal_lists)
     int lists;              // candidate lists per query `part` has room for (their stride); fused variants
     const int32_t *count;   // device: number of live queries, or null (= b)
@@ -224,6 +229,8 @@ hipError_t launch_copy_rows_f32(const float *src, int64_t src_stride, float *dst
 hipError_t launch_fill_i32(int32_t *dst, int32_t v, int64_t n, hipStream_t s);
 hipError_t launch_copy_i32(const int32_t *src, int32_t *dst, int64_t n, hipStream_t s);
 
+hipError_t launch_gather_rows(const float *x, int64_t d, const int32_t *sel, const int32_t *count, int64_t max_count,
+                              float *out, hipStream_t s);
 hipError_t launch_threshold_init(float *thr, int n, hipStream_t s);
 hipError_t launch_threshold_max(const int32_t *pred, const float *conf, const int32_t *model_labels, int64_t b,
                                 float *thr, hipStream_t s);
