@@ -200,7 +200,8 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         from oracle import freeze_oracle as fo
-        default_sample = {"c2_batched": 128, "c3_wide": 16, "c1_tiny": 256, "c4_cascade": 16, "c4_cascade_noisy": 16}
+        # sized for about 10-20 s of oracle time on the box's 16 host cores
+        default_sample = {"c2_batched": 768, "c3_wide": 96, "c1_tiny": 256, "c4_cascade": 48, "c4_cascade_noisy": 48}
         sample = min(args.cpu_sample or default_sample.get(wl.name, min(b, 64)), b)
         g = torch.Generator().manual_seed(wl.seed + 999)
         pick = torch.randperm(b, generator=g)[:sample].sort().values
