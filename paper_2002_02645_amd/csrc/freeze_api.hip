@@ -422,6 +422,64 @@ int cascade_checked(freeze_ctx *ctx, int num_layers, const int *layers, const fl
     return FREEZE_OK;
 }
 
+struct KmeansLayout {
+    size_t lookup_ws;
+    size_t bytes;
+};
+// workspace: two centre buffers, dummy labels, the look-up's outputs for n points and its workspace
+bool kmeans_layout(const freeze_ctx *ctx, int64_t n, int64_t d, int64_t kc, KmeansLayout *out)
+{
+    CacheLayout cl;
+    if (!ctx || n < 1 || n > (int64_t)1 << 30 || kc < 1 || kc > n || !cache_layout(kc, d, FREEZE_F32, &cl)) return false;
+    LayerCache tmp;   // shape of the centres as a cache
+    tmp.n = kc;
+    tmp.d = d;
+    tmp.n_pad = cl.n_pad;
+    tmp.d_pad = cl.d_pad;
+    LookupShape sh;
+    if (!lookup_shape(ctx, tmp, n, 1, 0, false, &sh)) return false;
+    out->lookup_ws = sh.ws_bytes;
+    out->bytes = sh.ws_bytes + 2 * align_up((size_t)kc * d * 4) + align_up((size_t)kc * 4) + 3 * align_up((size_t)n * 4) +
+                 align_up((size_t)n) + 2 * align_up((size_t)n * 4);
+    return true;
+}
+
+const LayerCache *get_projection(const freeze_ctx *ctx, int slot, int *err)
+{
+    if (!ctx) {
+        *err = FREEZE_EINVAL;
+        return nullptr;
+    }
+    if (slot < 0 || slot >= (int)ctx->layers.size()) {
+        *err = FREEZE_ELAYER;
+        return nullptr;
+    }
+    if (!ctx->layers[slot].built || !ctx->layers[slot].bias) {
+        *err = FREEZE_ENOTBUILT;
+        return nullptr;
+    }
+    *err = FREEZE_OK;
+    return &ctx->layers[slot];
+}
+// one workgroup per (tile of 256 inputs, tile of 256 outputs), whole depth
+DistPlan projection_plan(const freeze_ctx *ctx, const LayerCache &P, int64_t b)
+{
+    DistPlan pl{};
+    pl.variant = 3;
+    pl.bm = 256;
+    pl.r = 1;
+    pl.m_tiles = (int)((b + 255) / 256);
+    if (pl.m_tiles < 1) pl.m_tiles = 1;
+    pl.n_tiles = (int)(P.n_pad / kTileN);
+    pl.n_splits = pl.alloc_splits = pl.n_tiles;
+    pl.max_splits = pl.n_tiles;
+    pl.grid_units = pl.m_tiles * pl.n_tiles;
+    pl.num_cus = ctx->num_cus;
+    pl.b_pad = (int64_t)pl.m_tiles * 256;
+    plan_stream_k(pl, ctx->num_cus, P.d_pad);
+    return pl;
+}
+
 }  // namespace
 
 extern "C" {
@@ -622,30 +680,6 @@ size_t freeze_kmeans_storage_bytes(int64_t num_centers, int64_t d)
     return cl.bytes + align_up((size_t)num_centers * 4);
 }
 
-namespace {
-struct KmeansLayout {
-    size_t lookup_ws;
-    size_t bytes;
-};
-// workspace: two centre buffers, dummy labels, the look-up's outputs for n points and its workspace
-bool kmeans_layout(const freeze_ctx *ctx, int64_t n, int64_t d, int64_t kc, KmeansLayout *out)
-{
-    CacheLayout cl;
-    if (!ctx || n < 1 || n > (int64_t)1 << 30 || kc < 1 || kc > n || !cache_layout(kc, d, FREEZE_F32, &cl)) return false;
-    LayerCache tmp;   // shape of the centres as a cache
-    tmp.n = kc;
-    tmp.d = d;
-    tmp.n_pad = cl.n_pad;
-    tmp.d_pad = cl.d_pad;
-    LookupShape sh;
-    if (!lookup_shape(ctx, tmp, n, 1, 0, false, &sh)) return false;
-    out->lookup_ws = sh.ws_bytes;
-    out->bytes = sh.ws_bytes + 2 * align_up((size_t)kc * d * 4) + align_up((size_t)kc * 4) + 3 * align_up((size_t)n * 4) +
-                 align_up((size_t)n) + 2 * align_up((size_t)n * 4);
-    return true;
-}
-}  // namespace
-
 size_t freeze_kmeans_workspace_bytes(const freeze_ctx *ctx, int64_t n, int64_t d, int64_t num_centers)
 {
     KmeansLayout kl;
@@ -758,44 +792,6 @@ int freeze_projection_build(freeze_ctx *ctx, int slot, const void *weights, int 
     ctx->layers[slot].bias = bias_pad;
     return FREEZE_OK;
 }
-
-namespace {
-const LayerCache *get_projection(const freeze_ctx *ctx, int slot, int *err)
-{
-    if (!ctx) {
-        *err = FREEZE_EINVAL;
-        return nullptr;
-    }
-    if (slot < 0 || slot >= (int)ctx->layers.size()) {
-        *err = FREEZE_ELAYER;
-        return nullptr;
-    }
-    if (!ctx->layers[slot].built || !ctx->layers[slot].bias) {
-        *err = FREEZE_ENOTBUILT;
-        return nullptr;
-    }
-    *err = FREEZE_OK;
-    return &ctx->layers[slot];
-}
-// one workgroup per (tile of 256 inputs, tile of 256 outputs), whole depth
-DistPlan projection_plan(const freeze_ctx *ctx, const LayerCache &P, int64_t b)
-{
-    DistPlan pl{};
-    pl.variant = 3;
-    pl.bm = 256;
-    pl.r = 1;
-    pl.m_tiles = (int)((b + 255) / 256);
-    if (pl.m_tiles < 1) pl.m_tiles = 1;
-    pl.n_tiles = (int)(P.n_pad / kTileN);
-    pl.n_splits = pl.alloc_splits = pl.n_tiles;
-    pl.max_splits = pl.n_tiles;
-    pl.grid_units = pl.m_tiles * pl.n_tiles;
-    pl.num_cus = ctx->num_cus;
-    pl.b_pad = (int64_t)pl.m_tiles * 256;
-    plan_stream_k(pl, ctx->num_cus, P.d_pad);
-    return pl;
-}
-}  // namespace
 
 size_t freeze_project_workspace_bytes(const freeze_ctx *ctx, int slot, int64_t b)
 {

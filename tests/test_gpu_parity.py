@@ -88,6 +88,8 @@ def test_hand_example_on_gpu():
     (36000, 2080, 100, 10, 64, torch.float32), # stream-K, ragged d, workgroup ranges that span three tiles' parts
     (600, 16384, 40, 10, 0, torch.bfloat16),   # long activation, few queries: 1024-thread finishing blocks
     (600, 16392, 300, 10, 0, torch.float32),   # fused kernel, fp32 cache, long activation, d not a multiple of 64
+    (5000, 128, 50, 64, 0, torch.bfloat16),    # the largest k (= the largest R) on the tiled kernel
+    (5000, 128, 4, 64, 0, torch.float32),      # ... and on the small-batch kernel
     (50000, 64, 10000, 10, 0, torch.bfloat16), # 40 x 196 tiles on 256 CUs: balanced decomposition, workgroups that serve two query tiles
     (33000, 96, 7000, 5, 0, torch.float32),    # balanced decomposition, ragged last query tile
 ])
