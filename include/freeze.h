@@ -49,8 +49,11 @@ enum {
 
 enum { FREEZE_F32 = 0, FREEZE_BF16 = 1 }; /* element type of the entries handed to freeze_cache_build */
 
-/* Largest k and largest re-scoring width accepted by the look-ups. */
-#define FREEZE_MAX_K 64
+/* Largest k and largest re-scoring width accepted by the look-ups.  The bf16 matrix-core
+ * pass keeps at most FREEZE_MAX_RESCORE candidates per query for the exact fp32 re-scoring;
+ * candidates beyond the k-th absorb its rounding (entries whose coarse keys swap places around
+ * rank k), so k stays a third below that width unless the whole cache is taken (k = n). */
+#define FREEZE_MAX_K 48
 #define FREEZE_MAX_RESCORE 64
 
 /* Create / destroy a context with `num_layers` empty layer slots (host-only state). */
@@ -87,7 +90,8 @@ size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b
  * API: k nearest neighbours -> k (label, distance) tuples -> label with the most
  * occurrences m_i among the k -> hit decision; Pseudocode 1, FreezeInference).
  *   queries        [b, d] fp32 row-major.
- *   k              neighbours per query, 1 <= k <= min(n, FREEZE_MAX_K).
+ *   k              neighbours per query, 1 <= k <= min(n, FREEZE_MAX_K); k = n is also accepted up
+ *                  to FREEZE_MAX_RESCORE (every entry is then a candidate).
  *   vote_threshold hit iff the winning label holds >= vote_threshold of the k
  *                  neighbours; 1 <= vote_threshold <= k.
  *   rescore_r      candidates per query kept by the bf16 matrix-core pass and

@@ -79,7 +79,8 @@ int lists_per_query(const DistPlan &pl, bool device_count)
 bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, int rescore_r, bool cascade,
                   LookupShape *out)
 {
-    if (b < 0 || b > (int64_t)1 << 30 || k < 1 || k > FREEZE_MAX_K || k > L.n) return false;
+    if (b < 0 || b > (int64_t)1 << 30 || k < 1 || k > L.n) return false;
+    if (k > FREEZE_MAX_K && !(k == L.n && k <= FREEZE_MAX_RESCORE)) return false;
     int r = rescore_r == 0 ? default_rescore(k) : rescore_r;
     if (rescore_r != 0 && (rescore_r < k || rescore_r > FREEZE_MAX_RESCORE)) return false;
     if (r < k) r = k;

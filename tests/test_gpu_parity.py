@@ -88,8 +88,9 @@ def test_hand_example_on_gpu():
     (36000, 2080, 100, 10, 64, torch.float32), # stream-K, ragged d, workgroup ranges that span three tiles' parts
     (600, 16384, 40, 10, 0, torch.bfloat16),   # long activation, few queries: 1024-thread finishing blocks
     (600, 16392, 300, 10, 0, torch.float32),   # fused kernel, fp32 cache, long activation, d not a multiple of 64
-    (5000, 128, 50, 64, 0, torch.bfloat16),    # the largest k (= the largest R) on the tiled kernel
-    (5000, 128, 4, 64, 0, torch.float32),      # ... and on the small-batch kernel
+    (5000, 128, 50, 48, 0, torch.bfloat16),    # the largest k on the tiled kernel (R = 64)
+    (5000, 128, 4, 48, 0, torch.float32),      # ... and on the small-batch kernel
+    (64, 128, 20, 64, 0, torch.bfloat16),      # k = n = the re-scoring width: every entry is a candidate
     (50000, 64, 10000, 10, 0, torch.bfloat16), # 40 x 196 tiles on 256 CUs: balanced decomposition, workgroups that serve two query tiles
     (33000, 96, 7000, 5, 0, torch.float32),    # balanced decomposition, ragged last query tile
 ])
@@ -231,6 +232,7 @@ def test_argument_errors_launch_nothing():
         assert call(layer=1) == binding.FREEZE_ENOTBUILT
         assert call(k=0) == binding.FREEZE_EINVAL
         assert call(k=101) == binding.FREEZE_EINVAL
+        assert call(k=49, thr=3) == binding.FREEZE_EINVAL      # above the largest k (the cache has 100 entries)
         assert call(thr=0) == binding.FREEZE_EINVAL
         assert call(thr=6) == binding.FREEZE_EINVAL
         assert call(r=3) == binding.FREEZE_EINVAL
