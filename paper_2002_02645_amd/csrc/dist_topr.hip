@@ -283,20 +283,28 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 
         // The workgroup walks segments (cache tile, range of k-steps) of the flattened space: whole
         // tiles nt0 .. nt1-1, or under stream-K the k-steps [x sk_len, (x+1) sk_len) whatever tiles
-        // they fall in.
+        // they fall in.  Segment s of the range lies in tile (first tile + s); that number also names
+        // the slot its accumulators are left in, whatever order the segments are taken in.
+        // Under stream-K a range that ends inside a tile is taken with that last piece (k-steps from
+        // 0 up) first: then every workgroup moves through the depth upwards from 0, skipping one
+        // gap, and at any moment the workgroups of the chip read the query operand at two places
+        // of the depth instead of one place per starting offset, so most of those reads hit in L2.
         const int64_t sk_total = (int64_t)live_mt * p.n_tiles * nk;   // stream-K: (query tile, cache tile, k-step)
+        const int64_t g_begin = stream_k ? (int64_t)blockIdx.x * p.sk_len : (int64_t)nt0 * nk;
         const int64_t g_end = stream_k ? ((int64_t)(blockIdx.x + 1) * p.sk_len < sk_total
                                               ? (int64_t)(blockIdx.x + 1) * p.sk_len
                                               : sk_total)
                                        : (int64_t)nt1 * nk;
-        int seg = 0;
-        for (int64_t gk = stream_k ? (int64_t)blockIdx.x * p.sk_len : (int64_t)nt0 * nk; gk < g_end; ++seg) {
-            const int tile = (int)(gk / nk);                  // under stream-K: query tile * n_tiles + cache tile
+        const int tile0 = (int)(g_begin / nk);
+        const int nseg = g_begin < g_end ? (int)((g_end - 1) / nk) - tile0 + 1 : 0;
+        const bool head_first = stream_k && nseg >= 2 && g_end < (int64_t)(tile0 + nseg) * nk;
+        for (int it = 0; it < nseg; ++it) {
+            const int seg = head_first ? (it == 0 ? nseg - 1 : it - 1) : it;
+            const int tile = tile0 + seg;                     // under stream-K: query tile * n_tiles + cache tile
             const int nt = stream_k ? tile % p.n_tiles : tile;
             const int smt = stream_k ? tile / p.n_tiles : mt;   // the segment's query tile
-            const int ka = (int)(gk - (int64_t)tile * nk);                             // first k-step of the segment
-            const int kb = (g_end - gk < nk - ka) ? ka + (int)(g_end - gk) : nk;     // one past its last
-            gk += kb - ka;
+            const int ka = seg == 0 ? (int)(g_begin - (int64_t)tile0 * nk) : 0;                // first k-step of the segment
+            const int kb = seg == nseg - 1 ? (int)(g_end - (int64_t)tile * nk) : nk;          // one past its last
             const int n0 = nt * BN;
             const uint64_t gA = stream_k
                                     ? uniform_u64((uint64_t)(uintptr_t)p.q_bf + (size_t)smt * BM * tile_row_bytes)
