@@ -18,7 +18,9 @@
 // cache tiles, so that operand re-reads are served by that XCD's L2.
 //
 // Main loop: 8 waves (2 x 4), each owning a (TM*32) x 64 block of the tile as
-// 32x32x16 bf16 MFMA accumulators.  Both operands are stored in memory in a tiled,
+// 16x16x32 bf16 MFMA accumulators (this shape sustains about a tenth more than 32x32x16 on
+// random operands: the chip runs matrix work against its power limit, and the shader clock it
+// holds depends on the instruction shape and on the data).  Both operands are stored in memory in a tiled,
 // pre-swizzled layout ([row tile][k-block][row][32 elements], see tiled_chunk_offset)
 // whose per-k-step blocks are contiguous and are exactly the LDS image, so a stage is
 // filled by a linear copy with LDS-direct 16-byte loads (no VGPR staging, fully
@@ -26,9 +28,9 @@
 // chunk swizzle makes the ds_read_b128 fragment reads bank-conflict free.  The loads
 // are issued with inline asm: the compiler would otherwise order every LDS read
 // behind the outstanding direct loads, serialising load and compute.  The loop is
-// software-pipelined by hand (one barrier per k-step, placed before its last MFMA
-// layer; loads and the next stage's first fragment reads issued one at a time between
-// MFMAs), with scheduling barriers pinning the order.
+// software-pipelined by hand (one barrier per k-step, placed before the MFMAs of its
+// second half; loads and the next stage's first fragment reads issued one at a time
+// between MFMAs), with scheduling barriers pinning the order.
 //
 // Epilogue (per tile, in column slabs that reuse the operand LDS): waves write their
 // keys to the slab; thread t scans row t, collecting a bit mask of keys not above the
@@ -37,10 +39,11 @@
 #include "freeze_internal.h"
 #include "select_common.h"
 
+#include <type_traits>
+
 namespace fz {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
@@ -69,7 +72,8 @@ struct DistCfg {
     static constexpr int NS = NS_;                  // operand stages in LDS, all in use (NS - 1 in flight)
     static constexpr int WM = 2, WN = WN_;          // wave grid: 2 x 4 (8 waves) or 2 x 2 (4 waves)
     static constexpr int NWAVES = WM * WN, THREADS = 64 * NWAVES;
-    static constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
+    static constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);   // 32 x 32 blocks per wave (epilogue units)
+    static constexpr int AM = 2 * TM, BNB = 2 * TN;                  // 16 x 16 MFMA blocks per wave
     static constexpr int NSUB = BK / kKB;           // k-blocks (of 32 elements) per stage
     static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
     static constexpr int A_BYTES = BM * BK * 2;
@@ -89,7 +93,7 @@ struct DistCfg {
     static_assert(BM <= THREADS, "one scanning thread per row");
     static constexpr int LPS = NI_A + NI_B;         // direct loads per thread and stage
     static_assert(NS >= 2 && NS <= 6 && (NS - 1) * LPS <= 63, "vmcnt range");
-    static_assert((BK / 16) % 2 == 0, "fragment buffer parity");
+    static_assert(BK == 32, "a k-step is one 16x16x32 MFMA layer");
 };
 
 struct DistKernelArgs {
@@ -122,7 +126,7 @@ struct DistKernelArgs {
 // Epilogue of the keys-out variant: every key of the tile and the minimum of every block of 32
 // entries.  Keys pass through the LDS slab so that the global stores are whole 512-byte row pieces.
 template <class C>
-__device__ __forceinline__ void keys_epilogue(f32x16 (&acc)[C::TM][C::TN], const DistKernelArgs &p, float *slab, int mt,
+__device__ __forceinline__ void keys_epilogue(f32x4 (&acc)[C::AM][C::BNB], const DistKernelArgs &p, float *slab, int mt,
                                               int n0, int nq, int w, int wm, int wn, int lane)
 {
     constexpr int BM = C::BM, TM = C::TM, TN = C::TN;
@@ -131,16 +135,19 @@ __device__ __forceinline__ void keys_epilogue(f32x16 (&acc)[C::TM][C::TN], const
     static_assert(!C::KEYS || C::WNS == C::WN, "keys-out epilogue: one slab pass covers all wave columns");
 #pragma unroll
     for (int bj = 0; bj < TN; ++bj) {
-        {
-            const int col = n0 + wn * TN * 32 + bj * 32 + (lane & 31);
+        // the wave's 32 columns of this pass are two MFMA blocks; a lane holds column (lane & 15)
+        // of each and rows 4 (lane >> 4) .. + 3 of every 16-row block
+#pragma unroll
+        for (int v2 = 0; v2 < 2; ++v2) {
+            const int col = n0 + wn * TN * 32 + bj * 32 + v2 * 16 + (lane & 15);
             const float nrm = p.norm[col];   // col < n_pad always
-            const int sc = wn * 32 + (lane & 31);
+            const int sc = wn * 32 + v2 * 16 + (lane & 15);
 #pragma unroll
-            for (int bi = 0; bi < TM; ++bi) {
+            for (int bi = 0; bi < C::AM; ++bi) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-                    float v = __builtin_fmaf(scale, acc[bi][bj][e], nrm);
+                for (int e = 0; e < 4; ++e) {
+                    const int row = wm * TM * 32 + bi * 16 + (lane >> 4) * 4 + e;
+                    float v = __builtin_fmaf(scale, acc[bi][2 * bj + v2][e], nrm);
                     if (p.relu) v = __builtin_fmaxf(v, 0.f);
                     slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = v;
                 }
@@ -274,11 +281,12 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         // (i * NWAVES + w) * 1024 of the stage's A (or B) image; lane l moves 16 bytes at + 16 l.
         const uint64_t gA_part = uniform_u64((uint64_t)(uintptr_t)p.q_bf + (size_t)mt * BM * tile_row_bytes);
         // fragment read addresses, in 16-byte units relative to the stage's A / B image
-        const int g = lane >> 5;
-        const int rowA = wm * TM * 32 + (lane & 31);
-        const int rowB = wn * TN * 32 + (lane & 31);
-        const int rdA = rowA * 4, pcxA = g ^ tiled_chunk_swizzle(rowA);
-        const int rdB = rowB * 4, pcxB = g ^ tiled_chunk_swizzle(rowB);
+        // (a 16x16x32 operand: lane l holds row l & 15 of the block and the 8 elements of chunk l >> 4;
+        // rows 16 apart share their swizzle)
+        const int rowA = wm * TM * 32 + (lane & 15);
+        const int rowB = wn * TN * 32 + (lane & 15);
+        const int rdA = rowA * 4 + ((lane >> 4) ^ tiled_chunk_swizzle(rowA));
+        const int rdB = rowB * 4 + ((lane >> 4) ^ tiled_chunk_swizzle(rowB));
         const int nk = p.d_pad / BK;
 
         // The workgroup walks segments (cache tile, range of k-steps) of the flattened space: whole
@@ -321,91 +329,102 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                                          sbase + C::A_BYTES + (l - C::NI_A) * (C::NWAVES * 1024));
             };
 
-            f32x16 acc[TM][TN];
+            f32x4 acc[C::AM][C::BNB];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < C::AM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < C::BNB; ++j)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
             {
-                // Software-pipelined loop.  Invariant at the top of k-step kt: the fragments of its first
-                // sub-step are in (or on their way to) register buffer 0; k-blocks kt+1 .. kt+NS-1 are in
-                // flight or landed in the other stages.  Before the last sub-step every read of the
+                // Software-pipelined loop.  A k-step is one MFMA layer (32 deep), taken in two halves:
+                // the wave's upper A blocks against all its B blocks, then the lower ones.  Invariant at
+                // the top of k-step kt: its first A half and its B blocks are in (or on their way to)
+                // registers; k-blocks kt+1 .. kt+NS-1 are in flight or landed in the other stages.  The
+                // second A half is read during the first half's MFMAs; after that every read of the
                 // current stage has been issued, so the step's only barrier goes there: it publishes the
                 // next stage (each wave waited for its own part) and frees the current one.  The MFMAs of
-                // the last sub-step need nothing newer, so the matrix pipe restarts at once, and the next
+                // the second half need nothing newer, so the matrix pipe restarts at once, and the next
                 // stage's first fragments and the refill of the freed stage are issued one by one between
                 // them: a wave blocks while the memory pipeline accepts a load, so loads issued back to
                 // back stall the MFMAs behind them.  Past the last k-block the refills repeat it (never
-                // read): the loop body and the count of outstanding loads stay uniform.
-                constexpr int KS = BK / 16;           // sub-steps (one 16-deep MFMA layer each)
-                constexpr int NR = TM + TN;           // fragment reads per sub-step
-                // A stage's LPS loads are issued in two parts: LB of them between the MFMAs of the last
-                // sub-step of the k-step that frees the stage, the rest between the MFMAs of the following
-                // k-step's other sub-steps, so that loads leave at an even rate.
+                // read): the loop body and the count of outstanding loads stay uniform.  B fragments
+                // alternate between two register sets from one k-step to the next, so the loop takes
+                // k-steps in pairs (every range of k-steps here has an even length).
+                constexpr int KS = 2;                  // halves of a k-step
+                constexpr int AH = C::AM / 2;          // A blocks (MFMA groups of BNB) per half
+                constexpr int NR1 = AH + C::BNB;       // fragment reads issued during the second half
+                // A stage's LPS loads are issued in two parts: LB of them between the MFMAs of the second
+                // half of the k-step that frees the stage, the rest between the MFMAs of the following
+                // k-step's first half, so that loads leave at an even rate.
                 constexpr int LB = C::LPS / KS;
-                constexpr int G1 = (KS - 1) * TM;     // MFMA groups (of TN) before the last sub-step
+                constexpr int G1 = AH;                 // MFMA groups before the barrier
 #pragma unroll
                 for (int ps = 0; ps < C::NS; ++ps)
 #pragma unroll
                     for (int l = 0; l < (ps == C::NS - 1 ? LB : C::LPS); ++l) issue_one(ps, ka + ps < kb ? ka + ps : kb - 1, l);
                 wait_global_loads_le<(C::NS - 2) * C::LPS + LB>();
                 __syncthreads();
-                bf16x8 af[2][TM], bfr[2][TN];
-                auto read_frag = [&](int buf, int stage, int kk, int rr) {   // rr < TM: A block rr, else B block rr - TM
-                    if (rr < TM)
-                        af[buf][rr] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + (kk >> 1) * (BM * 4) + rr * 128 +
-                                             (((kk & 1) << 1) ^ pcxA)];
-                    else
-                        bfr[buf][rr - TM] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB +
-                                                   (kk >> 1) * (BN * 4) + (rr - TM) * 128 + (((kk & 1) << 1) ^ pcxB)];
+                bf16x8 af[2][AH], bfr[2][C::BNB];
+                auto read_a = [&](int h, int stage, int i) {   // A block h * AH + i of the stage
+                    af[h][i] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + (h * AH + i) * 64];
+                };
+                auto read_b = [&](int set, int stage, int j) {
+                    bfr[set][j] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB + j * 64];
                 };
 #pragma unroll
-                for (int rr = 0; rr < NR; ++rr) read_frag(0, 0, 0, rr);
+                for (int i = 0; i < AH; ++i) read_a(0, 0, i);
+#pragma unroll
+                for (int j = 0; j < C::BNB; ++j) read_b(0, 0, j);
                 int st = 0;
-                for (int kt = ka; kt < kb; ++kt) {
+                auto k_step = [&](int kt, auto set_tag) {
+                    constexpr int set = decltype(set_tag)::value;   // B register set of this k-step
                     const int nst = (st + 1 == C::NS) ? 0 : st + 1;
                     const int pst = (st == 0) ? C::NS - 1 : st - 1;
                     const int fill_kt = kt + C::NS < kb ? kt + C::NS : kb - 1;
                     const int pfill_kt = kt + C::NS - 1 < kb ? kt + C::NS - 1 : kb - 1;   // the stage freed one step ago
 #pragma unroll
-                    for (int kk = 0; kk < KS - 1; ++kk) {
+                    for (int i = 0; i < AH; ++i) read_a(1, st, i);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int rr = 0; rr < NR; ++rr) read_frag((kk + 1) & 1, st, kk + 1, rr);
+                    for (int i = 0; i < AH; ++i) {
+#pragma unroll
+                        for (int j = 0; j < C::BNB; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[0][i], bfr[set][j], acc[i][j], 0, 0, 0);
                         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-                            for (int j = 0; j < TN; ++j)
-                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-                            __builtin_amdgcn_sched_barrier(0);
-                            const int gi = kk * TM + i;
-#pragma unroll
-                            for (int l = LB + gi * (C::LPS - LB) / G1; l < LB + (gi + 1) * (C::LPS - LB) / G1; ++l)
-                                issue_one(pst, pfill_kt, l);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
+                        for (int l = LB + i * (C::LPS - LB) / G1; l < LB + (i + 1) * (C::LPS - LB) / G1; ++l)
+                            issue_one(pst, pfill_kt, l);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                     wait_global_loads_le<(C::NS - 2) * C::LPS>();   // own part of k-block kt+1 has landed
                     __syncthreads();                                // ... everyone's; and stage st is free
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int i = 0; i < TM; ++i) {
+                    for (int i = 0; i < AH; ++i) {
 #pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[(KS - 1) & 1][i], bfr[(KS - 1) & 1][j],
-                                                                               acc[i][j], 0, 0, 0);
-                        constexpr int RG = TM > 1 ? TM - 1 : 1;   // the reads go with the first TM-1 groups
+                        for (int j = 0; j < C::BNB; ++j)
+                            acc[AH + i][j] =
+                                __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][i], bfr[set][j], acc[AH + i][j], 0, 0, 0);
+                        constexpr int RG = AH > 1 ? AH - 1 : 1;   // the reads go with the first AH-1 groups
 #pragma unroll
-                        for (int rr = i * NR / RG; rr < (i + 1) * NR / RG && rr < NR && i < RG; ++rr) read_frag(0, nst, 0, rr);
+                        for (int rr = i * NR1 / RG; rr < (i + 1) * NR1 / RG && rr < NR1 && i < RG; ++rr) {
+                            if (rr < AH)
+                                read_a(0, nst, rr);
+                            else
+                                read_b(set ^ 1, nst, rr - AH);
+                        }
                         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int l = i * LB / TM; l < (i + 1) * LB / TM; ++l) issue_one(st, fill_kt, l);
+                        for (int l = i * LB / AH; l < (i + 1) * LB / AH; ++l) issue_one(st, fill_kt, l);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     st = nst;
+                };
+                for (int kt = ka; kt < kb; kt += 2) {
+                    k_step(kt, std::integral_constant<int, 0>{});
+                    k_step(kt + 1, std::integral_constant<int, 1>{});
                 }
                 wait_global_loads_le<0>();   // the refills past the last k-block
             }
@@ -417,13 +436,9 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                     f32x4 *dst = reinterpret_cast<f32x4 *>(p.partial) +
                                  ((size_t)blockIdx.x * p.sk_slots + seg) * (size_t)(BM * BN / 4);
 #pragma unroll
-                    for (int bi = 0; bi < TM; ++bi)
+                    for (int bi = 0; bi < C::AM; ++bi)
 #pragma unroll
-                        for (int bj = 0; bj < TN; ++bj)
-#pragma unroll
-                            for (int e4 = 0; e4 < 4; ++e4)
-                                dst[(((w * TM + bi) * TN + bj) * 4 + e4) * 64 + lane] =
-                                    f32x4{acc[bi][bj][4 * e4], acc[bi][bj][4 * e4 + 1], acc[bi][bj][4 * e4 + 2], acc[bi][bj][4 * e4 + 3]};
+                        for (int bj = 0; bj < C::BNB; ++bj) dst[((w * C::AM + bi) * C::BNB + bj) * 64 + lane] = acc[bi][bj];
                     continue;
                 }
                 keys_epilogue<C>(acc, p, slab, smt, n0, nq, w, wm, wn, lane);
@@ -435,16 +450,21 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 #pragma unroll 1
                 for (int wg = 0; wg < C::WN / C::WNS; ++wg) {
                     if (wn / C::WNS == wg) {
-                        const int col = n0 + wn * TN * 32 + bj * 32 + (lane & 31);
-                        const float nrm = p.norm[col];   // col < n_pad always
-                        const int sc = (wn % C::WNS) * 32 + (lane & 31);
+                        // the wave's 32 columns of this pass are two MFMA blocks; a lane holds column
+                        // (lane & 15) of each and rows 4 (lane >> 4) .. + 3 of every 16-row block
 #pragma unroll
-                        for (int bi = 0; bi < TM; ++bi) {
+                        for (int v2 = 0; v2 < 2; ++v2) {
+                            const int col = n0 + wn * TN * 32 + bj * 32 + v2 * 16 + (lane & 15);
+                            const float nrm = p.norm[col];   // col < n_pad always
+                            const int sc = (wn % C::WNS) * 32 + v2 * 16 + (lane & 15);
 #pragma unroll
-                            for (int e = 0; e < 16; ++e) {
-                                const int row = wm * TM * 32 + bi * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-                                const float key = __builtin_fmaf(-2.f, acc[bi][bj][e], nrm);
-                                slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = key;
+                            for (int bi = 0; bi < C::AM; ++bi) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) {
+                                    const int row = wm * TM * 32 + bi * 16 + (lane >> 4) * 4 + e;
+                                    const float key = __builtin_fmaf(-2.f, acc[bi][2 * bj + v2][e], nrm);
+                                    slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = key;
+                                }
                             }
                         }
                     }
@@ -542,26 +562,24 @@ __global__ __launch_bounds__(C::THREADS) void keys_fixup_kernel(DistKernelArgs p
     const int nk = p.d_pad / C::BK;
     const int64_t g0 = (int64_t)tile * nk, g1 = g0 + nk;
     const int w_first = (int)(g0 / p.sk_len), w_last = (int)((g1 - 1) / p.sk_len);
-    f32x16 acc[TM][TN];
+    f32x4 acc[C::AM][C::BNB];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < C::AM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < C::BNB; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
     for (int x = w_first; x <= w_last; ++x) {
         const int seg = tile - (int)(((int64_t)x * p.sk_len) / nk);   // tiles workgroup x touched before this one
         const f32x4 *src = reinterpret_cast<const f32x4 *>(p.partial) + ((size_t)x * p.sk_slots + seg) * (size_t)(BM * BN / 4);
 #pragma unroll
-        for (int bi = 0; bi < TM; ++bi)
+        for (int bi = 0; bi < C::AM; ++bi)
 #pragma unroll
-            for (int bj = 0; bj < TN; ++bj)
+            for (int bj = 0; bj < C::BNB; ++bj) {
+                const f32x4 v = src[((w * C::AM + bi) * C::BNB + bj) * 64 + lane];
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const f32x4 v = src[(((w * TM + bi) * TN + bj) * 4 + e4) * 64 + lane];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[bi][bj][4 * e4 + e] += v[e];
-                }
+                for (int e = 0; e < 4; ++e) acc[bi][bj][e] += v[e];
+            }
     }
     const int nq = p.count ? *p.count : p.b;
     keys_epilogue<C>(acc, p, slab, mt, nt * BN, nq, w, wm, wn, lane);
@@ -638,6 +656,7 @@ void plan_stream_k(DistPlan &pl, int num_cus, int64_t d_pad)
     if (fill < 0.9 && rounds <= 4 && nk >= 64 && total >= 16 * (int64_t)num_cus) {
         pl.sk_wgs = num_cus;
         pl.sk_len = (int)((total + num_cus - 1) / num_cus);
+        pl.sk_len += pl.sk_len & 1;   // the kernel takes k-steps in pairs (nk is even: d_pad is a multiple of 64)
         pl.sk_slots = (pl.sk_len - 1) / nk + 2;
     }
 }
@@ -666,6 +685,8 @@ static hipError_t launch_variant(const DistPlan &plan, const DistArgs &a, hipStr
     k.max_splits = plan.max_splits;
     k.num_cus = plan.num_cus;
     const int grid = a.count ? plan.grid_units : plan.m_tiles * plan.n_splits;
+    // the kernel takes k-steps (32 elements) in pairs
+    if (a.d_pad <= 0 || a.d_pad % 64 != 0 || (plan.sk_wgs > 0 && (plan.sk_len & 1))) return hipErrorInvalidValue;
     if constexpr (!C::KEYS) {
         if (!a.part || a.lists < (a.count ? plan.alloc_splits : plan.n_splits)) return hipErrorInvalidValue;
     }
