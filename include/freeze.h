@@ -275,7 +275,8 @@ int freeze_profile_read_calls(freeze_ctx *ctx, float *call_ms, int max_calls, in
 
 /*
  * Calibration microbenchmarks for benchmarks (they synchronise the device; default stream).
- * freeze_calibrate_mfma: back-to-back bf16 32x32x16 MFMAs from registers on every CU.
+ * freeze_calibrate_mfma: back-to-back bf16 16x16x32 MFMAs from registers on every CU, on
+ *   pseudo-random operands (the clock the chip holds under matrix work depends on the data).
  *   scratch        device buffer, 8-byte aligned, >= 2 MiB; contents overwritten.
  *   tflops         host out: sustained dense bf16 rate in TFLOP/s.
  *   shader_mhz     host out: shader clock held under that load, in MHz.

@@ -1,8 +1,11 @@
 // Calibration microbenchmarks (measurement aids, not part of the look-up): what this GPU
 // sustains on the two roofs the look-up kernels are priced against.
-//  - pure MFMA: every wave issues back-to-back, independent v_mfma_f32_32x32x16_bf16 from
-//    registers (no memory traffic at all); also reports the shader clock the chip holds
-//    under that load (shader-clock counter against the 100 MHz real-time counter);
+//  - pure MFMA: every wave issues back-to-back, independent v_mfma_f32_16x16x32_bf16 (the shape
+//    the distance kernel uses) from registers, no memory traffic at all, rotating through four
+//    operand pairs of pseudo-random bf16 values: the chip runs matrix work against its power
+//    limit, and the clock it holds depends on how much the operands toggle (constant operands
+//    read about 20 % higher).  Also reports that shader clock (shader-clock counter against the
+//    100 MHz real-time counter);
 //  - pure read: every byte of a buffer is read once with 16-byte loads (grid-stride).
 // Both synchronise the device: they are for benchmarks, not for the serving path.
 #include "../../include/freeze.h"
@@ -12,7 +15,24 @@
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+constexpr int kCalAcc = 32;   // independent accumulators per wave (128 registers, as in the distance kernel)
+
+// 8 bf16 values in [0.125, 1) with random sign and mantissa, from a hash of (thread, slot)
+__device__ inline bf16x8 random_operand(unsigned seed)
+{
+    u32x4 w;
+    for (int i = 0; i < 4; ++i) {
+        seed = seed * 1664525u + 1013904223u;
+        unsigned x = seed ^ (seed >> 15);
+        const unsigned lo = ((x >> 3) & 0x80ffu) | (0x3e00u + ((x >> 1) & 0x180u));
+        const unsigned hi = ((x >> 17) & 0x80ffu) | (0x3e00u + ((x >> 12) & 0x180u));
+        w[i] = lo | (hi << 16);
+    }
+    return __builtin_bit_cast(bf16x8, w);
+}
 
 __global__ __launch_bounds__(512) void mfma_peak_kernel(float *out, unsigned long long *clk, int iters)
 {
@@ -20,21 +40,22 @@ __global__ __launch_bounds__(512) void mfma_peak_kernel(float *out, unsigned lon
         clk[0] = clock64();
         clk[1] = wall_clock64();
     }
-    bf16x8 a, b;
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (__bf16)(0.001f * (float)(threadIdx.x + i));
-        b[i] = (__bf16)(0.002f * (float)(threadIdx.x ^ i));
+    bf16x8 a[4], b[4];
+    for (int i = 0; i < 4; ++i) {
+        a[i] = random_operand(threadIdx.x * 8u + i);
+        b[i] = random_operand(threadIdx.x * 8u + 4u + i);
     }
-    f32x16 acc[8];
-    for (int j = 0; j < 8; ++j)
-        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    f32x4 acc[kCalAcc];
+    for (int j = 0; j < kCalAcc; ++j)
+        for (int e = 0; e < 4; ++e) acc[j][e] = 0.f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+        for (int j = 0; j < kCalAcc; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j % 4], b[(j / 4) % 4], acc[j], 0, 0, 0);
     }
     float s = 0.f;
-    for (int j = 0; j < 8; ++j)
-        for (int e = 0; e < 16; ++e) s += acc[j][e];
+    for (int j = 0; j < kCalAcc; ++j)
+        for (int e = 0; e < 4; ++e) s += acc[j][e];
     out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         clk[2] = clock64();
@@ -70,7 +91,7 @@ int freeze_calibrate_mfma(void *scratch, size_t scratch_bytes, double *tflops, d
     if (scratch_bytes < need || (reinterpret_cast<uintptr_t>(scratch) % 8) != 0) return FREEZE_EWORKSPACE;
     unsigned long long *clk = static_cast<unsigned long long *>(scratch);
     float *out = reinterpret_cast<float *>(clk + 4);
-    const int iters = 20000;
+    const int iters = 5000;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return FREEZE_EHIP;
     hipLaunchKernelGGL(mfma_peak_kernel, dim3(cus), dim3(512), 0, nullptr, out, clk, 200);   // warm-up
@@ -86,7 +107,7 @@ int freeze_calibrate_mfma(void *scratch, size_t scratch_bytes, double *tflops, d
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rc != FREEZE_OK) return rc;
-    const double flops = (double)cus * 8.0 /*waves*/ * iters * 8.0 /*mfma*/ * 32768.0;
+    const double flops = (double)cus * 8.0 /*waves*/ * iters * (double)kCalAcc /*mfma*/ * 16384.0;
     *tflops = flops / (ms * 1e-3) / 1e12;
     *shader_mhz = (h[3] > h[1]) ? (double)(h[2] - h[0]) / ((double)(h[3] - h[1]) / 100.0) : 0.0;
     return FREEZE_OK;
