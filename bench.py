@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2_batched")
+    ap.add_argument("--cache-copies", type=int, default=0,
+                    help="identical copies of a single-layer cache the steps alternate between (0 = 2 when the cache is at most 2 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (profiling runs)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="queries in the oracle sample (0 = per workload)")
     ap.add_argument("--calibrate", action="store_true",
@@ -84,10 +86,18 @@ def main() -> int:
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
-    fc = binding.FreezeCache(nl, dev)
+    # A single-layer workload whose cache is small next to HBM is built twice and the steps
+    # alternate between the copies, so that no step finds its cache in the memory-side cache
+    # because the step before left it there.
+    cache_gib = data.layers[0].spec.n * data.layers[0].spec.d * 2 / 2**30
+    copies = args.cache_copies if args.cache_copies > 0 else (2 if (not cascade and cache_gib <= 2.0) else 1)
+    if cascade:
+        copies = 1
+    fc = binding.FreezeCache(nl if cascade else copies, dev)
     t0 = time.time()
     for l, L in enumerate(data.layers):
-        fc.build_layer(l, L.entries, L.labels, L.spec.num_classes)
+        for c in range(copies):
+            fc.build_layer(l + c, L.entries, L.labels, L.spec.num_classes)
     torch.cuda.synchronize()
     build_s = time.time() - t0
 
@@ -103,9 +113,11 @@ def main() -> int:
             fc.lookup_cascade(list(range(nl)), data.queries, k, list(wl.vote_thresholds), r, out=out)
     else:
         out = fc.alloc_outputs(b, k)
+        turn = [0]
 
         def step():
-            fc.lookup(0, data.queries[0], k, wl.vote_thresholds[0], r, out=out)
+            fc.lookup(turn[0] % copies, data.queries[0], k, wl.vote_thresholds[0], r, out=out)
+            turn[0] += 1
 
     for _ in range(args.warmup):
         step()
@@ -163,7 +175,7 @@ def main() -> int:
                                                      for s in wl.layers)
                           + f", batch {b}, k={k}, vote_thresholds={list(wl.vote_thresholds)}, "
                             f"rescore_r={r if r else 'default'}",
-              "event_ms_per_step": round(ev_ms_per_step, 4), "cache_build_s": round(build_s, 3),
+              "event_ms_per_step": round(ev_ms_per_step, 4), "cache_build_s": round(build_s, 3), "cache_copies": copies,
               "input_gen_s": round(gen_s, 2)}
     if cascade:
         hits = out["hits_per_layer"].cpu().numpy().astype(np.int64)
