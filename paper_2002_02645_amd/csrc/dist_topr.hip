@@ -17,10 +17,13 @@
 // id modulo 8) hold neighbouring units, which share query tiles and walk the same
 // cache tiles, so that operand re-reads are served by that XCD's L2.
 //
-// Main loop: 8 waves (2 x 4), each owning a (TM*32) x 64 block of the tile as
-// 16x16x32 bf16 MFMA accumulators (this shape sustains about a tenth more than 32x32x16 on
-// random operands: the chip runs matrix work against its power limit, and the shader clock it
-// holds depends on the instruction shape and on the data).  Both operands are stored in memory in a tiled,
+// Main loop: the tile is held as 16x16x32 bf16 MFMA accumulators (this shape sustains about a
+// tenth more than 32x32x16 on random operands: the chip runs matrix work against its power
+// limit, and the shader clock it holds depends on the instruction shape and on the data).
+// Two wave layouts: 4 waves (2 x 2), one per SIMD, each owning 128 x 128 in 256 AGPRs (the
+// R <= 16 variant: a third fewer fragment reads per MFMA; the MFMAs are issued through inline
+// asm so that the accumulators stay in AGPRs and the operands in VGPRs), and 8 waves (2 x 4),
+// two per SIMD, each owning (TM*32) x 64 in VGPRs (the other variants).  Both operands are stored in memory in a tiled,
 // pre-swizzled layout ([row tile][k-block][row][32 elements], see tiled_chunk_offset)
 // whose per-k-step blocks are contiguous and are exactly the LDS image, so a stage is
 // filled by a linear copy with LDS-direct 16-byte loads (no VGPR staging, fully
@@ -338,93 +341,163 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
             {
-                // Software-pipelined loop.  A k-step is one MFMA layer (32 deep), taken in two halves:
-                // the wave's upper A blocks against all its B blocks, then the lower ones.  Invariant at
-                // the top of k-step kt: its first A half and its B blocks are in (or on their way to)
-                // registers; k-blocks kt+1 .. kt+NS-1 are in flight or landed in the other stages.  The
-                // second A half is read during the first half's MFMAs; after that every read of the
-                // current stage has been issued, so the step's only barrier goes there: it publishes the
-                // next stage (each wave waited for its own part) and frees the current one.  The MFMAs of
-                // the second half need nothing newer, so the matrix pipe restarts at once, and the next
-                // stage's first fragments and the refill of the freed stage are issued one by one between
-                // them: a wave blocks while the memory pipeline accepts a load, so loads issued back to
-                // back stall the MFMAs behind them.  Past the last k-block the refills repeat it (never
-                // read): the loop body and the count of outstanding loads stay uniform.  B fragments
-                // alternate between two register sets from one k-step to the next, so the loop takes
-                // k-steps in pairs (every range of k-steps here has an even length).
-                constexpr int KS = 2;                  // halves of a k-step
-                constexpr int AH = C::AM / 2;          // A blocks (MFMA groups of BNB) per half
-                constexpr int NR1 = AH + C::BNB;       // fragment reads issued during the second half
-                // A stage's LPS loads are issued in two parts: LB of them between the MFMAs of the second
-                // half of the k-step that frees the stage, the rest between the MFMAs of the following
-                // k-step's first half, so that loads leave at an even rate.
-                constexpr int LB = C::LPS / KS;
-                constexpr int G1 = AH;                 // MFMA groups before the barrier
+                if constexpr (C::WN == 2) {
+                    // ---- one wave per SIMD: 128 x 128 per wave, accumulators in AGPRs ----
+                    // All NS stages are in use: at the top of k-step kt its fragments are in (or on their
+                    // way to) register buffer kt & 1, k-block kt+1 has landed, kt+2 .. kt+NS-1 are in
+                    // flight.  The step's barrier (after the wave's own loads of kt+1 and its own reads of
+                    // kt are done) publishes kt+1 and frees the stage of kt, which is refilled with kt+NS
+                    // during the step.  With a single wave on the SIMD nothing else covers an issue stall,
+                    // so every memory instruction goes alone into the shadow of an MFMA (the pipe is busy
+                    // 16 cycles per MFMA, issuing one takes 4), and the next step's fragment reads all
+                    // leave during the first 48 MFMAs, so that the wait for them at the next top is free.
+                    // The compiler does not know these MFMAs: the waits that order them against the LDS
+                    // reads are the explicit ones here, and the no-ops after the loop cover the distance
+                    // the hardware wants between the last MFMA and the first read of an accumulator.
+                    constexpr int AMB = C::AM, BB = C::BNB;   // 8 x 8 blocks
+                    static_assert(AMB == 8 && BB == 8, "4-wave loop is written for 128 x 128 per wave");
 #pragma unroll
-                for (int ps = 0; ps < C::NS; ++ps)
+                    for (int ps = 0; ps < C::NS; ++ps)
 #pragma unroll
-                    for (int l = 0; l < (ps == C::NS - 1 ? LB : C::LPS); ++l) issue_one(ps, ka + ps < kb ? ka + ps : kb - 1, l);
-                wait_global_loads_le<(C::NS - 2) * C::LPS + LB>();
-                __syncthreads();
-                bf16x8 af[2][AH], bfr[2][C::BNB];
-                auto read_a = [&](int h, int stage, int i) {   // A block h * AH + i of the stage
-                    af[h][i] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + (h * AH + i) * 64];
-                };
-                auto read_b = [&](int set, int stage, int j) {
-                    bfr[set][j] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB + j * 64];
-                };
+                        for (int l = 0; l < C::LPS; ++l) issue_one(ps, ka + ps < kb ? ka + ps : kb - 1, l);
+                    wait_global_loads_le<(C::NS - 1) * C::LPS>();
+                    __syncthreads();
+                    bf16x8 af[2][AMB], bfr[2][BB];
+                    auto read_a = [&](int buf, int stage, int i) { af[buf][i] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + i * 64]; };
+                    auto read_b = [&](int buf, int stage, int j) { bfr[buf][j] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB + j * 64]; };
 #pragma unroll
-                for (int i = 0; i < AH; ++i) read_a(0, 0, i);
+                    for (int j = 0; j < BB; ++j) read_b(0, 0, j);
 #pragma unroll
-                for (int j = 0; j < C::BNB; ++j) read_b(0, 0, j);
-                int st = 0;
-                auto k_step = [&](int kt, auto set_tag) {
-                    constexpr int set = decltype(set_tag)::value;   // B register set of this k-step
-                    const int nst = (st + 1 == C::NS) ? 0 : st + 1;
-                    const int pst = (st == 0) ? C::NS - 1 : st - 1;
-                    const int fill_kt = kt + C::NS < kb ? kt + C::NS : kb - 1;
-                    const int pfill_kt = kt + C::NS - 1 < kb ? kt + C::NS - 1 : kb - 1;   // the stage freed one step ago
-#pragma unroll
-                    for (int i = 0; i < AH; ++i) read_a(1, st, i);
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int i = 0; i < AH; ++i) {
-#pragma unroll
-                        for (int j = 0; j < C::BNB; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[0][i], bfr[set][j], acc[i][j], 0, 0, 0);
+                    for (int i = 0; i < AMB; ++i) read_a(0, 0, i);
+                    int st = 0;
+                    auto k_step = [&](int kt, auto buf_tag) {
+                        constexpr int buf = decltype(buf_tag)::value;
+                        const int nst = (st + 1 == C::NS) ? 0 : st + 1;
+                        const int fill_kt = kt + C::NS < kb ? kt + C::NS : kb - 1;
+                        // own part of k-block kt+1 has landed; own reads of k-block kt are done
+                        wait_global_loads_le<(C::NS - 2) * C::LPS>();
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                        __syncthreads();   // k-block kt+1 is everyone's; stage st is free
                         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int l = LB + i * (C::LPS - LB) / G1; l < LB + (i + 1) * (C::LPS - LB) / G1; ++l)
-                            issue_one(pst, pfill_kt, l);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    wait_global_loads_le<(C::NS - 2) * C::LPS>();   // own part of k-block kt+1 has landed
-                    __syncthreads();                                // ... everyone's; and stage st is free
-                    __builtin_amdgcn_sched_barrier(0);
+                        for (int i = 0; i < AMB; ++i) {
 #pragma unroll
-                    for (int i = 0; i < AH; ++i) {
-#pragma unroll
-                        for (int j = 0; j < C::BNB; ++j)
-                            acc[AH + i][j] =
-                                __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][i], bfr[set][j], acc[AH + i][j], 0, 0, 0);
-                        constexpr int RG = AH > 1 ? AH - 1 : 1;   // the reads go with the first AH-1 groups
-#pragma unroll
-                        for (int rr = i * NR1 / RG; rr < (i + 1) * NR1 / RG && rr < NR1 && i < RG; ++rr) {
-                            if (rr < AH)
-                                read_a(0, nst, rr);
-                            else
-                                read_b(set ^ 1, nst, rr - AH);
+                            for (int j = 0; j < BB; ++j) {
+                                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(af[buf][i]), "v"(bfr[buf][j]));
+                                __builtin_amdgcn_sched_barrier(0);
+                                // one memory instruction at a time in the shadow of an MFMA: the next k-block's
+                                // fragments (B blocks, then A blocks) after every third MFMA of the first 48, a
+                                // refill load after every eighth
+                                constexpr int RD_EVERY = 3;
+                                const int slot = i * BB + j;
+                                if (slot % RD_EVERY == 1 && slot / RD_EVERY < AMB + BB) {
+                                    const int rr = slot / RD_EVERY;
+                                    if (rr < BB) read_b(buf ^ 1, nst, rr);
+                                    else read_a(buf ^ 1, nst, rr - BB);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                                if (slot % 8 == 6) {
+                                    issue_one(st, fill_kt, slot / 8);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                            }
                         }
+                        st = nst;
+                    };
+                    for (int kt = ka; kt < kb; kt += 2) {
+                        k_step(kt, std::integral_constant<int, 0>{});
+                        k_step(kt + 1, std::integral_constant<int, 1>{});
+                    }
+                    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");   // MFMA results before the accumulators are read
+                } else {
+                    // Software-pipelined loop.  A k-step is one MFMA layer (32 deep), taken in two halves:
+                    // the wave's upper A blocks against all its B blocks, then the lower ones.  Invariant at
+                    // the top of k-step kt: its first A half and its B blocks are in (or on their way to)
+                    // registers; k-blocks kt+1 .. kt+NS-1 are in flight or landed in the other stages.  The
+                    // second A half is read during the first half's MFMAs; after that every read of the
+                    // current stage has been issued, so the step's only barrier goes there: it publishes the
+                    // next stage (each wave waited for its own part) and frees the current one.  The MFMAs of
+                    // the second half need nothing newer, so the matrix pipe restarts at once, and the next
+                    // stage's first fragments and the refill of the freed stage are issued one by one between
+                    // them: a wave blocks while the memory pipeline accepts a load, so loads issued back to
+                    // back stall the MFMAs behind them.  Past the last k-block the refills repeat it (never
+                    // read): the loop body and the count of outstanding loads stay uniform.  B fragments
+                    // alternate between two register sets from one k-step to the next, so the loop takes
+                    // k-steps in pairs (every range of k-steps here has an even length).
+                    constexpr int KS = 2;                  // halves of a k-step
+                    constexpr int AH = C::AM / 2;          // A blocks (MFMA groups of BNB) per half
+                    constexpr int NR1 = AH + C::BNB;       // fragment reads issued during the second half
+                    // A stage's LPS loads are issued in two parts: LB of them between the MFMAs of the second
+                    // half of the k-step that frees the stage, the rest between the MFMAs of the following
+                    // k-step's first half, so that loads leave at an even rate.
+                    constexpr int LB = C::LPS / KS;
+                    constexpr int G1 = AH;                 // MFMA groups before the barrier
+#pragma unroll
+                    for (int ps = 0; ps < C::NS; ++ps)
+#pragma unroll
+                        for (int l = 0; l < (ps == C::NS - 1 ? LB : C::LPS); ++l) issue_one(ps, ka + ps < kb ? ka + ps : kb - 1, l);
+                    wait_global_loads_le<(C::NS - 2) * C::LPS + LB>();
+                    __syncthreads();
+                    bf16x8 af[2][AH], bfr[2][C::BNB];
+                    auto read_a = [&](int h, int stage, int i) {   // A block h * AH + i of the stage
+                        af[h][i] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + (h * AH + i) * 64];
+                    };
+                    auto read_b = [&](int set, int stage, int j) {
+                        bfr[set][j] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB + j * 64];
+                    };
+#pragma unroll
+                    for (int i = 0; i < AH; ++i) read_a(0, 0, i);
+#pragma unroll
+                    for (int j = 0; j < C::BNB; ++j) read_b(0, 0, j);
+                    int st = 0;
+                    auto k_step = [&](int kt, auto set_tag) {
+                        constexpr int set = decltype(set_tag)::value;   // B register set of this k-step
+                        const int nst = (st + 1 == C::NS) ? 0 : st + 1;
+                        const int pst = (st == 0) ? C::NS - 1 : st - 1;
+                        const int fill_kt = kt + C::NS < kb ? kt + C::NS : kb - 1;
+                        const int pfill_kt = kt + C::NS - 1 < kb ? kt + C::NS - 1 : kb - 1;   // the stage freed one step ago
+#pragma unroll
+                        for (int i = 0; i < AH; ++i) read_a(1, st, i);
                         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int l = i * LB / AH; l < (i + 1) * LB / AH; ++l) issue_one(st, fill_kt, l);
+                        for (int i = 0; i < AH; ++i) {
+#pragma unroll
+                            for (int j = 0; j < C::BNB; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[0][i], bfr[set][j], acc[i][j], 0, 0, 0);
+                            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                            for (int l = LB + i * (C::LPS - LB) / G1; l < LB + (i + 1) * (C::LPS - LB) / G1; ++l)
+                                issue_one(pst, pfill_kt, l);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        wait_global_loads_le<(C::NS - 2) * C::LPS>();   // own part of k-block kt+1 has landed
+                        __syncthreads();                                // ... everyone's; and stage st is free
                         __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int i = 0; i < AH; ++i) {
+#pragma unroll
+                            for (int j = 0; j < C::BNB; ++j)
+                                acc[AH + i][j] =
+                                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][i], bfr[set][j], acc[AH + i][j], 0, 0, 0);
+                            constexpr int RG = AH > 1 ? AH - 1 : 1;   // the reads go with the first AH-1 groups
+#pragma unroll
+                            for (int rr = i * NR1 / RG; rr < (i + 1) * NR1 / RG && rr < NR1 && i < RG; ++rr) {
+                                if (rr < AH)
+                                    read_a(0, nst, rr);
+                                else
+                                    read_b(set ^ 1, nst, rr - AH);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                            for (int l = i * LB / AH; l < (i + 1) * LB / AH; ++l) issue_one(st, fill_kt, l);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        st = nst;
+                    };
+                    for (int kt = ka; kt < kb; kt += 2) {
+                        k_step(kt, std::integral_constant<int, 0>{});
+                        k_step(kt + 1, std::integral_constant<int, 1>{});
                     }
-                    st = nst;
-                };
-                for (int kt = ka; kt < kb; kt += 2) {
-                    k_step(kt, std::integral_constant<int, 0>{});
-                    k_step(kt + 1, std::integral_constant<int, 1>{});
                 }
                 wait_global_loads_le<0>();   // the refills past the last k-block
             }
@@ -726,7 +799,7 @@ hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t
     if (plan.r < 1 || plan.r > kMaxRescore || a.d_pad % kPadD != 0) return hipErrorInvalidValue;
     if (plan.variant == 3 && (!a.keys || (!a.bmin && !a.projection))) return hipErrorInvalidValue;
     switch (plan.variant) {
-    case 0: return launch_variant<DistCfg<256, 32, 16, 4>>(plan, a, s);
+    case 0: return launch_variant<DistCfg<256, 32, 16, 4, 2>>(plan, a, s);
     case 1: return launch_variant<DistCfg<256, 32, 32, 3>>(plan, a, s);
     case 2: return launch_variant<DistCfg<128, 32, 64, 4>>(plan, a, s);
     default: return launch_variant<DistCfg<256, 32, 0, 5>>(plan, a, s);
