@@ -309,6 +309,11 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         const int tile0 = (int)(g_begin / nk);
         const int nseg = g_begin < g_end ? (int)((g_end - 1) / nk) - tile0 + 1 : 0;
         const bool head_first = stream_k && nseg >= 2 && g_end < (int64_t)(tile0 + nseg) * nk;
+        // 4-wave fused variant: the first stages of a part's next tile are requested before the
+        // epilogue of the current one (whose slab leaves the upper stages alone) and land during it
+        constexpr int PF = (!C::KEYS && C::WN == 2) ? (C::OP_BYTES - BM * C::SLABW * 4) / C::STAGE_BYTES : 0;
+        static_assert(PF >= 0 && PF < C::NS, "prefetched stages lie above the slab");
+        bool prefetched = false;
         for (int it = 0; it < nseg; ++it) {
             const int seg = head_first ? (it == 0 ? nseg - 1 : it - 1) : it;
             const int tile = tile0 + seg;                     // under stream-K: query tile * n_tiles + cache tile
@@ -356,20 +361,26 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                     // the hardware wants between the last MFMA and the first read of an accumulator.
                     constexpr int AMB = C::AM, BB = C::BNB;   // 8 x 8 blocks
                     static_assert(AMB == 8 && BB == 8, "4-wave loop is written for 128 x 128 per wave");
+                    // k-block ka + ps goes to stage (s0 + ps) % NS; a prefetched tile starts in the first
+                    // stage above the slab and has its first PF stages on their way already
+                    const int s0 = prefetched ? C::NS - PF : 0;
 #pragma unroll
-                    for (int ps = 0; ps < C::NS; ++ps)
+                    for (int ps = 0; ps < C::NS; ++ps) {
+                        if (ps < PF && prefetched) continue;
+                        const int stg = s0 + ps < C::NS ? s0 + ps : s0 + ps - C::NS;
 #pragma unroll
-                        for (int l = 0; l < C::LPS; ++l) issue_one(ps, ka + ps < kb ? ka + ps : kb - 1, l);
+                        for (int l = 0; l < C::LPS; ++l) issue_one(stg, ka + ps < kb ? ka + ps : kb - 1, l);
+                    }
                     wait_global_loads_le<(C::NS - 1) * C::LPS>();
                     __syncthreads();
                     bf16x8 af[2][AMB], bfr[2][BB];
                     auto read_a = [&](int buf, int stage, int i) { af[buf][i] = smem16[stage * (C::STAGE_BYTES / 16) + rdA + i * 64]; };
                     auto read_b = [&](int buf, int stage, int j) { bfr[buf][j] = smem16[stage * (C::STAGE_BYTES / 16) + C::A_BYTES / 16 + rdB + j * 64]; };
 #pragma unroll
-                    for (int j = 0; j < BB; ++j) read_b(0, 0, j);
+                    for (int j = 0; j < BB; ++j) read_b(0, s0, j);
 #pragma unroll
-                    for (int i = 0; i < AMB; ++i) read_a(0, 0, i);
-                    int st = 0;
+                    for (int i = 0; i < AMB; ++i) read_a(0, s0, i);
+                    int st = s0;
                     auto k_step = [&](int kt, auto buf_tag) {
                         constexpr int buf = decltype(buf_tag)::value;
                         const int nst = (st + 1 == C::NS) ? 0 : st + 1;
@@ -518,6 +529,38 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                 continue;
             }
             // ---- epilogue: fold this tile into the per-row top-R lists ----
+            // The norms of the wave's columns are fetched first: nothing else in the epilogue loads from
+            // memory, so the prefetch below is never part of a wait.
+            // (the lane number is made opaque here: addresses derived from it are then recomputed per tile
+            // instead of being kept, and spilled, across the main loop)
+            int elane = lane;
+            asm volatile("" : "+v"(elane));
+            float nrm_r[C::BNB];
+#pragma unroll
+            for (int cb = 0; cb < C::BNB; ++cb) nrm_r[cb] = p.norm[n0 + wn * TN * 32 + cb * 16 + (elane & 15)];   // < n_pad always
+            if constexpr (PF > 0) {
+                prefetched = false;
+                // the norms are in registers by here (the compiler places its waits for them in front of
+                // this) and cannot be fetched again later
+#pragma unroll
+                for (int cb = 0; cb < C::BNB; ++cb) asm volatile("" : "+v"(nrm_r[cb]));
+                if (it + 1 < nseg) {   // uniform; fused variants walk whole tiles in order: the next one is nt + 1
+                    const uint64_t gBn = uniform_u64((uint64_t)(uintptr_t)p.c_bf + (size_t)(nt + 1) * BN * tile_row_bytes);
+#pragma unroll
+                    for (int ps = 0; ps < PF; ++ps)
+#pragma unroll
+                        for (int l = 0; l < C::LPS; ++l) {
+                            const uint32_t sbase = smem_base + (C::NS - PF + ps) * C::STAGE_BYTES + w * 1024;
+                            if (l < C::NI_A)
+                                load16_global_to_lds(gA + (size_t)ps * C::A_BYTES + l * (C::NWAVES * 1024), lane_off,
+                                                     sbase + l * (C::NWAVES * 1024));
+                            else
+                                load16_global_to_lds(gBn + (size_t)ps * (BN * BK * 2) + (l - C::NI_A) * (C::NWAVES * 1024), lane_off,
+                                                     sbase + C::A_BYTES + (l - C::NI_A) * (C::NWAVES * 1024));
+                        }
+                    prefetched = true;
+                }
+            }
 #pragma unroll
             for (int bj = 0; bj < TN; ++bj) {
 #pragma unroll 1
@@ -527,14 +570,13 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                         // (lane & 15) of each and rows 4 (lane >> 4) .. + 3 of every 16-row block
 #pragma unroll
                         for (int v2 = 0; v2 < 2; ++v2) {
-                            const int col = n0 + wn * TN * 32 + bj * 32 + v2 * 16 + (lane & 15);
-                            const float nrm = p.norm[col];   // col < n_pad always
-                            const int sc = (wn % C::WNS) * 32 + v2 * 16 + (lane & 15);
+                            const float nrm = nrm_r[2 * bj + v2];
+                            const int sc = (wn % C::WNS) * 32 + v2 * 16 + (elane & 15);
 #pragma unroll
                             for (int bi = 0; bi < C::AM; ++bi) {
 #pragma unroll
                                 for (int e = 0; e < 4; ++e) {
-                                    const int row = wm * TM * 32 + bi * 16 + (lane >> 4) * 4 + e;
+                                    const int row = wm * TM * 32 + bi * 16 + (elane >> 4) * 4 + e;
                                     const float key = __builtin_fmaf(-2.f, acc[bi][2 * bj + v2][e], nrm);
                                     slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = key;
                                 }
