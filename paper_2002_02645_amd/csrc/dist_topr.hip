@@ -133,7 +133,6 @@ __device__ __forceinline__ void keys_epilogue(f32x4 (&acc)[C::AM][C::BNB], const
                                               int n0, int nq, int w, int wm, int wn, int lane)
 {
     constexpr int BM = C::BM, TM = C::TM, TN = C::TN;
-    const int g = lane >> 5;
     const float scale = p.projection ? 1.f : -2.f;
     static_assert(!C::KEYS || C::WNS == C::WN, "keys-out epilogue: one slab pass covers all wave columns");
 #pragma unroll
@@ -157,15 +156,16 @@ __device__ __forceinline__ void keys_epilogue(f32x4 (&acc)[C::AM][C::BNB], const
             }
         }
         __syncthreads();
-        // half-wave h of wave w copies row it*2*NWAVES + 2w + h: 32 lanes x 4 keys = the slab's 128 columns
-        const int l32 = lane & 31;
-        const int seg = l32 >> 3;                                   // wave column the 4 keys came from
-        const int gcol = n0 + seg * TN * 32 + bj * 32 + (l32 & 7) * 4;   // entry index of the first key
+        // a row of the slab is LPR lanes x 4 keys; a wave copies 64 / LPR rows per round
+        constexpr int LPR = C::SLABW / 4, RPW = 64 / LPR;
+        const int lr = lane % LPR;
+        const int seg = lr >> 3;                                   // wave column the 4 keys came from
+        const int gcol = n0 + seg * TN * 32 + bj * 32 + (lr & 7) * 4;   // entry index of the first key
 #pragma unroll 2
-        for (int it = 0; it < BM / (2 * C::NWAVES); ++it) {
-            const int row = it * 2 * C::NWAVES + w * 2 + g;
+        for (int it = 0; it < BM / (RPW * C::NWAVES); ++it) {
+            const int row = (it * C::NWAVES + w) * RPW + lane / LPR;
             const int grow = mt * BM + row;
-            const f32x4 v = reinterpret_cast<const f32x4 *>(slab + row * C::SLABW)[(l32 ^ row) & (C::SLABW / 4 - 1)];
+            const f32x4 v = reinterpret_cast<const f32x4 *>(slab + row * C::SLABW)[(lr ^ row) & (LPR - 1)];
             const bool live = grow < nq;
             if (live) *reinterpret_cast<f32x4 *>(p.keys + (size_t)grow * p.n_pad + gcol) = v;
             // minimum (key, index) pair of the 32-entry block: 4 own keys, then the 8 lanes of the block
@@ -182,7 +182,7 @@ __device__ __forceinline__ void keys_epilogue(f32x4 (&acc)[C::AM][C::BNB], const
                 const uint64_t o = ((uint64_t)hi << 32) | lo;
                 mn = o < mn ? o : mn;
             }
-            if (live && (l32 & 7) == 0 && !p.projection) p.bmin[(size_t)grow * (p.n_pad / 32) + (gcol >> 5)] = mn;
+            if (live && (lr & 7) == 0 && !p.projection) p.bmin[(size_t)grow * (p.n_pad / 32) + (gcol >> 5)] = mn;
         }
         __syncthreads();
     }
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 template <class C>
 __global__ __launch_bounds__(C::THREADS) void keys_fixup_kernel(DistKernelArgs p)
 {
-    constexpr int BM = C::BM, BN = C::BN, TM = C::TM, TN = C::TN;
+    constexpr int BM = C::BM, BN = C::BN;
     __shared__ __attribute__((aligned(16))) unsigned char smem[BM * C::SLABW * 4];
     float *slab = reinterpret_cast<float *>(smem);
     const int tid = threadIdx.x, lane = tid & 63;
