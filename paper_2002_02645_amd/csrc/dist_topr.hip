@@ -48,6 +48,7 @@ namespace fz {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
 // LDS-direct 16-byte load: lane i reads 16 bytes at sbase + voff (scalar 64-bit base, 32-bit
@@ -193,7 +194,11 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, TM = C::TM, TN = C::TN;
     __shared__ __attribute__((aligned(16))) unsigned char smem[C::LDS_BYTES];
-    uint64_t *top = reinterpret_cast<uint64_t *>(smem + C::OP_BYTES);   // [RMAX][BM]
+    // Per-row candidate lists: keys (ordered bits) in chunks of four slots, [RMAX / 4][BM][4], so that
+    // a row's thread reads its whole list with RMAX / 4 conflict-free 16-byte reads; entry indices [RMAX][BM].
+    uint32_t *top_key = reinterpret_cast<uint32_t *>(smem + C::OP_BYTES);
+    uint32_t *top_idx = top_key + C::RMAX * BM;
+    auto key_slot = [&](int i, int t) { return ((i >> 2) * BM + t) * 4 + (i & 3); };
     float *slab = reinterpret_cast<float *>(smem);                      // [BM][SLABW], aliases operands
     const bf16x8 *smem16 = reinterpret_cast<const bf16x8 *>(smem);
 
@@ -270,13 +275,18 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         first_part = false;
 
         // per-row selection state lives with thread t (< BM)
-        uint64_t curmax = kSentinel;
+        // (kmax, imax) = the list's largest entry under the order (key, index), held in slot maxpos;
+        // slots past r hold the smallest key and never count
+        uint32_t kmax = 0xffffffffu, imax = 0xffffffffu;
         int maxpos = 0;
         float tau = __builtin_inff();
         if constexpr (!C::KEYS) {
             if (tid < BM) {
 #pragma unroll
-                for (int i = 0; i < C::RMAX; ++i) top[i * BM + tid] = kSentinel;
+                for (int i = 0; i < C::RMAX; ++i) {
+                    top_key[key_slot(i, tid)] = i < p.r ? 0xffffffffu : 0u;
+                    top_idx[i * BM + tid] = 0xffffffffu;
+                }
             }
         }
 
@@ -627,18 +637,40 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                                 mk &= mk - 1;
                                 const float key = slab[t * C::SLABW + ((((sc >> 2) ^ t) & (NG - 1)) << 2) + (sc & 3)];
                                 const int tilecol = (wg * C::WNS + sc / 32) * TN * 32 + bj * 32 + (sc & 31);
-                                const uint64_t ent = ((uint64_t)ordered_bits(key) << 32) | (uint32_t)(n0 + tilecol);
-                                if (ent < curmax) {
-                                    top[maxpos * BM + t] = ent;
-                                    curmax = 0;
+                                const uint32_t kb = ordered_bits(key), col = (uint32_t)(n0 + tilecol);
+                                if (kb < kmax || (kb == kmax && col < imax)) {
+                                    // replace the largest entry, then find the new largest: the largest key, and
+                                    // among equal keys (rare) the largest index
+                                    top_key[key_slot(maxpos, t)] = kb;
+                                    top_idx[maxpos * BM + t] = col;
+                                    u32x4 k4[C::RMAX > 0 ? C::RMAX / 4 : 1];   // (the keys-out variant never gets here)
+#pragma unroll
+                                    for (int j = 0; j < C::RMAX / 4; ++j)
+                                        k4[j] = *reinterpret_cast<const u32x4 *>(top_key + (j * BM + t) * 4);
+                                    uint32_t km = 0;
+#pragma unroll
+                                    for (int i = 0; i < C::RMAX; ++i) km = k4[i >> 2][i & 3] > km ? k4[i >> 2][i & 3] : km;
+                                    int pos = 0, same = 0;
 #pragma unroll
                                     for (int i = 0; i < C::RMAX; ++i) {
-                                        if (i < r) {
-                                            const uint64_t u = top[i * BM + t];
-                                            if (u >= curmax) { curmax = u; maxpos = i; }
+                                        const bool eq = k4[i >> 2][i & 3] == km;
+                                        pos = eq ? i : pos;
+                                        same += eq;
+                                    }
+                                    uint32_t im = top_idx[pos * BM + t];
+                                    if (same > 1) {
+#pragma unroll 1
+                                        for (int i = 0; i < r; ++i) {
+                                            if (top_key[key_slot(i, t)] == km) {
+                                                const uint32_t u = top_idx[i * BM + t];
+                                                if (u >= im) { im = u; pos = i; }
+                                            }
                                         }
                                     }
-                                    tau = (curmax == kSentinel) ? __builtin_inff() : from_ordered_bits((uint32_t)(curmax >> 32));
+                                    kmax = km;
+                                    imax = im;
+                                    maxpos = pos;
+                                    tau = (km == 0xffffffffu) ? __builtin_inff() : from_ordered_bits(km);
                                 }
                             }
                         }
@@ -653,7 +685,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
 #pragma unroll
             for (int i = 0; i < C::RMAX; ++i)
                 if (i < r) {
-                    dst[i] = top[i * BM + tid];
+                    dst[i] = ((uint64_t)top_key[key_slot(i, tid)] << 32) | top_idx[i * BM + tid];
                     if (clear_next_slot) dst[r + i] = kSentinel;
                 }
         }
