@@ -145,14 +145,21 @@ __device__ __forceinline__ void keys_epilogue(f32x4 (&acc)[C::AM][C::BNB], const
             const int col = n0 + wn * TN * 32 + bj * 32 + v2 * 16 + (lane & 15);
             const float nrm = p.norm[col];   // col < n_pad always
             const int sc = wn * 32 + v2 * 16 + (lane & 15);
+            // the column swizzle depends on the row modulo NGS = SLABW / 4 only, so the 16-row blocks one
+            // period apart share an address up to a constant (an immediate offset)
+            constexpr int NGS = C::SLABW / 4, RP = NGS > 16 ? NGS / 16 : 1;
 #pragma unroll
-            for (int bi = 0; bi < C::AM; ++bi) {
+            for (int e = 0; e < 4; ++e) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int row = wm * TM * 32 + bi * 16 + (lane >> 4) * 4 + e;
-                    float v = __builtin_fmaf(scale, acc[bi][2 * bj + v2][e], nrm);
-                    if (p.relu) v = __builtin_fmaxf(v, 0.f);
-                    slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = v;
+                for (int par = 0; par < RP; ++par) {
+                    const int row0 = wm * TM * 32 + par * 16 + (lane >> 4) * 4 + e;
+                    float *dst = slab + row0 * C::SLABW + ((((sc >> 2) ^ row0) & (NGS - 1)) << 2) + (sc & 3);
+#pragma unroll
+                    for (int bi = par; bi < C::AM; bi += RP) {
+                        float v = __builtin_fmaf(scale, acc[bi][2 * bj + v2][e], nrm);
+                        if (p.relu) v = __builtin_fmaxf(v, 0.f);
+                        dst[(bi - par) * 16 * C::SLABW] = v;
+                    }
                 }
             }
         }
@@ -582,13 +589,18 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                         for (int v2 = 0; v2 < 2; ++v2) {
                             const float nrm = nrm_r[2 * bj + v2];
                             const int sc = (wn % C::WNS) * 32 + v2 * 16 + (elane & 15);
+                            // the column swizzle depends on the row modulo NGS = SLABW / 4 only, so the 16-row
+                            // blocks one period apart share an address up to a constant (an immediate offset)
+                            constexpr int NGS = C::SLABW / 4, RP = NGS > 16 ? NGS / 16 : 1;
 #pragma unroll
-                            for (int bi = 0; bi < C::AM; ++bi) {
+                            for (int e = 0; e < 4; ++e) {
 #pragma unroll
-                                for (int e = 0; e < 4; ++e) {
-                                    const int row = wm * TM * 32 + bi * 16 + (elane >> 4) * 4 + e;
-                                    const float key = __builtin_fmaf(-2.f, acc[bi][2 * bj + v2][e], nrm);
-                                    slab[row * C::SLABW + ((((sc >> 2) ^ row) & (C::SLABW / 4 - 1)) << 2) + (sc & 3)] = key;
+                                for (int par = 0; par < RP; ++par) {
+                                    const int row0 = wm * TM * 32 + par * 16 + (elane >> 4) * 4 + e;
+                                    float *dst = slab + row0 * C::SLABW + ((((sc >> 2) ^ row0) & (NGS - 1)) << 2) + (sc & 3);
+#pragma unroll
+                                    for (int bi = par; bi < C::AM; bi += RP)
+                                        dst[(bi - par) * 16 * C::SLABW] = __builtin_fmaf(-2.f, acc[bi][2 * bj + v2][e], nrm);
                                 }
                             }
                         }
