@@ -607,19 +607,29 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                     }
                     __syncthreads();
                     if (tid < BM) {
-                        const int t = tid;
+                        int t = tid;
+                        asm volatile("" : "+v"(t));   // opaque: slab addresses are recomputed here, not kept across the main loop
                         // First pass over the row: one bit per group of four columns whose smallest key
                         // is not above the row's current R-th best (two min instructions and a compare
                         // per four keys); almost every group fails once the list has filled.
                         const f32x4 *srow = reinterpret_cast<const f32x4 *>(slab + t * C::SLABW);
                         constexpr int NG = C::SLABW / 4;
                         static_assert(NG <= 32, "one mask word");
+                        // (sixteen groups are read before the first is looked at, so that the reads overlap;
+                        // the minima go through v_min3_f32 directly: the keys are never NaN)
                         uint32_t gmask = 0;
-#pragma unroll 8
-                        for (int cg = 0; cg < NG; ++cg) {
-                            const f32x4 v = srow[(cg ^ t) & (NG - 1)];
-                            const float m = __builtin_fminf(__builtin_fminf(v[0], v[1]), __builtin_fminf(v[2], v[3]));
-                            gmask |= (uint32_t)(m <= tau) << cg;
+#pragma unroll
+                        for (int c0 = 0; c0 < NG; c0 += 16) {
+                            f32x4 v[16];
+#pragma unroll
+                            for (int c = 0; c < 16; ++c) v[c] = srow[((c0 + c) ^ t) & (NG - 1)];
+#pragma unroll
+                            for (int c = 0; c < 16; ++c) {
+                                float m;
+                                asm("v_min3_f32 %0, %1, %2, %3" : "=v"(m) : "v"(v[c][0]), "v"(v[c][1]), "v"(v[c][2]));
+                                asm("v_min_f32 %0, %1, %2" : "=v"(m) : "v"(m), "v"(v[c][3]));
+                                gmask |= (uint32_t)(m <= tau) << (c0 + c);
+                            }
                         }
                         // Second pass: the flagged groups give a bit per key that passes and is a real
                         // cache entry (padding columns are not).
