@@ -93,6 +93,8 @@ def test_hand_example_on_gpu():
     (64, 128, 20, 64, 0, torch.bfloat16),      # k = n = the re-scoring width: every entry is a candidate
     (50000, 64, 10000, 10, 0, torch.bfloat16), # 40 x 196 tiles on 256 CUs: balanced decomposition, workgroups that serve two query tiles
     (33000, 96, 7000, 5, 0, torch.float32),    # balanced decomposition, ragged last query tile
+    (4000, 512, 300, 5, 12, torch.bfloat16),   # R = 12: lists shorter than the kernel variant's 16 slots
+    (4000, 512, 300, 9, 24, torch.float32),    # R = 24 on the 32-slot variant
     (1, 1, 3, 1, 0, torch.float32),            # a cache of one scalar entry
     (5, 3, 2, 2, 0, torch.bfloat16),           # a handful of short entries, small-batch kernel
     (7, 5, 40, 3, 0, torch.float32),           # ... and the tiled kernel (more queries than entries)
