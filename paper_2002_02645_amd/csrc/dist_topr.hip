@@ -23,22 +23,21 @@
 // Two wave layouts: 4 waves (2 x 2), one per SIMD, each owning 128 x 128 in 256 AGPRs (the
 // R <= 16 variant: a third fewer fragment reads per MFMA; the MFMAs are issued through inline
 // asm so that the accumulators stay in AGPRs and the operands in VGPRs), and 8 waves (2 x 4),
-// two per SIMD, each owning (TM*32) x 64 in VGPRs (the other variants).  Both operands are stored in memory in a tiled,
-// pre-swizzled layout ([row tile][k-block][row][32 elements], see tiled_chunk_offset)
-// whose per-k-step blocks are contiguous and are exactly the LDS image, so a stage is
-// filled by a linear copy with LDS-direct 16-byte loads (no VGPR staging, fully
-// sequential DRAM access) into a ring of NS stages with NS-1 stages in flight.  The
-// chunk swizzle makes the ds_read_b128 fragment reads bank-conflict free.  The loads
-// are issued with inline asm: the compiler would otherwise order every LDS read
-// behind the outstanding direct loads, serialising load and compute.  The loop is
-// software-pipelined by hand (one barrier per k-step, placed before the MFMAs of its
-// second half; loads and the next stage's first fragment reads issued one at a time
-// between MFMAs), with scheduling barriers pinning the order.
+// two per SIMD, each owning (TM*32) x 64 in VGPRs (the other variants).
+// Both operands are stored in memory in a tiled, pre-swizzled layout ([row tile][k-block][row]
+// [32 elements], see tiled_chunk_offset) whose per-k-step blocks are contiguous and are exactly
+// the LDS image, so a stage is filled by a linear copy with LDS-direct 16-byte loads (no VGPR
+// staging, fully sequential DRAM access) into a ring of NS stages, all in use.  The chunk
+// swizzle makes the ds_read_b128 fragment reads bank-conflict free.  The loads are issued with
+// inline asm: the compiler would otherwise order every LDS read behind the outstanding direct
+// loads, serialising load and compute.  The loops are software-pipelined by hand, one barrier
+// per k-step, loads and fragment reads issued one at a time between MFMAs, with scheduling
+// barriers pinning the order (details at each loop).
 //
-// Epilogue (per tile, in column slabs that reuse the operand LDS): waves write their
-// keys to the slab; thread t scans row t, collecting a bit mask of keys not above the
-// row's current R-th best, then inserts the survivors into the row's list under the
-// total order (key, index).
+// Epilogue (per tile, in column slabs that reuse the operand LDS): waves write their keys to
+// the slab; thread t scans row t, collecting a bit mask of keys not above the row's current
+// R-th best, then inserts the survivors into the row's list (keys and entry indices in
+// separate LDS arrays) under the total order (key, index).
 #include "freeze_internal.h"
 #include "select_common.h"
 
