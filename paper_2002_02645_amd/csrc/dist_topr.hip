@@ -281,9 +281,10 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         first_part = false;
 
         // per-row selection state lives with thread t (< BM)
-        // (kmax, imax) = the list's largest entry under the order (key, index), held in slot maxpos;
-        // slots past r hold the smallest key and never count
-        uint32_t kmax = 0xffffffffu, imax = 0xffffffffu;
+        // kmax = key of the list's largest entry under the order (key, index), held in slot maxpos (its
+        // index is looked up only when a key equal to kmax turns up); slots past r hold the smallest key
+        // and never count
+        uint32_t kmax = 0xffffffffu;
         int maxpos = 0;
         float tau = __builtin_inff();
         if constexpr (!C::KEYS) {
@@ -659,7 +660,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                                 const float key = slab[t * C::SLABW + ((((sc >> 2) ^ t) & (NG - 1)) << 2) + (sc & 3)];
                                 const int tilecol = (wg * C::WNS + sc / 32) * TN * 32 + bj * 32 + (sc & 31);
                                 const uint32_t kb = ordered_bits(key), col = (uint32_t)(n0 + tilecol);
-                                if (kb < kmax || (kb == kmax && col < imax)) {
+                                if (kb < kmax || (kb == kmax && col < top_idx[maxpos * BM + t])) {
                                     // replace the largest entry, then find the new largest: the largest key, and
                                     // among equal keys (rare) the largest index
                                     top_key[key_slot(maxpos, t)] = kb;
@@ -678,8 +679,8 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                                         pos = eq ? i : pos;
                                         same += eq;
                                     }
-                                    uint32_t im = top_idx[pos * BM + t];
                                     if (same > 1) {
+                                        uint32_t im = top_idx[pos * BM + t];
 #pragma unroll 1
                                         for (int i = 0; i < r; ++i) {
                                             if (top_key[key_slot(i, t)] == km) {
@@ -689,7 +690,6 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                                         }
                                     }
                                     kmax = km;
-                                    imax = im;
                                     maxpos = pos;
                                     tau = (km == 0xffffffffu) ? __builtin_inff() : from_ordered_bits(km);
                                 }
