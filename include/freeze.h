@@ -95,8 +95,12 @@ size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b
  *   vote_threshold hit iff the winning label holds >= vote_threshold of the k
  *                  neighbours; 1 <= vote_threshold <= k.
  *   rescore_r      candidates per query kept by the bf16 matrix-core pass and
- *                  re-scored exactly in fp32; 0 = library default, else
- *                  k <= rescore_r <= FREEZE_MAX_RESCORE (clamped to n).
+ *                  re-scored exactly in fp32; 0 = library default (16 for k <= 10,
+ *                  32 for k <= 24, else 64), else k <= rescore_r <= FREEZE_MAX_RESCORE
+ *                  (clamped to n).  The k reported neighbours are the exact nearest
+ *                  among these candidates; a width close to k leaves the bf16 ranking
+ *                  no slack around rank k, and the last neighbours can then differ from
+ *                  the exact ones.
  *   out_labels     [b] int32  winning label (equal counts -> smaller label id).
  *   out_hit        [b] uint8  1 = cache hit.
  *   out_votes      [b] int32  occurrences m of the winning label.
