@@ -333,7 +333,8 @@ __device__ __forceinline__ void rescore_block(const FinishArgs &a, const float *
             acc[j] = 0.f;
             cand[j] = idx_s[(r0 + j < r) ? r0 + j : r - 1];
         }
-        for (int64_t i = (int64_t)tid * 8; i < a.d; i += NT * 8) {
+#pragma unroll 4
+        for (int64_t i = (int64_t)tid * 8; i < a.d; i += NT * 8) {   // four rounds of loads in flight
             const f32x4 q0 = *reinterpret_cast<const f32x4 *>(qrow + i);
             const f32x4 q1 = *reinterpret_cast<const f32x4 *>(qrow + i + 4);
             const float qv[8] = {q0[0], q0[1], q0[2], q0[3], q1[0], q1[1], q1[2], q1[3]};
