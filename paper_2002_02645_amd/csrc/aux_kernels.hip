@@ -39,22 +39,53 @@ __global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, i
     const int rit = (int)(row % kTileN);
     uint4 *tile_base = reinterpret_cast<uint4 *>(c_bf + tile * kTileN * d_pad);
     float ss = 0.f;
+    // rows start 16-byte aligned when the batch does and d is a multiple of 8 (bf16) or 4 (fp32):
+    // whole chunks are then fetched with 16-byte loads
+    const bool vec = row < n && (reinterpret_cast<uintptr_t>(entries) % 16) == 0 && (dtype == 0 ? d % 4 == 0 : d % 8 == 0);
     for (int64_t j = threadIdx.x; j < d_pad / 8; j += 256) {   // one 16-byte chunk (8 elements) per step
         uint16_t h[8];
+        float f[8];
+        if (vec && j * 8 + 8 <= d) {
+            if (dtype == 0) {
+                const float *src = reinterpret_cast<const float *>(entries) + row * d + j * 8;
+                const f32x4 v0 = *reinterpret_cast<const f32x4 *>(src), v1 = *reinterpret_cast<const f32x4 *>(src + 4);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t i = j * 8 + e;
-            float f = 0.f;
-            h[e] = 0;
-            if (row < n && i < d) {
-                if (dtype == 0) {
-                    f = reinterpret_cast<const float *>(entries)[row * d + i];
-                    h[e] = bf16_rne(f);
-                } else {
-                    h[e] = reinterpret_cast<const uint16_t *>(entries)[row * d + i];
+                for (int e = 0; e < 4; ++e) {
+                    f[e] = v0[e];
+                    f[4 + e] = v1[e];
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) h[e] = bf16_rne(f[e]);
+            } else {
+                const uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(entries) + row * d + j * 8);
+                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    h[2 * e] = (uint16_t)(wv[e] & 0xffffu);
+                    h[2 * e + 1] = (uint16_t)(wv[e] >> 16);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] = 0.f;   // (fp32 rows are kept only for fp32 input)
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int64_t i = j * 8 + e;
+                f[e] = 0.f;
+                h[e] = 0;
+                if (row < n && i < d) {
+                    if (dtype == 0) {
+                        f[e] = reinterpret_cast<const float *>(entries)[row * d + i];
+                        h[e] = bf16_rne(f[e]);
+                    } else {
+                        h[e] = reinterpret_cast<const uint16_t *>(entries)[row * d + i];
+                    }
                 }
             }
-            if (c_f32 && row < n) c_f32[row * d_pad + i] = f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (c_f32 && row < n) c_f32[row * d_pad + j * 8 + e] = f[e];
             const float x = bf16_to_f32(h[e]);
             ss = __builtin_fmaf(x, x, ss);
         }
