@@ -48,7 +48,7 @@ namespace {
 // per-lane offset) and they land in LDS at lds_byte_addr + 16 i (M0 = wave-uniform destination).
 __device__ __forceinline__ void load16_global_to_lds(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
                  : "memory", "m0");
 }
 __device__ __forceinline__ uint64_t uniform_u64(uint64_t x)

@@ -58,6 +58,12 @@ __device__ __forceinline__ void load16_global_to_lds(uint64_t sbase, uint32_t vo
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
                  : "memory", "m0");
 }
+// the same with the non-temporal hint (data that no other workgroup will ask for again)
+__device__ __forceinline__ void load16_global_to_lds_nt(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
 __device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
 {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
@@ -69,7 +75,7 @@ __device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
 template <int N>
 __device__ __forceinline__ void wait_global_loads_le() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int BM_, int BK_, int RMAX_, int NS_, int WN_ = 4>
+template <int BM_, int BK_, int RMAX_, int NS_, int WN_ = 4, bool B_ONCE_ = false>
 struct DistCfg {
     static constexpr int BM = BM_, BN = kTileN, BK = BK_, RMAX = RMAX_;
     static constexpr int NS = NS_;                  // operand stages in LDS, all in use (NS - 1 in flight)
@@ -88,6 +94,10 @@ struct DistCfg {
     static constexpr int WNS = (WN >= 4 && BM * 4 * 32 * 4 <= OP_BYTES) ? 4 : ((WN >= 2 && BM * 2 * 32 * 4 <= OP_BYTES) ? 2 : 1);
     static constexpr int SLABW = WNS * 32;          // keys per row in one slab
     static constexpr bool KEYS = (RMAX == 0);       // no fused selection: write every key (small batches)
+    // the launch reads every byte of the cache operand exactly once (one query tile): its loads carry
+    // the non-temporal hint, so that the stream does not push the query operand, which every
+    // workgroup of an XCD re-reads, out of L2
+    static constexpr bool B_ONCE = B_ONCE_;
     static constexpr int TOP_BYTES = RMAX * BM * 8;
     static constexpr int LDS_BYTES = OP_BYTES + TOP_BYTES;
     static_assert(BM * SLABW * 4 <= OP_BYTES, "slab must fit in the operand area");
@@ -349,6 +359,9 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                 if (l < C::NI_A)
                     load16_global_to_lds(gA + (size_t)kt * C::A_BYTES + l * (C::NWAVES * 1024), lane_off,
                                          sbase + l * (C::NWAVES * 1024));
+                else if constexpr (C::B_ONCE)
+                    load16_global_to_lds_nt(gB + (size_t)kt * (BN * BK * 2) + (l - C::NI_A) * (C::NWAVES * 1024), lane_off,
+                                         sbase + C::A_BYTES + (l - C::NI_A) * (C::NWAVES * 1024));
                 else
                     load16_global_to_lds(gB + (size_t)kt * (BN * BK * 2) + (l - C::NI_A) * (C::NWAVES * 1024), lane_off,
                                          sbase + C::A_BYTES + (l - C::NI_A) * (C::NWAVES * 1024));
@@ -897,7 +910,9 @@ hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t
     case 0: return launch_variant<DistCfg<256, 32, 16, 4, 2>>(plan, a, s);
     case 1: return launch_variant<DistCfg<256, 32, 32, 3>>(plan, a, s);
     case 2: return launch_variant<DistCfg<128, 32, 64, 4>>(plan, a, s);
-    default: return launch_variant<DistCfg<256, 32, 0, 5>>(plan, a, s);
+    default:
+        if (plan.sk_wgs > 0 && plan.m_tiles == 1) return launch_variant<DistCfg<256, 32, 0, 5, 4, true>>(plan, a, s);
+        return launch_variant<DistCfg<256, 32, 0, 5>>(plan, a, s);
     }
 }
 
