@@ -285,7 +285,8 @@ int freeze_profile_read_calls(freeze_ctx *ctx, float *call_ms, int max_calls, in
  *   tflops         host out: sustained dense bf16 rate in TFLOP/s.
  *   shader_mhz     host out: shader clock held under that load, in MHz.
  * freeze_calibrate_hbm_read: reads every byte of `buffer` (device, 16-byte aligned, >= 1 MiB,
- *   initialised by the caller; never written) five times.
+ *   initialised by the caller; never written) five times, with non-temporal 16-byte loads, each
+ *   workgroup walking a contiguous share.
  *   gbytes_per_s   host out: sustained read rate in GB/s.
  */
 int freeze_calibrate_mfma(void *scratch, size_t scratch_bytes, double *tflops, double *shader_mhz);

@@ -127,6 +127,12 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
                             smem_base + NORMS + ((t & 1) * 8 + w) * 256);
     };
 
+    // the stream starts before the queries are converted: its first stages are on their way meanwhile
+    if (total > 0) issue_norms(nt0);
+#pragma unroll
+    for (int ps = 0; ps < C::NS - 1; ++ps)
+        if (ps < total) issue(ps, ps);
+
     // queries -> LDS: bf16 (round to nearest even) in the tiled layout with one 16-row tile, rows
     // past the batch and elements past d zero.  Every workgroup converts them for itself (32 KiB of
     // L2-resident reads), which saves a kernel launch in front of a 0.2 ms look-up.
@@ -156,11 +162,6 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
             dst[tiled_chunk_offset(row, j, kQRows)] = v;
         }
     }
-    if (total > 0) issue_norms(nt0);
-#pragma unroll
-    for (int ps = 0; ps < C::NS - 1; ++ps)
-        if (ps < total) issue(ps, ps);
-
     const int g = lane >> 5;
     const int rowA = lane & 15;              // lanes whose MFMA row is 16..31 supply zeros instead
     const bool has_q = (lane & 31) < kQRows;
