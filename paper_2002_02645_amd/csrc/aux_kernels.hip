@@ -125,6 +125,8 @@ hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t
 // one; rows up to the next tile boundary are zero filled.  One block per pair of rows: in the
 // tiled layout the 64-byte pieces of two neighbouring rows share a 128-byte line, so eight
 // consecutive threads (two rows x four 16-byte chunks of one k-block) write a whole line.
+// With few rows and long activations the grid's second dimension cuts the row pair into ranges
+// of chunks, so that a batch of 256 rows still fills the chip.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, const int32_t *sel, const int32_t *count,
                                                          int b, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf)
@@ -139,7 +141,9 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
     const float *src = (row < nq) ? queries + (int64_t)(sel ? sel[row] : row) * d : nullptr;
     const bool vec = (d % 4) == 0;     // rows are then 16-byte aligned (the batch pointer is)
     const int64_t pair_chunks = d_pad / 4;   // 16-byte chunks of the two rows together
-    for (int64_t jj = threadIdx.x; jj < pair_chunks; jj += 256) {
+    const int64_t per = ((pair_chunks + gridDim.y - 1) / gridDim.y + 255) / 256 * 256;   // chunks per block of the pair
+    const int64_t jj_end = (blockIdx.y + 1) * per < pair_chunks ? (blockIdx.y + 1) * per : pair_chunks;
+    for (int64_t jj = blockIdx.y * per + threadIdx.x; jj < jj_end; jj += 256) {
         const int64_t j = (jj >> 3) * 4 + (jj & 3);   // chunk of 8 elements within the row
         const int64_t i0 = j * 8;
         float x[8];
@@ -171,8 +175,13 @@ hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int
                              int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, hipStream_t s)
 {
     if (bm % 2 != 0 || b_pad % 2 != 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(query_prep_kernel, dim3((unsigned)(b_pad / 2)), dim3(256), 0, s, queries, sel, count, (int)b, bm,
-                       d, d_pad, q_bf);
+    // about 2048 blocks in all, at least four rounds of 256 chunks each
+    const int64_t pairs = b_pad / 2, rounds = d_pad / 4 / 256;
+    int64_t ysplit = pairs > 0 ? 2048 / pairs : 1;
+    if (ysplit > rounds / 4) ysplit = rounds / 4;
+    if (ysplit < 1) ysplit = 1;
+    hipLaunchKernelGGL(query_prep_kernel, dim3((unsigned)pairs, (unsigned)ysplit), dim3(256), 0, s, queries, sel, count,
+                       (int)b, bm, d, d_pad, q_bf);
     return hipGetLastError();
 }
 
