@@ -311,12 +311,15 @@ bool cascade_layout(const freeze_ctx *ctx, int num_layers, const int *layers, in
     for (int l = 0; l < num_layers; ++l) {
         const LayerCache *L = get_layer(ctx, layers[l], err);
         if (!L) return false;
-        LookupShape sh;
-        if (!lookup_shape(ctx, *L, b, k, rescore_r, true, &sh)) {
+        // a layer is looked up either with the live count on the device (later layers of a cascade)
+        // or with all b requests (its first layer; every layer while thresholds are calibrated)
+        LookupShape sh, sh_all;
+        if (!lookup_shape(ctx, *L, b, k, rescore_r, true, &sh) || !lookup_shape(ctx, *L, b, k, rescore_r, false, &sh_all)) {
             *err = FREEZE_EINVAL;
             return false;
         }
         if (sh.ws_bytes > mx) mx = sh.ws_bytes;
+        if (sh_all.ws_bytes > mx) mx = sh_all.ws_bytes;
     }
     out->lookup_ws = mx;
     const size_t bb = (size_t)(b > 0 ? b : 1);
@@ -404,8 +407,11 @@ int cascade_checked(freeze_ctx *ctx, int num_layers, const int *layers, const fl
     const int32_t *count = nullptr;
     for (int l = 0; l < num_layers; ++l) {
         const LayerCache &L = ctx->layers[layers[l]];
+        // Every request enters the first layer: its look-up is planned like a single-layer one, with
+        // the count known on the host (any route, any decomposition); the later layers are sized for
+        // b and read the live count on the device.
         LookupShape sh;
-        lookup_shape(ctx, L, b, k, rescore_r, true, &sh);
+        lookup_shape(ctx, L, b, k, rescore_r, l != 0, &sh);
         HitRule rule = rules[(size_t)l];
         rule.out_conf = t_conf;
         int rc = enqueue_lookup(ctx, L, sh, queries_per_layer[l], sel, count, b, k, rule, t_labels, t_hit, t_votes,
@@ -661,7 +667,7 @@ int freeze_compute_thresholds(freeze_ctx *ctx, int num_layers, const int *layers
     for (int l = 0; l < num_layers; ++l) {
         const LayerCache &L = ctx->layers[layers[l]];
         LookupShape sh;
-        lookup_shape(ctx, L, b, k, rescore_r, true, &sh);
+        lookup_shape(ctx, L, b, k, rescore_r, false, &sh);
         int kind = 1;
         if (int rck = confidence_rule_for(ctx, layers[l], k, &kind)) return rck;
         const HitRule rule{kind, 1, 0.f, t_conf};
