@@ -99,6 +99,9 @@ def test_hand_example_on_gpu():
     (5, 3, 2, 2, 0, torch.bfloat16),           # a handful of short entries, small-batch kernel
     (7, 5, 40, 3, 0, torch.float32),           # ... and the tiled kernel (more queries than entries)
     (257, 33, 257, 4, 0, torch.bfloat16),      # one entry and one query past a tile
+    (20000, 2048, 1800, 10, 0, torch.bfloat16),  # 8 x 79 tiles in 32 splits of 2 or 3 tiles, long rows
+    (9000, 2112, 4000, 20, 0, torch.float32),    # 16 query tiles on the R = 32 variant, ragged d, fp32 cache
+    (9000, 2048, 2000, 10, 64, torch.bfloat16),  # 16 query tiles on the R = 64 variant (128-query tiles)
 ])
 def test_shapes_against_oracle(n, d, b, k, r, dtype):
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
