@@ -103,8 +103,12 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     } else {
         // One query tile and a long activation: materialising the keys (4 B per entry and query)
         // is cheap next to the cache stream (2 d B per entry), lets the tile be 256 queries wide for
-        // any R, and keeps the selection out of the streaming kernel.
-        out->keys = !cascade && b <= 256 && b * 20 <= L.d_pad && select_supported(L.n_pad, r);
+        // any R, and keeps the selection out of the streaming kernel.  One query tile and a cache of
+        // moderate size: every workgroup of the fused kernel gets a few tiles only and spends most of
+        // its time filling its empty candidate lists key by key, so the keys go out here too
+        // (measured cross-over: about 2^26 keys; 256 x 2,000: 129 -> 69 us, 200 x 50,000 x 512: 209 -> 80 us).
+        out->keys = !cascade && b <= 256 && (b * 20 <= L.d_pad || b * L.n_pad <= ((int64_t)1 << 26)) &&
+                    select_supported(L.n_pad, r);
         out->plan = plan_dist(b, L.n, r, ctx->num_cus, out->keys, L.d_pad);
         out->ws_bytes = align_up((size_t)out->plan.b_pad * L.d_pad * 2);
         if (out->keys)
