@@ -296,6 +296,7 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
         // and never count
         uint32_t kmax = 0xffffffffu;
         int maxpos = 0;
+        int fill = 0;   // slots taken while the list still has empty ones (they fill in order)
         float tau = __builtin_inff();
         if constexpr (!C::KEYS) {
             if (tid < BM) {
@@ -678,6 +679,13 @@ __global__ __launch_bounds__(C::THREADS) void dist_topr_kernel(DistKernelArgs p)
                                     // among equal keys (rare) the largest index
                                     top_key[key_slot(maxpos, t)] = kb;
                                     top_idx[maxpos * BM + t] = col;
+                                    if (fill + 1 < r) {
+                                        // empty slots remain: each of them is a largest entry, the next one
+                                        // is taken next, and nothing else about the list's maximum changes
+                                        maxpos = ++fill;
+                                        continue;
+                                    }
+                                    fill = r;
                                     u32x4 k4[C::RMAX > 0 ? C::RMAX / 4 : 1];   // (the keys-out variant never gets here)
 #pragma unroll
                                     for (int j = 0; j < C::RMAX / 4; ++j)
