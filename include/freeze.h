@@ -25,6 +25,11 @@
  *  - Neighbour order is (distance, entry index) ascending: equal distances rank
  *    the lower entry index first.
  *  - Inputs must be finite; the result for NaN/Inf inputs is unspecified.
+ *  - A context is plain host state without locks: calls on one context must not overlap in
+ *    time on the host (building a layer while another thread looks it up, or two threads
+ *    with stage timing enabled).  Look-ups enqueued on different streams may run side by side
+ *    on the device when each has its own workspace and outputs; a cache being read must not
+ *    be rebuilt until those look-ups have finished.
  */
 #ifndef FREEZE_H
 #define FREEZE_H
