@@ -15,11 +15,11 @@
 //     smallest entry overall is <= T, and every entry <= T lies in one of exactly those R
 //     blocks: their 32 R entries are a superset of the R best.  It re-scores all of them
 //     exactly in fp32 (d <= 1024: one KiB or two per entry) and keeps the k nearest.
-// The threshold and filter kernels at the end of this file serve the keys-out variant of the
-// tiled kernel (long activations, one query tile), where the keys are materialised:
-//  - block_threshold_kernel finds, per query, the R-th smallest block minimum T;
-//  - key_filter_kernel collects the entries with (key, index) <= T (at most 32 R) into a
-//    candidate list, which the general finishing kernel sorts, cuts to R and re-scores.
+// The threshold kernel at the end of this file serves the keys-out variant of the tiled kernel
+// (one query tile), where the keys are materialised: block_threshold_kernel finds, per query, the
+// R-th smallest block minimum T and collects the entries with (key, index) <= T (at most 32 R,
+// all of them in the R blocks whose minimum is <= T) into a candidate list, which the general
+// finishing kernel sorts, cuts to R and re-scores.
 //
 // Paper: Sec. 3 (k nearest neighbours of the layer output), Sec. 5 "Cache lookup
 // performance" (look-up latency decides whether freezing pays off).
@@ -257,50 +257,47 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
 
 // ---------------------------------------------------------------------------------------
 // Per query: T = the R-th smallest of the NB block minima (pairs (ordered key, index), all
-// distinct).  One workgroup of 1024 threads per query (rth_smallest_of).
+// distinct), then the candidate list: exactly R blocks have a minimum <= T and they hold every entry
+// whose pair is <= T (at most 32 R, see the file header; `cap` >= that bound), so only those
+// blocks' keys are read, 128 bytes each.  One workgroup of 1024 threads per query.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThrThreads) void block_threshold_kernel(const uint64_t *bmin, int64_t nb, int r_sel,
-                                                                      uint64_t *tau, int32_t *cand_count)
+                                                                      const float *keys, int64_t n_pad, int n,
+                                                                      uint64_t *cand, int32_t *cand_count, int cap)
 {
     __shared__ uint64_t list[kThrList];
     __shared__ uint64_t sel_s;
     __shared__ int list_n;
+    __shared__ int blk_n, cnt_s;
+    __shared__ int32_t blk_s[kMaxRescore];
     const int q = blockIdx.x, tid = threadIdx.x;
-    if (tid == 0) cand_count[q] = 0;
-    if (r_sel >= nb) {   // fewer blocks than wanted entries: everything passes
-        if (tid == 0) tau[q] = kSentinel;
-        return;
+    const uint64_t *bq = bmin + (size_t)q * nb;
+    // fewer blocks than wanted entries: everything passes
+    const uint64_t t = r_sel >= nb ? kSentinel : rth_smallest_of(bq, nb, r_sel, list, &sel_s, &list_n, tid);
+    if (tid == 0) {
+        blk_n = 0;
+        cnt_s = 0;
     }
-    const uint64_t t = rth_smallest_of(bmin + (size_t)q * nb, nb, r_sel, list, &sel_s, &list_n, tid);
-    if (tid == 0) tau[q] = t;
-}
-
-// ---------------------------------------------------------------------------------------
-// Collect, per query, the entries whose (ordered key, index) pair is <= T.  Grid: (chunks, b).
-// At most 32 * R entries pass (see the file header); `cap` >= that bound.
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void key_filter_kernel(const float *keys, int64_t n_pad, int n, const uint64_t *tau,
-                                                            uint64_t *cand, int32_t *cand_count, int cap)
-{
-    const int q = blockIdx.y;
-    const uint64_t t = tau[q];
-    const float *kq = keys + (size_t)q * n_pad;
-    const int64_t per = (n_pad / 4 + gridDim.x - 1) / gridDim.x;   // float4 groups per block
-    const int64_t lo = (int64_t)blockIdx.x * per;
-    const int64_t hi = (lo + per < n_pad / 4) ? lo + per : n_pad / 4;
-    for (int64_t j = lo + threadIdx.x; j < hi; j += 256) {
-        const float4 v = reinterpret_cast<const float4 *>(kq)[j];
-        const float kv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int64_t idx = j * 4 + e;
-            const uint64_t pr = ((uint64_t)ordered_bits(kv[e]) << 32) | (uint32_t)idx;
-            if (pr <= t && idx < n) {
-                const int pos = atomicAdd(&cand_count[q], 1);
-                if (pos < cap) cand[(size_t)q * cap + pos] = pr;
-            }
+    __syncthreads();
+    for (int64_t i = tid; i < nb; i += kThrThreads) {
+        if (bq[i] <= t) {
+            const int pos = atomicAdd(&blk_n, 1);
+            if (pos < kMaxRescore) blk_s[pos] = (int32_t)i;
         }
     }
+    __syncthreads();
+    const int nblk = blk_n < kMaxRescore ? blk_n : kMaxRescore;   // = min(r_sel, nb)
+    const float *kq = keys + (size_t)q * n_pad;
+    for (int c = tid; c < nblk * 32; c += kThrThreads) {
+        const int64_t idx = (int64_t)blk_s[c >> 5] * 32 + (c & 31);
+        const uint64_t pr = ((uint64_t)ordered_bits(kq[idx]) << 32) | (uint32_t)idx;
+        if (pr <= t && idx < n) {
+            const int pos = atomicAdd(&cnt_s, 1);
+            if (pos < cap) cand[(size_t)q * cap + pos] = pr;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) cand_count[q] = cnt_s;
 }
 
 }  // namespace
@@ -326,8 +323,7 @@ size_t select_workspace_bytes(int64_t rows, int64_t n_pad, int r, size_t align)
 {
     auto up = [&](size_t x) { return (x + align - 1) / align * align; };
     const size_t b = (size_t)rows;
-    return up(b * (size_t)n_pad * 4) + up(b * (size_t)(n_pad / 32) * 8) + up(b * 8) + up(b * 4) +
-           up(b * (size_t)(32 * r) * 8);
+    return up(b * (size_t)n_pad * 4) + up(b * (size_t)(n_pad / 32) * 8) + up(b * 4) + up(b * (size_t)(32 * r) * 8);
 }
 
 int plan_skinny_splits(int64_t n, int num_cus)
@@ -368,18 +364,12 @@ hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_select(const float *keys, const uint64_t *bmin, int64_t n_pad, int n, int b, int r, uint64_t *tau,
+hipError_t launch_select(const float *keys, const uint64_t *bmin, int64_t n_pad, int n, int b, int r,
                          int32_t *cand_count, uint64_t *cand, hipStream_t s)
 {
     const int64_t nb = n_pad / 32;
     if (!select_supported(n_pad, r) || b < 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(block_threshold_kernel, dim3(b), dim3(kThrThreads), 0, s, bmin, nb, r, tau, cand_count);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    int chunks = (int)((n_pad / 4 + 256 * 16 - 1) / (256 * 16));   // ~16 float4 groups per thread
-    if (chunks < 1) chunks = 1;
-    if (chunks > 256) chunks = 256;
-    hipLaunchKernelGGL(key_filter_kernel, dim3(chunks, b), dim3(256), 0, s, keys, n_pad, n, tau, cand, cand_count,
+    hipLaunchKernelGGL(block_threshold_kernel, dim3(b), dim3(kThrThreads), 0, s, bmin, nb, r, keys, n_pad, n, cand, cand_count,
                        32 * r);
     return hipGetLastError();
 }

@@ -232,14 +232,13 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
             const size_t rows = (size_t)sh.plan.b_pad;
             da.keys = ws.take<float>(rows * L.n_pad);
             da.bmin = ws.take<uint64_t>(rows * (L.n_pad / 32));
-            uint64_t *tau = ws.take<uint64_t>(rows);
             int32_t *cand_count = ws.take<int32_t>(rows);
             uint64_t *cand = ws.take<uint64_t>(rows * 32 * sh.r);
             da.partial = sh.plan.sk_wgs > 0 ? ws.take<float>(dist_partial_bytes(sh.plan) / 4) : nullptr;
             if (launch_dist_topr(sh.plan, da, s) != hipSuccess) return FREEZE_EHIP;
             marks.mark(2);
             marked2 = true;
-            if (launch_select(da.keys, da.bmin, L.n_pad, (int)L.n, (int)b, sh.r, tau, cand_count, cand, s) != hipSuccess)
+            if (launch_select(da.keys, da.bmin, L.n_pad, (int)L.n, (int)b, sh.r, cand_count, cand, s) != hipSuccess)
                 return FREEZE_EHIP;
             fa.part = cand;
             fa.part_count = cand_count;

@@ -168,7 +168,7 @@ bool skinny_supported(int64_t b, int64_t n_pad, int64_t d_pad, int r, int num_cu
 // block minima, then the candidate lists.  b queries, rows of n_pad keys.
 bool select_supported(int64_t n_pad, int r);
 size_t select_workspace_bytes(int64_t rows, int64_t n_pad, int r, size_t align);
-hipError_t launch_select(const float *keys, const uint64_t *bmin, int64_t n_pad, int n, int b, int r, uint64_t *tau,
+hipError_t launch_select(const float *keys, const uint64_t *bmin, int64_t n_pad, int n, int b, int r,
                          int32_t *cand_count, uint64_t *cand, hipStream_t s);
 int plan_skinny_splits(int64_t n, int num_cus);
 size_t skinny_workspace_bytes(int64_t n_pad, int r, size_t align);
