@@ -46,6 +46,51 @@ def measured_traffic(kernel: str, workload: str):
     return (vals["FETCH_SIZE"] * factor["FETCH_SIZE"] + vals["WRITE_SIZE"] * factor["WRITE_SIZE"]) * 1024.0
 
 
+def time_next_rows(torch, binding, dev):
+    """Wall-clock times (synchronised, inputs resident) of the k-means cache and of the projection on
+    seeded synthetic inputs: 50,000 points x 8,192 in 10 classes -> 200 centres; 1,024 outputs."""
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.time() - t0) / reps * 1e3
+
+    res = {"data": "synthetic", "kmeans": {}, "projection": []}
+    g = torch.Generator(device=dev)
+    g.manual_seed(20020264)
+    n, d, kc, classes, nq = 50000, 8192, 200, 10, 10000
+    cent = torch.randn(classes, d, device=dev, generator=g)
+    cls = torch.randint(0, classes, (n,), device=dev, generator=g)
+    pts = (cent[cls] + 0.8 * torch.randn(n, d, device=dev, generator=g)).contiguous()
+    lab = cls.to(torch.int32)
+    init = pts[:kc].clone()
+    fc = binding.FreezeCache(1, dev)
+    t1 = timed(lambda: fc.build_kmeans_layer(0, pts, lab, classes, init, 1), 3)
+    t5 = timed(lambda: fc.build_kmeans_layer(0, pts, lab, classes, init, 5), 3)
+    q = (cent[torch.randint(0, classes, (nq,), device=dev, generator=g)] +
+         0.8 * torch.randn(nq, d, device=dev, generator=g)).contiguous()
+    tl = timed(lambda: fc.lookup_confidence(0, q, 1, 0.01), 10)
+    res["kmeans"] = {"points": n, "d": d, "centres": kc, "build_ms_1_round": round(t1, 3), "build_ms_5_rounds": round(t5, 3),
+                     "ms_per_round": round((t5 - t1) / 4, 3), "lookup_queries": nq, "lookup_ms": round(tl, 3)}
+    fc.close()
+    del pts, q
+    for (b, dd, m) in [(10000, 8192, 1024), (4096, 65536, 1024), (256, 65536, 1024)]:
+        x = torch.randn(b, dd, device=dev, generator=g)
+        w = (torch.randn(m, dd, device=dev, generator=g) / dd ** 0.5).to(torch.bfloat16)
+        bias = torch.zeros(m, device=dev)
+        fc = binding.FreezeCache(1, dev)
+        fc.build_projection(0, w, bias)
+        ms = timed(lambda: fc.project(0, x, True), 10)
+        res["projection"].append({"inputs": b, "d": dd, "outputs": m, "ms": round(ms, 3),
+                                  "TFLOPs": round(2.0 * b * dd * m / ms / 1e9, 1)})
+        fc.close()
+        del x, w
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -60,6 +105,9 @@ def main() -> int:
                     help="also measure what this GPU sustains on a pure MFMA loop and on a pure 1 GiB read")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--next-rows", action="store_true",
+                    help="instead of a look-up workload, time the k-means cache (Sec. 4 of the paper) and the "
+                         "projection in front of the look-up (Sec. 3) at the paper's scale; prints one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (one-GPU boxes; the path has no multi-GPU part); "
@@ -77,6 +125,10 @@ def main() -> int:
     binding.lib()   # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.next_rows:
+        print(json.dumps(time_next_rows(torch, binding, dev)))
+        return 0
 
     wl = synth.WORKLOADS[args.workload]
     nl = len(wl.layers)
