@@ -111,7 +111,7 @@ __device__ inline uint64_t rth_smallest_of(const uint64_t *src, int64_t nb, int 
                                            int *list_n, int tid)
 {
     if (tid == 0) *list_n = 0;
-    // round 1: thread minima -> 256 group minima -> T1 = the r_sel-th smallest group minimum
+    // first pass: thread minima -> 256 group minima -> T1 = the r_sel-th smallest group minimum
     uint64_t v[kThrRegs];
     uint64_t m = kSentinel;
 #pragma unroll
@@ -141,7 +141,7 @@ __device__ inline uint64_t rth_smallest_of(const uint64_t *src, int64_t nb, int 
     __syncthreads();
     const uint64_t t1 = *sel_s;
     __syncthreads();
-    // round 2: gather the values <= T1 (at least r_sel, at most V * r_sel of them)
+    // second pass: gather the values <= T1 (at least r_sel, at most V * r_sel of them)
 #pragma unroll
     for (int i = 0; i < kThrRegs; ++i) {
         if (v[i] <= t1 && v[i] != kSentinel) {
