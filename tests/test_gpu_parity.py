@@ -102,6 +102,10 @@ def test_hand_example_on_gpu():
     (20000, 2048, 1800, 10, 0, torch.bfloat16),  # 8 x 79 tiles in 32 splits of 2 or 3 tiles, long rows
     (9000, 2112, 4000, 20, 0, torch.float32),    # 16 query tiles on the R = 32 variant, ragged d, fp32 cache
     (9000, 2048, 2000, 10, 64, torch.bfloat16),  # 16 query tiles on the R = 64 variant (128-query tiles)
+    (2000000, 64, 300, 48, 0, torch.bfloat16),   # two million entries, the largest k
+    (3000, 64, 100000, 10, 0, torch.bfloat16),   # a hundred thousand queries (391 query tiles)
+    (1500000, 96, 16, 20, 0, torch.bfloat16),    # small-batch kernel at its largest batch, 1.5 million entries
+    (120, 70000, 40, 10, 0, torch.bfloat16),     # activations longer than any benchmark layer
 ])
 def test_shapes_against_oracle(n, d, b, k, r, dtype):
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
