@@ -208,6 +208,8 @@ def main() -> int:
             per_layer[i % nl][j] += c[j]
         counted[i % nl] += 1
     per_layer = [[v / max(counted[l], 1) for v in per_layer[l]] for l in range(nl)]
+    # per step: the stage times of its look-ups added up (kernel time without the gaps between calls)
+    step_ms = sorted(sum(sum(c) for c in calls[i:i + nl]) for i in range(0, len(calls) - nl + 1, nl))
 
     # roofline of the dominant kernel: the distance pass of the (first) layer.
     # algorithmic flops per launch = 2 * B * N * d; algorithmic bytes (small batches) = N * d * 2
@@ -236,6 +238,8 @@ def main() -> int:
                           + f", batch {b}, k={k}, vote_thresholds={list(wl.vote_thresholds)}, "
                             f"rescore_r={r if r else 'default'}",
               "event_ms_per_step": round(ev_ms_per_step, 4),
+              "stage_sum_ms_median": round(step_ms[len(step_ms) // 2], 4) if step_ms else None,
+              "stage_sum_ms_min": round(step_ms[0], 4) if step_ms else None,
               "ms_per_step_without_stage_events": round(ms_per_step_plain, 4), "cache_build_s": round(build_s, 3), "cache_copies": copies,
               "input_gen_s": round(gen_s, 2)}
     if cascade:
