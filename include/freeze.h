@@ -49,7 +49,8 @@ enum {
     FREEZE_ELAYER = -2,     /* layer index out of range */
     FREEZE_ENOTBUILT = -3,  /* layer has no cache yet */
     FREEZE_EWORKSPACE = -4, /* storage / workspace buffer too small or misaligned */
-    FREEZE_EHIP = -5        /* a HIP runtime call failed (launch error) */
+    FREEZE_EHIP = -5,       /* a HIP runtime call failed (launch error) */
+    FREEZE_ESCRATCH = -6    /* freeze_lookup_static: the look-up needs more than FREEZE_STATIC_SCRATCH_BYTES */
 };
 
 enum { FREEZE_F32 = 0, FREEZE_BF16 = 1 }; /* element type of the entries handed to freeze_cache_build */
@@ -121,6 +122,24 @@ int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, i
                   int rescore_r, int32_t *out_labels, uint8_t *out_hit, int32_t *out_votes,
                   int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace, size_t workspace_bytes,
                   void *stream);
+
+/*
+ * freeze_lookup for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as freeze_lookup, except that the workspace is a buffer of
+ * FREEZE_STATIC_SCRATCH_BYTES bytes that lives inside the library's device code (every GPU the
+ * library runs on holds one until the process ends).  The call allocates nothing, on the
+ * device or through any library.  A look-up whose freeze_lookup_workspace_bytes() exceeds
+ * FREEZE_STATIC_SCRATCH_BYTES is refused with FREEZE_ESCRATCH before anything is enqueued
+ * (32 MiB covers e.g. 16 queries against 1,000,000 x 512 entries, or 256 queries against
+ * 2,000 x 512).  All calls on one GPU share that GPU's buffer, whatever context or stream they
+ * use: calls that overlap in time on one GPU race; order them on one stream.  The buffer keeps
+ * the last call's contents; nothing in it needs to be zero when a call starts.
+ */
+#define FREEZE_STATIC_SCRATCH_BYTES (32u << 20)
+int freeze_lookup_static(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k,
+                         int vote_threshold, int rescore_r, int32_t *out_labels, uint8_t *out_hit,
+                         int32_t *out_votes, int32_t *out_nbr_idx, float *out_nbr_dist, void *stream);
 
 /* Bytes of workspace freeze_lookup_cascade needs. `layers` is a host array. 0 on invalid arguments. */
 size_t freeze_cascade_workspace_bytes(const freeze_ctx *ctx, int num_layers, const int *layers, int64_t b,

@@ -16,6 +16,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "_lib", "libfreeze_hip.so")
 
 FREEZE_OK, FREEZE_EINVAL, FREEZE_ELAYER, FREEZE_ENOTBUILT, FREEZE_EWORKSPACE, FREEZE_EHIP = 0, -1, -2, -3, -4, -5
+FREEZE_ESCRATCH = -6
+FREEZE_STATIC_SCRATCH_BYTES = 32 << 20
 FREEZE_F32, FREEZE_BF16 = 0, 1
 
 _lib = None
@@ -50,6 +52,8 @@ def lib():
     L.freeze_lookup_workspace_bytes.argtypes = [p, i32, i64, i32, i32]
     L.freeze_lookup.restype = i32
     L.freeze_lookup.argtypes = [p, i32, p, i64, i32, i32, i32, p, p, p, p, p, p, sz, p]
+    L.freeze_lookup_static.restype = i32
+    L.freeze_lookup_static.argtypes = [p, i32, p, i64, i32, i32, i32, p, p, p, p, p, p]
     L.freeze_cascade_workspace_bytes.restype = sz
     L.freeze_cascade_workspace_bytes.argtypes = [p, i32, p, i64, i32, i32]
     L.freeze_lookup_cascade.restype = i32
@@ -155,6 +159,16 @@ def freeze_lookup(ctx, layer: int, queries: torch.Tensor, k: int, vote_threshold
                                _ptr(out_hit), _ptr(out_votes), _ptr(out_nbr_idx), _ptr(out_nbr_dist),
                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "freeze_lookup")
+
+
+def freeze_lookup_static(ctx, layer: int, queries: torch.Tensor, k: int, vote_threshold: int, rescore_r: int,
+                         out_labels: torch.Tensor, out_hit: torch.Tensor, out_votes: torch.Tensor,
+                         out_nbr_idx: torch.Tensor, out_nbr_dist: torch.Tensor, stream=None) -> None:
+    assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous() and queries.dim() == 2
+    b = queries.shape[0]
+    _check(lib().freeze_lookup_static(ctx, layer, _ptr(queries), b, k, vote_threshold, rescore_r, _ptr(out_labels),
+                                      _ptr(out_hit), _ptr(out_votes), _ptr(out_nbr_idx), _ptr(out_nbr_dist),
+                                      _stream(stream)), "freeze_lookup_static")
 
 
 def freeze_cascade_workspace_bytes(ctx, layers: Sequence[int], b: int, k: int, rescore_r: int = 0) -> int:

@@ -3,6 +3,7 @@
 // every step of the look-up itself runs in the HIP kernels.
 #include "../../include/freeze.h"
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -19,7 +20,44 @@ struct freeze_ctx {
     int profiled_calls = 0;
 };
 
+// Scratch of freeze_lookup_static: the look-up's workspace for callers that cannot allocate.
+// Every GPU the library runs on holds its own copy of this array until the process ends; host
+// code never uses the array's name as an address, only what hipGetSymbolAddress returned for
+// the device in question (static_scratch_ptr).
+static __device__ __align__(256) unsigned char scratch[FREEZE_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};   // per device: address of that device's copy of `scratch`
+
+// Address of the current device's copy of `scratch`, resolved once per device with that device
+// current.  Null (and *err set) when there is no usable device.
+void *static_scratch_ptr(hipError_t *err)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *err = e;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            *err = e != hipSuccess ? e : hipErrorInvalidSymbol;
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *err = hipSuccess;
+    return g_scratch_ptr[dev];
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -507,6 +545,10 @@ int freeze_create(freeze_ctx **out, int num_layers)
         c->num_cus = prop.multiProcessorCount;
     else
         (void)hipGetLastError();   // no device: keep the MI355X default; launches will report the error
+    // set-up of freeze_lookup_static for this device (it resolves the address itself when a context
+    // is later used on another device, and reports the error there if this attempt failed)
+    hipError_t scratch_err;
+    (void)static_scratch_ptr(&scratch_err);
     *out = c;
     return FREEZE_OK;
 }
@@ -580,6 +622,26 @@ int freeze_lookup(freeze_ctx *ctx, int layer, const float *queries, int64_t b, i
     const HitRule rule{0, vote_threshold, 0.f, nullptr};
     return lookup_checked(ctx, layer, queries, b, k, rule, rescore_r, out_labels, out_hit, out_votes, out_nbr_idx,
                           out_nbr_dist, workspace, workspace_bytes, stream);
+}
+
+int freeze_lookup_static(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k, int vote_threshold,
+                         int rescore_r, int32_t *out_labels, uint8_t *out_hit, int32_t *out_votes, int32_t *out_nbr_idx,
+                         float *out_nbr_dist, void *stream)
+{
+    if (vote_threshold < 1 || vote_threshold > k) return FREEZE_EINVAL;
+    int err;
+    const LayerCache *L = get_layer(ctx, layer, &err);
+    if (!L) return err;
+    LookupShape sh;
+    if (!lookup_shape(ctx, *L, b, k, rescore_r, false, &sh)) return FREEZE_EINVAL;
+    if (sh.ws_bytes > (size_t)FREEZE_STATIC_SCRATCH_BYTES) return FREEZE_ESCRATCH;
+    if (b == 0) return FREEZE_OK;
+    hipError_t herr;
+    void *ws = static_scratch_ptr(&herr);
+    if (!ws) return FREEZE_EHIP;
+    const HitRule rule{0, vote_threshold, 0.f, nullptr};
+    return lookup_checked(ctx, layer, queries, b, k, rule, rescore_r, out_labels, out_hit, out_votes, out_nbr_idx,
+                          out_nbr_dist, ws, (size_t)FREEZE_STATIC_SCRATCH_BYTES, stream);
 }
 
 int freeze_lookup_confidence(freeze_ctx *ctx, int layer, const float *queries, int64_t b, int k, float conf_threshold,
@@ -924,6 +986,7 @@ const char *freeze_strerror(int code)
     case FREEZE_ENOTBUILT: return "layer cache not built";
     case FREEZE_EWORKSPACE: return "storage or workspace too small or misaligned";
     case FREEZE_EHIP: return "HIP runtime error";
+    case FREEZE_ESCRATCH: return "look-up needs more scratch than the library's static buffer holds";
     default: return "unknown error";
     }
 }

@@ -35,7 +35,7 @@ def test_binding_has_the_same_names():
 def test_host_side_checks_without_gpu():
     L = binding.lib()
     assert L.freeze_strerror(0) == b"ok"
-    for code in range(-5, 0):
+    for code in range(-6, 0):
         assert L.freeze_strerror(code) not in (b"ok", b"unknown error")
     h = ctypes.c_void_p()
     assert L.freeze_create(ctypes.byref(h), 0) == binding.FREEZE_EINVAL
