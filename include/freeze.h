@@ -55,11 +55,9 @@ enum {
 
 enum { FREEZE_F32 = 0, FREEZE_BF16 = 1 }; /* element type of the entries handed to freeze_cache_build */
 
-/* Largest k and largest re-scoring width accepted by the look-ups.  The bf16 matrix-core
- * pass keeps at most FREEZE_MAX_RESCORE candidates per query for the exact fp32 re-scoring;
- * candidates beyond the k-th absorb its rounding (entries whose coarse keys swap places around
- * rank k), so k stays a third below that width unless the whole cache is taken (k = n). */
-#define FREEZE_MAX_K 48
+/* Largest k and largest re-scoring width accepted by the look-ups.  The bf16 matrix-core pass
+ * keeps FREEZE_MAX_RESCORE candidates per query at most for the exact fp32 re-scoring. */
+#define FREEZE_MAX_K 64
 #define FREEZE_MAX_RESCORE 64
 
 /* Create / destroy a context with `num_layers` empty layer slots (host-only state). */
@@ -96,17 +94,22 @@ size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b
  * API: k nearest neighbours -> k (label, distance) tuples -> label with the most
  * occurrences m_i among the k -> hit decision; Pseudocode 1, FreezeInference).
  *   queries        [b, d] fp32 row-major.
- *   k              neighbours per query, 1 <= k <= min(n, FREEZE_MAX_K); k = n is also accepted up
- *                  to FREEZE_MAX_RESCORE (every entry is then a candidate).
+ *   k              neighbours per query, 1 <= k <= min(n, FREEZE_MAX_K).
  *   vote_threshold hit iff the winning label holds >= vote_threshold of the k
  *                  neighbours; 1 <= vote_threshold <= k.
  *   rescore_r      candidates per query kept by the bf16 matrix-core pass and
  *                  re-scored exactly in fp32; 0 = library default (16 for k <= 10,
  *                  32 for k <= 24, else 64), else k <= rescore_r <= FREEZE_MAX_RESCORE
- *                  (clamped to n).  The k reported neighbours are the exact nearest
- *                  among these candidates; a width close to k leaves the bf16 ranking
- *                  no slack around rank k, and the last neighbours can then differ from
- *                  the exact ones.
+ *                  (clamped to n).  The width changes the speed, never the result: after
+ *                  the re-scoring the library checks, per query, that no entry outside the
+ *                  candidates can be nearer than the k-th neighbour found (from the spread
+ *                  between coarse keys and exact distances of the candidates themselves, with
+ *                  a margin of 8 standard deviations); a query that fails the check is
+ *                  re-scored over a wider candidate set (up to 256), and if that fails too it
+ *                  is scanned against every entry in fp32 inside the same call.  A width
+ *                  close to k (or data whose bf16 keys cannot tell the neighbours apart:
+ *                  clusters far from the origin, k = R) sends more queries down those slower
+ *                  paths.
  *   out_labels     [b] int32  winning label (equal counts -> smaller label id).
  *   out_hit        [b] uint8  1 = cache hit.
  *   out_votes      [b] int32  occurrences m of the winning label.
@@ -283,6 +286,14 @@ int freeze_compact_misses(const uint8_t *hit, const int32_t *sel_in, int64_t cou
  */
 int freeze_gather_rows(const float *x, int64_t d, const int32_t *sel, const int32_t *count,
                        int64_t max_count, float *out, void *stream);
+
+/*
+ * Counters of how the look-ups of this context were confirmed (measurement aid): while a device
+ * array of three uint64 is attached, every look-up adds to it the number of queries whose result was
+ * confirmed exact after the first re-scoring [0], after the wider re-scoring [1], and the number
+ * redone by the exact scan [2].  The library never clears it.  NULL detaches.
+ */
+int freeze_lookup_stats_attach(freeze_ctx *ctx, void *counters);
 
 /*
  * Stage timing for benchmarks (measurement aid; the look-up results do not depend on it).

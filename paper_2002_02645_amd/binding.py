@@ -84,6 +84,8 @@ def lib():
     L.freeze_gather_rows.argtypes = [p, i64, p, p, i64, p, p]
     L.freeze_compute_thresholds.restype = i32
     L.freeze_compute_thresholds.argtypes = [p, i32, p, p, i64, i32, i32, p, p, p, sz, p]
+    L.freeze_lookup_stats_attach.restype = i32
+    L.freeze_lookup_stats_attach.argtypes = [p, p]
     L.freeze_profile_enable.restype = i32
     L.freeze_profile_enable.argtypes = [p, i32]
     L.freeze_profile_read.restype = i32
@@ -313,6 +315,13 @@ def freeze_compact_misses(hit: torch.Tensor, sel_in: Optional[torch.Tensor], sel
     assert hit.is_cuda and hit.dtype == torch.uint8
     _check(lib().freeze_compact_misses(_ptr(hit), _ptr(sel_in), hit.numel(), _ptr(sel_out), _ptr(out_count),
                                        _stream(stream)), "freeze_compact_misses")
+
+
+def freeze_lookup_stats_attach(ctx, counters: Optional[torch.Tensor]) -> None:
+    """counters: device tensor of three int64 (confirmed at once, after the wider re-scoring, exact scans) or None."""
+    if counters is not None:
+        assert counters.is_cuda and counters.dtype == torch.int64 and counters.numel() >= 3 and counters.is_contiguous()
+    _check(lib().freeze_lookup_stats_attach(ctx, _ptr(counters)), "freeze_lookup_stats_attach")
 
 
 def freeze_profile_enable(ctx, enable: bool) -> None:

@@ -129,10 +129,17 @@ hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t
 // of chunks, so that a batch of 256 rows still fills the chip.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, const int32_t *sel, const int32_t *count,
-                                                         int b, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf)
+                                                         int b, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf,
+                                                         int32_t *flag_count, int32_t *tickets)
 {
     const int nq = count ? *count : b;
     const int row0 = blockIdx.x * 2;   // bm is even: both rows lie in one tile
+    // counters of the kernels that follow in this look-up (the list of flagged queries, the exact
+    // scan's tickets) start at zero
+    if (blockIdx.y == 0 && threadIdx.x < 2) {
+        if (tickets && row0 + (int)threadIdx.x < b) tickets[row0 + threadIdx.x] = 0;
+        if (flag_count && blockIdx.x == 0 && threadIdx.x == 0) *flag_count = 0;
+    }
     const int live_pad = ((nq + bm - 1) / bm) * bm;
     if (row0 >= live_pad) return;
     uint4 *tile_base = reinterpret_cast<uint4 *>(q_bf + (int64_t)(row0 / bm) * bm * d_pad);
@@ -172,7 +179,8 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
 }
 
 hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
-                             int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, hipStream_t s)
+                             int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, int32_t *flag_count,
+                             int32_t *tickets, hipStream_t s)
 {
     if (bm % 2 != 0 || b_pad % 2 != 0) return hipErrorInvalidValue;
     // about 2048 blocks in all, at least four rounds of 256 chunks each
@@ -181,7 +189,7 @@ hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int
     if (ysplit > rounds / 4) ysplit = rounds / 4;
     if (ysplit < 1) ysplit = 1;
     hipLaunchKernelGGL(query_prep_kernel, dim3((unsigned)pairs, (unsigned)ysplit), dim3(256), 0, s, queries, sel, count,
-                       (int)b, bm, d, d_pad, q_bf);
+                       (int)b, bm, d, d_pad, q_bf, flag_count, tickets);
     return hipGetLastError();
 }
 
@@ -502,6 +510,62 @@ struct FinishKernelArgs {
     int sort_cap;   // power of two >= the largest number of entries gathered per query (LDS allocation)
 };
 
+// Exactness certificate of the bf16 pre-filter, by the first wave of the block (every thread
+// calls; the verdict is valid in every thread after the call).
+//
+// The m candidates ent[0 .. m) (coarse key kappa_j in the upper half) were re-scored exactly
+// (dist_s[j]); dk is the k-th smallest of those exact distances.  Every entry that was NOT
+// re-scored has a coarse key >= the float behind excl_bits (+inf or the "no entry" marker: there is
+// no such entry).
+// The coarse key is the exact distance minus |q|^2 plus an error (bf16 rounding of the query, and of
+// the entries when the cache is stored in fp32; fp32 accumulation), so e_j = kappa_j - dist_j
+// samples (error - |q|^2) on entries as near to the query as any that could have been missed.  With
+// mean and standard deviation sd of the e_j, an excluded entry has, under that error distribution,
+//     distance >= kappa_excl - mean - z sd sqrt(1 + 1/m),
+// and when this exceeds dk no excluded entry can be among the k nearest: the result is the exact
+// one.  z = kCertZ; the estimate needs kCertMinSamples samples from as many distinct distances
+// (duplicated rows repeat one sample).  Otherwise the verdict is "unconfirmed" and the caller
+// widens the candidate set or hands the query to the exact scan.
+__device__ __forceinline__ bool certificate(const uint64_t *ent, const float *dist_s, int m, float dk, uint32_t excl_bits,
+                                            int distinct, int tid, int *verdict_s)
+{
+    if (tid < 64) {
+        const double e0 = (double)from_ordered_bits((uint32_t)(ent[0] >> 32)) - (double)dist_s[0];
+        double s1 = 0.0, s2 = 0.0;
+        for (int j = tid; j < m; j += 64) {
+            const double e = ((double)from_ordered_bits((uint32_t)(ent[j] >> 32)) - (double)dist_s[j]) - e0;
+            s1 += e;
+            s2 += e * e;
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            s1 += __shfl_xor(s1, off, 64);
+            s2 += __shfl_xor(s2, off, 64);
+        }
+        if (tid == 0) {
+            int ok;
+            if (excl_bits >= 0xff800000u) {
+                ok = 1;   // nothing was left out (marker), or only padding rows (their keys are +inf)
+            } else if (m < kCertMinSamples || distinct < kCertMinSamples) {
+                ok = 0;
+            } else {
+                const double mean_rel = s1 / m;
+                double var = (s2 - m * mean_rel * mean_rel) / (m - 1);
+                var = var > 0.0 ? var : 0.0;
+                const double mean = e0 + mean_rel;
+                const double kex = (double)from_ordered_bits(excl_bits);
+                double margin = kCertZ * __builtin_sqrt(var * (1.0 + 1.0 / m));
+                const double floor_ = 4.0 * 5.9604644775390625e-8 * (__builtin_fabs(kex) + __builtin_fabs(mean) + (double)dk);
+                margin = margin > floor_ ? margin : floor_;
+                ok = (kex - mean - margin > (double)dk) ? 1 : 0;   // false for NaN
+            }
+            *verdict_s = ok;
+        }
+    }
+    __syncthreads();
+    return *verdict_s != 0;
+}
+
 // 256-thread blocks are held to four waves per SIMD, i.e. at most 128 registers: the compiler
 // would take 169 and leave two blocks per CU, too few to cover one block's merge and final
 // phases with the other blocks' re-scoring loads (0.55 -> 0.45 ms on 10,000 queries x 8,192).
@@ -511,13 +575,15 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKer
     const FinishArgs &a = fa.a;
     extern __shared__ uint64_t ent[];   // sort_cap entries (dynamic: small merges keep occupancy high)
     __shared__ float red[NT / 64][8];
-    __shared__ float dist_s[kMaxRescore];
-    __shared__ int32_t idx_s[kMaxRescore];
+    __shared__ float dist_s[kTier1];
+    __shared__ int32_t idx_s[kTier1];
     __shared__ int32_t lab_s[kMaxK];
     __shared__ int32_t cnt_s[kMaxK];
     __shared__ float dsel_s[kMaxK];
     __shared__ double conf_s[kMaxK];
     __shared__ int32_t nearest_s;
+    __shared__ int real_s, distinct_s, verdict_s;
+    __shared__ uint32_t excl_s;
 
     const int nq = a.count ? *a.count : a.b;
     const int q = blockIdx.x;
@@ -537,8 +603,36 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKer
     int sort_n = 2;
     while (sort_n < total) sort_n <<= 1;   // <= fa.sort_cap, the LDS allocation
     const uint64_t *src = a.part + (size_t)q * stride;
-    for (int i = tid; i < sort_n; i += NT) ent[i] = (i < total) ? src[i] : kSentinel;
+    if (tid == 0) {
+        real_s = 0;
+        excl_s = 0xffffffffu;
+    }
     __syncthreads();
+    int mine = 0;
+    for (int i = tid; i < sort_n; i += NT) {
+        const uint64_t x = (i < total) ? src[i] : kSentinel;
+        ent[i] = x;
+        mine += (uint32_t)x < (uint32_t)a.n;   // a real cache entry (the "no entry" marker carries index 2^32 - 1)
+    }
+    if (mine) atomicAdd(&real_s, mine);
+    __syncthreads();
+    if (!a.part_count) {
+        // Per-split lists: a split that filled its list kept its r smallest keys, so every entry
+        // of its range that it dropped has a key >= the list's largest.  The smallest of these
+        // bounds bounds every entry outside the gathered lists.  (Slots rotate with the thread
+        // number so that neighbouring threads read different LDS banks.)
+        for (int sp = tid; sp < n_splits; sp += NT) {
+            uint32_t mx = 0;
+            for (int j = 0; j < r; ++j) {
+                int jj = j + sp;
+                jj -= (jj / r) * r;
+                const uint32_t kb = (uint32_t)(ent[sp * r + jj] >> 32);
+                mx = kb > mx ? kb : mx;
+            }
+            atomicMin(&excl_s, mx);   // a list with an empty slot dropped nothing: its largest is the marker
+        }
+        __syncthreads();
+    }
     for (int size = 2; size <= sort_n; size <<= 1) {
         for (int stride2 = size >> 1; stride2 > 0; stride2 >>= 1) {
             for (int i = tid; i < (sort_n >> 1); i += NT) {
@@ -554,74 +648,120 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKer
             __syncthreads();
         }
     }
-    if (tid < r) {
-        // With finite inputs every one of the first r entries is a real cache row.  Non-finite
-        // inputs (outside the contract) can leave "no entry" markers here: map them to row 0 so
-        // that nothing is read out of bounds.
-        const uint32_t ci = (uint32_t)(ent[tid] & 0xffffffffu);
-        idx_s[tid] = ci < (uint32_t)a.n ? (int32_t)ci : 0;
-    }
-    __syncthreads();
-
-    // 2. exact fp32 re-scoring: each wave takes a group of candidates and needs no block barrier
+    const int real = real_s;   // real entries gathered: they sort in front of the markers
+    // a candidate list (keys-out selection) holds every entry up to its largest pair
+    const uint32_t excl_outside = a.part_count ? (real >= a.n || real < 1 ? 0xffffffffu : (uint32_t)(ent[real - 1] >> 32))
+                                               : excl_s;
     const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
-    if (a.d >= 4096 && a.d % 8 == 0)
-        rescore_block<NT>(a, qrow, idx_s, dist_s, red, r, tid);
-    else if (tid < 256) {   // short activations: four waves, one group of candidates each
-        if (r <= 16)
-            rescore_wave<4>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
-        else if (r <= 32)
-            rescore_wave<8>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
-        else
-            rescore_wave<16>(a, qrow, idx_s, dist_s, r, tid >> 6, tid & 63);
-    }
-    __syncthreads();
 
-    // 3. final order (dist, index) and the first k
-    if (tid < r) {
-        const float dm = dist_s[tid];
-        const int32_t im = idx_s[tid];
-        int rank = 0;
-        for (int j = 0; j < r; ++j) {
-            const float dj = dist_s[j];
-            const int32_t ij = idx_s[j];
-            rank += (dj < dm) || (dj == dm && ij < im);
+    // Two rounds at most: the r best by the coarse key, then (when the certificate does not
+    // confirm the result) up to kTier1 of the gathered entries.
+    int done = 0;   // candidates re-scored so far
+    int m = r;
+    for (int round = 0; round < 2; ++round) {
+        if (tid >= done && tid < m) {
+            // With finite inputs every one of the first r entries is a real cache row.  Non-finite
+            // inputs (outside the contract) can leave "no entry" markers here: map them to row 0 so
+            // that nothing is read out of bounds.
+            const uint32_t ci = (uint32_t)(ent[tid] & 0xffffffffu);
+            idx_s[tid] = ci < (uint32_t)a.n ? (int32_t)ci : 0;
         }
-        if (rank < a.k) {
-            a.out_nbr_idx[(int64_t)q * a.k + rank] = im;
-            a.out_nbr_dist[(int64_t)q * a.k + rank] = dm;
-            lab_s[rank] = a.labels[im];
-            dsel_s[rank] = dm;
-            if (rank == 0) nearest_s = im;
+        if (tid == 0) distinct_s = 0;
+        __syncthreads();
+
+        // 2. exact fp32 re-scoring: each wave takes a group of candidates and needs no block barrier
+        if (a.d >= 4096 && a.d % 8 == 0)
+            rescore_block<NT>(a, qrow, idx_s + done, dist_s + done, red, m - done, tid);
+        else if (tid < 256) {   // short activations: four waves, one group of candidates each
+            if (m - done <= 16)
+                rescore_wave<4>(a, qrow, idx_s + done, dist_s + done, m - done, tid >> 6, tid & 63);
+            else if (m - done <= 32)
+                rescore_wave<8>(a, qrow, idx_s + done, dist_s + done, m - done, tid >> 6, tid & 63);
+            else
+                rescore_wave<16>(a, qrow, idx_s + done, dist_s + done, m - done, tid >> 6, tid & 63);
         }
+        __syncthreads();
+
+        // 3. final order (dist, index) and the first k
+        for (int c = tid; c < m; c += NT) {
+            const float dm = dist_s[c];
+            const int32_t im = idx_s[c];
+            int rank = 0, twin = 0;
+            for (int j = 0; j < m; ++j) {
+                const float dj = dist_s[j];
+                const int32_t ij = idx_s[j];
+                rank += (dj < dm) || (dj == dm && ij < im);
+                twin |= (dj == dm && ij < im);
+            }
+            if (!twin) atomicAdd(&distinct_s, 1);
+            if (rank < a.k) {
+                a.out_nbr_idx[(int64_t)q * a.k + rank] = im;
+                a.out_nbr_dist[(int64_t)q * a.k + rank] = dm;
+                lab_s[rank] = a.labels[im];
+                dsel_s[rank] = dm;
+                if (rank == 0) nearest_s = im;
+            }
+        }
+        __syncthreads();
+        done = m;
+
+        // the certificate: is any entry that was not re-scored possibly nearer than the k-th?
+        uint32_t excl = excl_outside;
+        if (real > m) {
+            const uint32_t nxt = (uint32_t)(ent[m] >> 32);
+            excl = nxt < excl ? nxt : excl;
+        }
+        const bool ok = certificate(ent, dist_s, m, dsel_s[a.k - 1], excl, distinct_s, tid, &verdict_s);
+        if (ok) {
+            if (a.stats && tid == 0) atomicAdd(a.stats + round, 1ull);
+            break;
+        }
+        const int wider = real < kTier1 ? real : kTier1;
+        if (round == 1 || wider <= m) {
+            // unconfirmed: the exact scan redoes this query (the outputs written below stand until then)
+            if (tid == 0) {
+                const int pos = atomicAdd(a.flag_count, 1);
+                a.flag_list[pos] = q;
+                if (a.stats) atomicAdd(a.stats + 2, 1ull);
+            }
+            break;
+        }
+        m = wider;
+        __syncthreads();   // verdict_s, distinct_s and the lists are rewritten by the next round
     }
-    __syncthreads();
 
     // 4. vote and hit decision
     decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s, nearest_s);
 }
 
 // ---------------------------------------------------------------------------------------
-// Finishing kernels of the small-batch path (short activations, at most 16 queries), from the
-// block minima alone:
-//  1. skinny_select_kernel (one workgroup per query): T = the R-th smallest block minimum; the R
-//     blocks whose minimum is <= T hold every entry that is <= T, hence the R best by the
-//     coarse key.  It starts from the per-workgroup minima of the streaming kernel, so it reads
-//     only the block minima of the R groups that can matter.
-//  2. skinny_rescore_kernel (one workgroup per pair of selected blocks and query: the work
-//     would take one CU tens of microseconds): exact fp32 re-scoring of the 64 entries (same
-//     arithmetic as above), then a wave-local sort that passes on the `keep` nearest.
-//  3. skinny_final_kernel (one workgroup per query): the k nearest by (distance, index) of what
-//     was passed on, then the label and hit decision.
+// Finishing kernel of the small-batch path (short activations, at most 16 queries), from the
+// block minima alone.  One launch, grid (pairs of blocks, queries), 1024 threads:
+//  1. selection (every workgroup of a query repeats it: a few thousand L2-resident reads): T =
+//     the R-th smallest block minimum; the R blocks whose minimum is <= T hold every entry that is
+//     <= T, hence the R best by the coarse key.  It starts from the per-workgroup minima of the
+//     streaming kernel, so only the block minima of the R groups that can matter are read.  The
+//     selected blocks are put in ascending order of their minima, the same in every workgroup.
+//  2. workgroup x re-scores blocks 2 x and 2 x + 1 of that order exactly in fp32 (64 entries, the
+//     same arithmetic as above), sorts them in one wave and leaves the `keep` nearest, and for
+//     each block the (coarse key, exact distance) of its minimum entry: samples of the coarse
+//     key's error for the certificate.
+//  3. the last workgroup of a query to arrive (a ticket per query) takes the k nearest by
+//     (distance, index) of what was left, decides label and hit, and checks the certificate:
+//     every entry outside the selected blocks has a coarse key >= T.  Unconfirmed queries go on
+//     the list of the exact scan.
 // ---------------------------------------------------------------------------------------
-struct SkinnySelectArgs {
+struct SkinnyTailArgs {
+    FinishArgs a;            // queries, cache rows, n, d, d_pad, outputs, flag list (a.r = blocks to take)
     const uint64_t *bmin;    // [b, nb] smallest (ordered key, index) of every block of 32 entries
     const uint64_t *wgmin;   // [b, n_groups] smallest value of each group of blocks
     int64_t nb;
     int n_groups, n_tiles;   // group j = the blocks of cache tiles [j n_tiles / n_groups, (j+1) n_tiles / n_groups)
-    int r;                   // blocks to take
-    int32_t *blocks;         // [b, kMaxRescore] out: the selected blocks
-    int32_t *nblk;           // [b] out: how many
+    uint64_t *cand;          // [b, pairs * keep] packed (ordered distance, index), marker-padded
+    uint64_t *samp;          // [b, 2 pairs] (coarse key bits << 32 | distance bits) of each block's minimum entry
+    int32_t *tickets;        // [b], zero on entry (the streaming kernel clears them); left zero
+    int keep;                // entries each workgroup passes on (<= 64)
+    int pairs;               // workgroups per query
 };
 
 // The R-th smallest of list[0..cnt) (distinct values), cnt <= kThrList, by the whole workgroup.
@@ -640,164 +780,165 @@ __device__ inline uint64_t rth_of_list(uint64_t *list, int cnt, int r_sel, uint6
     return list[r_sel - 1];
 }
 
-__global__ __launch_bounds__(kThrThreads) void skinny_select_kernel(SkinnySelectArgs sa)
+__global__ __launch_bounds__(kThrThreads) void skinny_tail_kernel(SkinnyTailArgs sa)
 {
+    const FinishArgs &a = sa.a;
     __shared__ uint64_t list[kThrList];
     __shared__ uint64_t gm_s[kThrThreads];
+    __shared__ uint64_t pick_s[kMaxRescore];   // minima (pairs) of the selected blocks, ascending
     __shared__ uint64_t sel_s;
-    __shared__ int list_n, blk_n, grp_n;
+    __shared__ int list_n, blk_n, grp_n, last_s, distinct_s, verdict_s;
     __shared__ int32_t grp_s[kMaxRescore];
-    const int q = blockIdx.x, tid = threadIdx.x;
-    const int64_t nb = sa.nb;
-    const int r = sa.r;
-    int32_t *blk = sa.blocks + (size_t)q * kMaxRescore;
-    if (r >= nb) {   // fewer blocks than wanted: take them all
-        if (tid < (int)nb) blk[tid] = tid;
-        if (tid == 0) sa.nblk[q] = (int)nb;
-        return;
-    }
-    // 1a. the groups that can hold one of the r smallest block minima: those whose own minimum
-    //     is among the r smallest group minima (T1 = the r-th of them bounds the answer above)
-    const int ng = sa.n_groups;
-    if (tid == 0) {
-        list_n = 0;
-        blk_n = 0;
-        grp_n = 0;
-    }
-    const uint64_t my_gm = tid < ng ? sa.wgmin[(size_t)q * ng + tid] : kSentinel;
-    gm_s[tid] = my_gm;
-    __syncthreads();
-    uint64_t t1 = kSentinel;
-    if (r < ng) {
-        if (r <= 32) {
-            t1 = smallest_sorted(gm_s, list, ng, r, tid, kThrThreads)[r - 1];
-        } else {
-            select_by_rank_counting(gm_s, ng, r - 1, tid, &sel_s);
-            __syncthreads();
-            t1 = sel_s;
-        }
-        __syncthreads();
-    }
-    if (tid < ng && my_gm <= t1) {
-        const int pos = atomicAdd(&grp_n, 1);
-        if (pos < kMaxRescore) grp_s[pos] = tid;
-    }
-    __syncthreads();
-    const int ngrp = grp_n < kMaxRescore ? grp_n : kMaxRescore;   // min(r, ng) groups
-    // 1b. gather their block minima <= T1: at least r, at most r * (blocks per group)
-    const int bpg = ((sa.n_tiles + ng - 1) / ng) * (kTileN / 32);
-    const uint64_t *src = sa.bmin + (size_t)q * nb;
-    for (int c = tid; c < ngrp * bpg; c += kThrThreads) {
-        const int gidx = grp_s[c / bpg];
-        const int64_t b0 = ((int64_t)gidx * sa.n_tiles / ng) * (kTileN / 32);
-        const int64_t b1 = ((int64_t)(gidx + 1) * sa.n_tiles / ng) * (kTileN / 32);
-        const int64_t bi = b0 + c % bpg;
-        if (bi < b1) {
-            const uint64_t x = src[bi];
-            if (x <= t1) {
-                const int pos = atomicAdd(&list_n, 1);
-                if (pos < kThrList) list[pos] = x;
-            }
-        }
-    }
-    __syncthreads();
-    const int cnt = list_n < kThrList ? list_n : kThrList;
-    // 1c. the r smallest of them are the minima of the blocks to take (distinct values)
-    if (r <= 32 && cnt <= kThrList / 2) {
-        const uint64_t *res = smallest_sorted(list, list + kThrList / 2, cnt, r, tid, kThrThreads);
-        if (tid < r) blk[tid] = (int32_t)((uint32_t)res[tid] >> 5);   // block of the minimum's entry
-        if (tid == 0) sa.nblk[q] = r;
-    } else {
-        const uint64_t t = rth_of_list(list, cnt, r, &sel_s, tid);
-        __syncthreads();
-        for (int i = tid; i < cnt; i += kThrThreads) {
-            const uint64_t x = list[i];
-            if (x <= t) {
-                const int pos = atomicAdd(&blk_n, 1);
-                if (pos < kMaxRescore) blk[pos] = (int32_t)((uint32_t)x >> 5);
-            }
-        }
-        __syncthreads();
-        if (tid == 0) sa.nblk[q] = blk_n < r ? blk_n : r;
-    }
-}
-
-struct SkinnyRescoreArgs {
-    FinishArgs a;             // queries, cache rows, n, d, d_pad
-    const int32_t *blocks;    // [b, kMaxRescore]
-    const int32_t *nblk;      // [b]
-    uint64_t *cand;           // [b, pairs * keep] out: packed (ordered distance, index), sentinel-padded
-    int keep;                 // entries each workgroup passes on (<= 64)
-    int pairs;                // workgroups per query
-};
-
-// grid (pairs, b), 256 threads: blocks 2 x and 2 x + 1 of the query's selection
-__global__ __launch_bounds__(256) void skinny_rescore_kernel(SkinnyRescoreArgs ra)
-{
-    const FinishArgs &a = ra.a;
-    __shared__ int32_t idx_s[64];
-    __shared__ int32_t row_s[64];
+    __shared__ int32_t idx_s[64], row_s[64];
     __shared__ float dist_s[64];
-    const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
-    const int nblk = ra.nblk[q];
-    uint64_t *out = ra.cand + ((size_t)q * ra.pairs + blockIdx.x) * ra.keep;
-    const int first = blockIdx.x * 2;
-    const int here = nblk - first < 2 ? nblk - first : 2;   // blocks of this workgroup
-    if (here <= 0) {
-        if (tid < ra.keep) out[tid] = kSentinel;
-        return;
-    }
-    const int m = here * 32;
-    // entries past the cache (padding rows of the last tile) are re-scored as row 0 and dropped below
-    if (tid < m) {
-        const int e = ra.blocks[(size_t)q * kMaxRescore + first + (tid >> 5)] * 32 + (tid & 31);
-        idx_s[tid] = e < a.n ? e : -1 - e;
-    }
-    __syncthreads();
-    if (tid < m) row_s[tid] = idx_s[tid] < 0 ? 0 : idx_s[tid];
-    __syncthreads();
-    const float *qrow = a.queries + (int64_t)q * a.d;
-    if (a.d % 8 != 0)
-        rescore_wave<4>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);
-    else if (a.c_f32)
-        rescore_short<4, true>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);
-    else
-        rescore_short<16, false>(a, qrow, row_s, dist_s, m, tid >> 6, lane, 4);   // every row of the pair in one round of loads
-    __syncthreads();
-    if (tid < 64) {
-        uint64_t x = kSentinel;
-        if (tid < m && idx_s[tid] >= 0) x = ((uint64_t)ordered_bits(dist_s[tid]) << 32) | (uint32_t)idx_s[tid];
-        x = wave_sort64(x, lane);
-        if (lane < ra.keep) out[lane] = x;
-    }
-}
-
-struct SkinnyFinalArgs {
-    FinishArgs a;
-    const uint64_t *cand;   // [b, count]
-    int count;              // <= kThrList / 2
-};
-
-__global__ __launch_bounds__(kThrThreads) void skinny_final_kernel(SkinnyFinalArgs fa)
-{
-    const FinishArgs &a = fa.a;
-    __shared__ uint64_t list[kThrList];
-    __shared__ int32_t lab_s[kMaxK];
-    __shared__ int32_t cnt_s[kMaxK];
+    __shared__ int32_t lab_s[kMaxK], cnt_s[kMaxK];
     __shared__ float dsel_s[kMaxK];
     __shared__ double conf_s[kMaxK];
     __shared__ int32_t nearest_s;
-    const int q = blockIdx.x, tid = threadIdx.x;
-    const int m = fa.count;
-    for (int c = tid; c < m; c += kThrThreads) list[c] = fa.cand[(size_t)q * m + c];
+    const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int64_t nb = sa.nb;
+    const int r = a.r;
+
+    // ---- 1. selection ----
+    int nblk;
+    if (r >= nb) {   // fewer blocks than wanted: take them all, in index order
+        if (tid < (int)nb) pick_s[tid] = sa.bmin[(size_t)q * nb + tid];
+        nblk = (int)nb;
+        __syncthreads();
+    } else {
+        // 1a. the groups that can hold one of the r smallest block minima: those whose own minimum
+        //     is among the r smallest group minima (T1 = the r-th of them bounds the answer above)
+        const int ng = sa.n_groups;
+        if (tid == 0) {
+            list_n = 0;
+            blk_n = 0;
+            grp_n = 0;
+        }
+        const uint64_t my_gm = tid < ng ? sa.wgmin[(size_t)q * ng + tid] : kSentinel;
+        gm_s[tid] = my_gm;
+        __syncthreads();
+        uint64_t t1 = kSentinel;
+        if (r < ng) {
+            if (r <= 32) {
+                t1 = smallest_sorted(gm_s, list, ng, r, tid, kThrThreads)[r - 1];
+            } else {
+                select_by_rank_counting(gm_s, ng, r - 1, tid, &sel_s);
+                __syncthreads();
+                t1 = sel_s;
+            }
+            __syncthreads();
+        }
+        if (tid < ng && my_gm <= t1) {
+            const int pos = atomicAdd(&grp_n, 1);
+            if (pos < kMaxRescore) grp_s[pos] = tid;
+        }
+        __syncthreads();
+        const int ngrp = grp_n < kMaxRescore ? grp_n : kMaxRescore;   // min(r, ng) groups
+        // 1b. gather their block minima <= T1: at least r, at most r * (blocks per group)
+        const int bpg = ((sa.n_tiles + ng - 1) / ng) * (kTileN / 32);
+        const uint64_t *src = sa.bmin + (size_t)q * nb;
+        for (int c = tid; c < ngrp * bpg; c += kThrThreads) {
+            const int gidx = grp_s[c / bpg];
+            const int64_t b0 = ((int64_t)gidx * sa.n_tiles / ng) * (kTileN / 32);
+            const int64_t b1 = ((int64_t)(gidx + 1) * sa.n_tiles / ng) * (kTileN / 32);
+            const int64_t bi = b0 + c % bpg;
+            if (bi < b1) {
+                const uint64_t x = src[bi];
+                if (x <= t1) {
+                    const int pos = atomicAdd(&list_n, 1);
+                    if (pos < kThrList) list[pos] = x;
+                }
+            }
+        }
+        __syncthreads();
+        const int cnt = list_n < kThrList ? list_n : kThrList;
+        // 1c. the r smallest of them, ascending, are the minima of the blocks to take (distinct values)
+        if (r <= 32 && cnt <= kThrList / 2) {
+            const uint64_t *res = smallest_sorted(list, list + kThrList / 2, cnt, r, tid, kThrThreads);
+            if (tid < r) pick_s[tid] = res[tid];
+        } else {
+            const uint64_t t = rth_of_list(list, cnt, r, &sel_s, tid);
+            __syncthreads();
+            for (int i = tid; i < cnt; i += kThrThreads) {
+                const uint64_t x = list[i];
+                if (x <= t) {
+                    const int pos = atomicAdd(&blk_n, 1);
+                    if (pos < kMaxRescore) pick_s[pos] = x;
+                }
+            }
+            __syncthreads();
+            if (tid < 64) {   // exactly r <= 64 values: one wave puts them in order
+                const uint64_t v = wave_sort64(lane < r ? pick_s[lane] : kSentinel, lane);
+                if (lane < r) pick_s[lane] = v;
+            }
+        }
+        nblk = r;
+        __syncthreads();
+    }
+
+    // ---- 2. exact re-scoring of this workgroup's two blocks ----
+    uint64_t *out = sa.cand + ((size_t)q * sa.pairs + blockIdx.x) * sa.keep;
+    uint64_t *samp = sa.samp + (size_t)q * 2 * sa.pairs + 2 * blockIdx.x;
+    const int first = blockIdx.x * 2;
+    const int here = nblk - first < 2 ? nblk - first : 2;   // blocks of this workgroup
+    if (here <= 0) {
+        if (tid < sa.keep) out[tid] = kSentinel;
+        if (tid < 2) samp[tid] = kSentinel;
+    } else {
+        const int m = here * 32;
+        // entries past the cache (padding rows of the last tile) are re-scored as row 0 and dropped below
+        if (tid < m) {
+            const int e = (int)((uint32_t)pick_s[first + (tid >> 5)] >> 5) * 32 + (tid & 31);
+            idx_s[tid] = e < a.n ? e : -1 - e;
+            row_s[tid] = e < a.n ? e : 0;
+        }
+        __syncthreads();
+        const float *qrow = a.queries + (int64_t)q * a.d;
+        if (a.d % 8 != 0)
+            rescore_wave<4>(a, qrow, row_s, dist_s, m, tid >> 6, lane, kThrThreads / 64);
+        else if (a.c_f32)
+            rescore_short<4, true>(a, qrow, row_s, dist_s, m, tid >> 6, lane, kThrThreads / 64);
+        else
+            rescore_short<4, false>(a, qrow, row_s, dist_s, m, tid >> 6, lane, kThrThreads / 64);
+        __syncthreads();
+        if (tid < 64) {
+            uint64_t x = kSentinel;
+            if (tid < m && idx_s[tid] >= 0) x = ((uint64_t)ordered_bits(dist_s[tid]) << 32) | (uint32_t)idx_s[tid];
+            x = wave_sort64(x, lane);
+            if (lane < sa.keep) out[lane] = x;
+        } else if (tid < 66) {
+            const int hb = tid - 64;
+            uint64_t sv = kSentinel;
+            if (hb < here) {
+                const uint64_t pr = pick_s[first + hb];   // (coarse key, index) of the block's minimum entry
+                sv = (pr & 0xffffffff00000000ull) | __float_as_uint(dist_s[hb * 32 + ((uint32_t)pr & 31u)]);
+            }
+            samp[hb] = sv;
+        }
+    }
+
+    // ---- 3. the last workgroup of the query finishes it ----
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) last_s = (atomicAdd(&sa.tickets[q], 1) == sa.pairs - 1);
+    __syncthreads();
+    if (!last_s) return;   // uniform
+    __threadfence();
+    const int mcand = sa.pairs * sa.keep;   // <= kThrList / 2
+    for (int c = tid; c < mcand; c += kThrThreads)
+        list[c] = __hip_atomic_load(sa.cand + (size_t)q * mcand + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+        sa.tickets[q] = 0;
+        distinct_s = 0;
+    }
     __syncthreads();
     const uint64_t *res;
     if (a.k <= 32) {
-        res = smallest_sorted(list, list + kThrList / 2, m, a.k, tid, kThrThreads);
+        res = smallest_sorted(list, list + kThrList / 2, mcand, a.k, tid, kThrThreads);
     } else {
         int n2 = 2;
-        while (n2 < m) n2 <<= 1;
-        for (int c = m + tid; c < n2; c += kThrThreads) list[c] = kSentinel;
+        while (n2 < mcand) n2 <<= 1;
+        for (int c = mcand + tid; c < n2; c += kThrThreads) list[c] = kSentinel;
         __syncthreads();
         bitonic_sort_lds(list, n2, tid, kThrThreads);
         res = list;
@@ -814,6 +955,28 @@ __global__ __launch_bounds__(kThrThreads) void skinny_final_kernel(SkinnyFinalAr
         if (tid == 0) nearest_s = im;
     }
     __syncthreads();
+    // certificate from the block minima: gm_s = the samples' coarse keys (upper halves), dist_s = their distances
+    if (tid < nblk) {
+        const uint64_t sv = __hip_atomic_load(sa.samp + (size_t)q * 2 * sa.pairs + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        gm_s[tid] = sv & 0xffffffff00000000ull;
+        dist_s[tid] = __uint_as_float((uint32_t)sv);
+    }
+    __syncthreads();
+    if (tid < nblk) {
+        int twin = 0;
+        for (int j = 0; j < tid; ++j) twin |= (dist_s[j] == dist_s[tid]);
+        if (!twin) atomicAdd(&distinct_s, 1);
+    }
+    __syncthreads();
+    const uint32_t excl = r >= nb ? 0xffffffffu : (uint32_t)(pick_s[nblk - 1] >> 32);
+    const bool ok = certificate(gm_s, dist_s, nblk, dsel_s[a.k - 1], excl, distinct_s, tid, &verdict_s);
+    if (tid == 0) {
+        if (!ok) {
+            const int pos = atomicAdd(a.flag_count, 1);
+            a.flag_list[pos] = q;
+        }
+        if (a.stats) atomicAdd(a.stats + (ok ? 0 : 2), 1ull);
+    }
     decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s, nearest_s);
 }
 
@@ -821,29 +984,22 @@ size_t skinny_finish_workspace_bytes(int r, size_t align)
 {
     auto up = [&](size_t x) { return (x + align - 1) / align * align; };
     const size_t pairs = (size_t)(r + 1) / 2;
-    return up((size_t)kSkinnyRows * kMaxRescore * 4) + up((size_t)kSkinnyRows * 4) + up((size_t)kSkinnyRows * pairs * 64 * 8);
+    return up((size_t)kSkinnyRows * pairs * 64 * 8) + up((size_t)kSkinnyRows * pairs * 2 * 8);
 }
 
 hipError_t launch_skinny_finish(const FinishArgs &a, const uint64_t *bmin, const uint64_t *wgmin, int64_t nb,
-                                int n_groups, int n_tiles, int32_t *blocks, int32_t *nblk, uint64_t *cand, hipStream_t s)
+                                int n_groups, int n_tiles, uint64_t *cand, uint64_t *samp, int32_t *tickets, hipStream_t s)
 {
     if (a.r < 1 || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r || a.b < 1 || a.b > kSkinnyRows || a.sel || a.count)
         return hipErrorInvalidValue;
     if (n_groups < 1 || n_groups > kThrThreads || n_groups > n_tiles) return hipErrorInvalidValue;
+    if (!a.flag_count || !a.flag_list || !tickets) return hipErrorInvalidValue;
     const int64_t bpg = ((int64_t)(n_tiles + n_groups - 1) / n_groups) * (kTileN / 32);
     if (a.r < nb && bpg * a.r > kThrList) return hipErrorInvalidValue;
-    SkinnySelectArgs sa{bmin, wgmin, nb, n_groups, n_tiles, a.r, blocks, nblk};
-    hipLaunchKernelGGL(skinny_select_kernel, dim3((unsigned)a.b), dim3(kThrThreads), 0, s, sa);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     const int pairs = (a.r + 1) / 2;   // a.r >= the number of blocks selected
     const int keep = a.k <= 32 ? a.k : 64;
-    SkinnyRescoreArgs ra{a, blocks, nblk, cand, keep, pairs};
-    hipLaunchKernelGGL(skinny_rescore_kernel, dim3((unsigned)pairs, (unsigned)a.b), dim3(256), 0, s, ra);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    SkinnyFinalArgs fa{a, cand, pairs * keep};
-    hipLaunchKernelGGL(skinny_final_kernel, dim3((unsigned)a.b), dim3(kThrThreads), 0, s, fa);
+    SkinnyTailArgs ta{a, bmin, wgmin, nb, n_groups, n_tiles, cand, samp, tickets, keep, pairs};
+    hipLaunchKernelGGL(skinny_tail_kernel, dim3((unsigned)pairs, (unsigned)a.b), dim3(kThrThreads), 0, s, ta);
     return hipGetLastError();
 }
 
@@ -851,6 +1007,7 @@ hipError_t launch_finish(const FinishArgs &a, hipStream_t s)
 {
     const int total = a.part_count ? a.part_stride : a.alloc_splits * a.r;
     if (total > kMaxMergeEntries || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r) return hipErrorInvalidValue;
+    if (!a.flag_count || !a.flag_list) return hipErrorInvalidValue;
     FinishKernelArgs fa{a, 2};
     while (fa.sort_cap < total) fa.sort_cap <<= 1;
     // a block per query: with few queries and long activations use 1024-thread blocks
@@ -860,6 +1017,139 @@ hipError_t launch_finish(const FinishArgs &a, hipStream_t s)
     else
         hipLaunchKernelGGL(finish_kernel<256>, dim3((unsigned)a.b), dim3(256), (size_t)fa.sort_cap * sizeof(uint64_t), s,
                            fa);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Exact scan of the queries whose result the certificate did not confirm (Sec. 3: the look-up
+// returns THE k nearest neighbours): brute-force fp32 distances sum (q_i - c_i)^2 to every
+// stored entry, the same arithmetic as the re-scoring above, no bf16 anywhere.  A fixed grid of
+// workgroups shares the flagged queries: with nf of them, each is cut into S = grid / nf
+// ranges of entries (at least one, at most max_splits); a workgroup scans its range 256 entries
+// at a time and keeps the k nearest by (distance, index); the last workgroup of a query to finish
+// (a ticket per query) merges the S lists and writes the neighbours, the label and the hit
+// decision over that query's outputs.  Nothing is flagged on the paper's kind of data, and then
+// the kernel reads one counter and returns.
+// ---------------------------------------------------------------------------------------
+struct ScanArgs {
+    FinishArgs a;
+    int32_t *tickets;    // [b], zero on entry; left zero
+    uint64_t *part_x;    // [items, k] the k nearest of each (query, range), packed (ordered distance, index)
+    int max_splits;
+};
+
+__global__ __launch_bounds__(256) void exact_scan_kernel(ScanArgs sa)
+{
+    const FinishArgs &a = sa.a;
+    extern __shared__ uint64_t ent[];   // >= 512 entries and >= max_splits * k
+    __shared__ float red[4][8];
+    __shared__ float dist_s[256];
+    __shared__ int32_t idx_s[256];
+    __shared__ uint64_t best_s[kMaxK];
+    __shared__ int32_t lab_s[kMaxK];
+    __shared__ int32_t cnt_s[kMaxK];
+    __shared__ float dsel_s[kMaxK];
+    __shared__ double conf_s[kMaxK];
+    __shared__ int32_t nearest_s;
+    __shared__ int surv_s, last_s;
+
+    const int nf = *a.flag_count;
+    if (nf <= 0) return;   // the usual case
+    const int tid = threadIdx.x;
+    const int grid = (int)gridDim.x, k = a.k;
+    int S = grid / nf;
+    const int by_size = (a.n + 255) / 256;   // a range holds at least one 256-entry chunk
+    S = S > sa.max_splits ? sa.max_splits : S;
+    S = S > by_size ? by_size : S;
+    S = S < 1 ? 1 : S;
+    const int64_t items = (int64_t)nf * S;
+    for (int64_t item = blockIdx.x; item < items; item += grid) {
+        const int j = (int)(item / S), sp = (int)(item - (int64_t)j * S);
+        const int q = a.flag_list[j];
+        const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
+        const int row0 = (int)((int64_t)a.n * sp / S), row1 = (int)((int64_t)a.n * (sp + 1) / S);
+        if (tid < kMaxK) best_s[tid] = kSentinel;
+        __syncthreads();
+        for (int base = row0; base < row1; base += 256) {
+            const int m = row1 - base < 256 ? row1 - base : 256;
+            if (tid < m) idx_s[tid] = base + tid;
+            if (tid == 0) surv_s = 0;
+            __syncthreads();
+            if (a.d >= 4096 && a.d % 8 == 0)
+                rescore_block<256>(a, qrow, idx_s, dist_s, red, m, tid);
+            else
+                rescore_wave<16>(a, qrow, idx_s, dist_s, m, tid >> 6, tid & 63);
+            __syncthreads();
+            // entries that beat the k-th best so far, then the k best of those and the list
+            const uint64_t tau = best_s[k - 1];
+            if (tid < m) {
+                const uint64_t x = ((uint64_t)ordered_bits(dist_s[tid]) << 32) | (uint32_t)(base + tid);
+                if (x < tau) ent[atomicAdd(&surv_s, 1)] = x;
+            }
+            __syncthreads();
+            const int c = surv_s;
+            if (c > 0) {   // uniform
+                int n2 = 2;
+                while (n2 < c + k) n2 <<= 1;   // <= 512
+                for (int i = c + tid; i < n2; i += 256) ent[i] = i < c + k ? best_s[i - c] : kSentinel;
+                __syncthreads();
+                bitonic_sort_lds(ent, n2, tid, 256);
+                if (tid < k) best_s[tid] = ent[tid];
+                __syncthreads();
+            }
+        }
+        if (tid < k) sa.part_x[(size_t)item * k + tid] = best_s[tid];
+        __threadfence();   // the list is visible to the whole device before the ticket is taken
+        __syncthreads();
+        if (tid == 0) last_s = (atomicAdd(&sa.tickets[j], 1) == S - 1);
+        __syncthreads();
+        if (last_s) {   // uniform: this workgroup finished the query's last range
+            __threadfence();
+            const int total = S * k;
+            int n2 = 2;
+            while (n2 < total) n2 <<= 1;
+            const uint64_t *src = sa.part_x + (size_t)j * S * k;
+            for (int i = tid; i < n2; i += 256)
+                ent[i] = i < total ? __hip_atomic_load(src + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : kSentinel;
+            __syncthreads();
+            bitonic_sort_lds(ent, n2, tid, 256);
+            if (tid < k) {
+                const uint64_t x = ent[tid];
+                const int32_t im = (uint32_t)x < (uint32_t)a.n ? (int32_t)(uint32_t)x : 0;   // (non-finite inputs only)
+                const float dm = from_ordered_bits((uint32_t)(x >> 32));
+                a.out_nbr_idx[(int64_t)q * k + tid] = im;
+                a.out_nbr_dist[(int64_t)q * k + tid] = dm;
+                lab_s[tid] = a.labels[im];
+                dsel_s[tid] = dm;
+                if (tid == 0) {
+                    nearest_s = im;
+                    sa.tickets[j] = 0;
+                }
+            }
+            __syncthreads();
+            decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s, nearest_s);
+        }
+        __syncthreads();
+    }
+}
+
+static int scan_max_splits(int k) { return kMaxMergeEntries / k < kScanMaxSplits ? kMaxMergeEntries / k : kScanMaxSplits; }
+static int scan_grid(int num_cus) { return 2 * num_cus; }
+
+size_t scan_scratch_entries(int64_t b, int k, int num_cus)
+{
+    // items = flagged queries x ranges <= max(b, grid)
+    const int64_t items = b > scan_grid(num_cus) ? b : scan_grid(num_cus);
+    return (size_t)items * (size_t)k;
+}
+
+hipError_t launch_exact_scan(const FinishArgs &a, int32_t *tickets, uint64_t *part_x, int num_cus, hipStream_t s)
+{
+    if (!a.flag_count || !a.flag_list || !tickets || !part_x || a.k < 1 || a.k > kMaxK) return hipErrorInvalidValue;
+    ScanArgs sa{a, tickets, part_x, scan_max_splits(a.k)};
+    int cap = 512;
+    while (cap < sa.max_splits * a.k) cap <<= 1;
+    hipLaunchKernelGGL(exact_scan_kernel, dim3((unsigned)scan_grid(num_cus)), dim3(256), (size_t)cap * sizeof(uint64_t), s, sa);
     return hipGetLastError();
 }
 

@@ -87,6 +87,8 @@ struct SkinnyArgs {
     const float *norm;
     uint64_t *bmin;         // [b, n_pad / 32] smallest (ordered key, index) of each block of 32 entries
     uint64_t *wgmin;        // [b, n_splits] smallest of the block minima each workgroup wrote
+    int32_t *flag_count;    // cleared here for the finishing kernels: the count of flagged queries ...
+    int32_t *tickets;       // ... and 2 * kSkinnyRows tickets
     int b, d_pad, n_tiles, n_splits;
     int64_t n_pad;
 };
@@ -127,6 +129,10 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
                             smem_base + NORMS + ((t & 1) * 8 + w) * 256);
     };
 
+    if (sp == 0 && tid < 2 * kSkinnyRows + 1) {
+        if (tid < 2 * kSkinnyRows) p.tickets[tid] = 0;
+        else *p.flag_count = 0;
+    }
     // the stream starts before the queries are converted: its first stages are on their way meanwhile
     if (total > 0) issue_norms(nt0);
 #pragma unroll
@@ -343,6 +349,7 @@ size_t skinny_workspace_bytes(int64_t n_pad, int r, size_t align)
 
 hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
 {
+    if (!a.flag_count || !a.tickets) return hipErrorInvalidValue;
     if (!a.queries || a.d < 1 || a.d > a.d_pad || a.d_pad > kSkinnyMaxD || a.d_pad % kPadD != 0 || a.r < 1 || a.r > kMaxRescore || a.b < 1 || a.b > kSkinnyRows)
         return hipErrorInvalidValue;
     SkinnyArgs k{};
@@ -352,6 +359,8 @@ hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
     k.norm = a.norm;
     k.bmin = a.bmin;
     k.wgmin = a.wgmin;
+    k.flag_count = a.flag_count;
+    k.tickets = a.tickets;
     k.b = a.b;
     k.d_pad = a.d_pad;
     k.n_pad = a.n_pad;

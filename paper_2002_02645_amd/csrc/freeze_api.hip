@@ -18,6 +18,7 @@ struct freeze_ctx {
     bool profile = false;
     std::vector<hipEvent_t> events;
     int profiled_calls = 0;
+    unsigned long long *stats = nullptr;   // device counters of the certificate's verdicts, or null
 };
 
 // Scratch of freeze_lookup_static: the look-up's workspace for callers that cannot allocate.
@@ -125,6 +126,10 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     if ((int64_t)r > L.n) r = (int)L.n;
     out->r = r;
     out->cascade = cascade;
+    // list and count of the queries the certificate flags, the exact scan's tickets and lists
+    const size_t bb = (size_t)(b > 0 ? b : 1);
+    const size_t scan_bytes = align_up(4) + 2 * align_up((bb > 2 * kSkinnyRows ? bb : 2 * kSkinnyRows) * 4) +
+                              align_up(scan_scratch_entries(b, k, ctx->num_cus) * 8);
     out->skinny = !cascade && skinny_supported(b, L.n_pad, L.d_pad, r, ctx->num_cus);
     out->keys = false;
     if (out->skinny) {
@@ -137,7 +142,7 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
         pl.n_splits = plan_skinny_splits(L.n, ctx->num_cus);
         pl.b_pad = kSkinnyRows;
         out->plan = pl;
-        out->ws_bytes = align_up((size_t)pl.b_pad * L.d_pad * 2) + skinny_workspace_bytes(L.n_pad, r, kAlign);
+        out->ws_bytes = align_up((size_t)pl.b_pad * L.d_pad * 2) + skinny_workspace_bytes(L.n_pad, r, kAlign) + scan_bytes;
     } else {
         // One query tile and a long activation: materialising the keys (4 B per entry and query)
         // is cheap next to the cache stream (2 d B per entry), lets the tile be 256 queries wide for
@@ -154,6 +159,7 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
                              align_up(dist_partial_bytes(out->plan));
         else
             out->ws_bytes += align_up((size_t)out->plan.b_pad * lists_per_query(out->plan, cascade) * r * 8);
+        out->ws_bytes += scan_bytes;
     }
     return true;
 }
@@ -221,20 +227,25 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
 {
     Carver ws(workspace);
     uint16_t *q_bf = ws.take<uint16_t>((size_t)sh.plan.b_pad * L.d_pad);
+    const size_t bb = (size_t)b > 2 * (size_t)kSkinnyRows ? (size_t)b : 2 * (size_t)kSkinnyRows;
+    int32_t *flag_count = ws.take<int32_t>(1);
+    int32_t *flag_list = ws.take<int32_t>(bb);
+    int32_t *tickets = ws.take<int32_t>(bb);   // the exact scan's; the small-batch finishing kernel's follow at + kSkinnyRows
+    uint64_t *scan_lists = ws.take<uint64_t>(scan_scratch_entries(b, k, ctx->num_cus));
     StageMarks marks(ctx, s);
 
     marks.mark(0);
-    // (the small-batch streaming kernel converts its few queries itself)
-    if (!sh.skinny &&
-        launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf, s) != hipSuccess)
+    // (the small-batch streaming kernel converts its few queries itself); the first kernel of the
+    // look-up also clears the flag count and the tickets
+    if (!sh.skinny && launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf, flag_count,
+                                        tickets, s) != hipSuccess)
         return FREEZE_EHIP;
 
     FinishArgs fa{};
     marks.mark(1);
     bool marked2 = false;
     const uint64_t *skinny_bmin = nullptr, *skinny_wgmin = nullptr;
-    int32_t *skinny_blocks = nullptr, *skinny_nblk = nullptr;
-    uint64_t *skinny_cand = nullptr;
+    uint64_t *skinny_cand = nullptr, *skinny_samp = nullptr;
     if (sh.skinny) {
         SkinnyLaunch sl{};
         sl.queries = queries;
@@ -243,6 +254,8 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
         sl.norm = L.norm;
         sl.bmin = ws.take<uint64_t>((size_t)kSkinnyRows * (L.n_pad / 32));
         sl.wgmin = ws.take<uint64_t>((size_t)kSkinnyRows * (L.n_pad / kTileN));
+        sl.flag_count = flag_count;
+        sl.tickets = tickets;
         sl.b = (int)b;
         sl.n = (int)L.n;
         sl.d_pad = (int)L.d_pad;
@@ -254,9 +267,8 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
         marked2 = true;
         skinny_bmin = sl.bmin;
         skinny_wgmin = sl.wgmin;
-        skinny_blocks = ws.take<int32_t>((size_t)kSkinnyRows * kMaxRescore);
-        skinny_nblk = ws.take<int32_t>(kSkinnyRows);
         skinny_cand = ws.take<uint64_t>((size_t)kSkinnyRows * ((sh.r + 1) / 2) * 64);
+        skinny_samp = ws.take<uint64_t>((size_t)kSkinnyRows * ((sh.r + 1) / 2) * 2);
     } else {
         DistArgs da{};
         da.q_bf = q_bf;
@@ -324,13 +336,18 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     fa.out_votes = out_votes;
     fa.out_nbr_idx = out_nbr_idx;
     fa.out_nbr_dist = out_nbr_dist;
+    fa.flag_count = flag_count;
+    fa.flag_list = flag_list;
+    fa.stats = ctx->stats;
     if (skinny_bmin) {
         if (launch_skinny_finish(fa, skinny_bmin, skinny_wgmin, L.n_pad / 32, sh.plan.n_splits,
-                                 (int)(L.n_pad / kTileN), skinny_blocks, skinny_nblk, skinny_cand, s) != hipSuccess)
+                                 (int)(L.n_pad / kTileN), skinny_cand, skinny_samp, tickets + kSkinnyRows, s) != hipSuccess)
             return FREEZE_EHIP;
     } else if (launch_finish(fa, s) != hipSuccess) {
         return FREEZE_EHIP;
     }
+    // the queries whose result the certificate did not confirm (usually none) are redone exactly
+    if (launch_exact_scan(fa, tickets, scan_lists, ctx->num_cus, s) != hipSuccess) return FREEZE_EHIP;
     marks.mark(3);
     marks.done();
     return FREEZE_OK;
@@ -895,7 +912,7 @@ int freeze_project(freeze_ctx *ctx, int slot, const float *x, int64_t b, int rel
     uint16_t *x_bf = ws.take<uint16_t>((size_t)pl.b_pad * P->d_pad);
     float *tmp = ws.take<float>((size_t)b * P->n_pad);
     float *partial = pl.sk_wgs > 0 ? ws.take<float>(dist_partial_bytes(pl) / 4) : nullptr;
-    if (launch_query_prep(x, nullptr, nullptr, b, pl.b_pad, pl.bm, P->d, P->d_pad, x_bf, s) != hipSuccess)
+    if (launch_query_prep(x, nullptr, nullptr, b, pl.b_pad, pl.bm, P->d, P->d_pad, x_bf, nullptr, nullptr, s) != hipSuccess)
         return FREEZE_EHIP;
     const bool direct = P->n == P->n_pad;   // the output rows are then exactly what the kernel writes
     DistArgs da{};
@@ -932,6 +949,13 @@ int freeze_gather_rows(const float *x, int64_t d, const int32_t *sel, const int3
     if (max_count > 0 && (!x || !sel || !out)) return FREEZE_EINVAL;
     if (launch_gather_rows(x, d, sel, count, max_count, out, static_cast<hipStream_t>(stream)) != hipSuccess)
         return FREEZE_EHIP;
+    return FREEZE_OK;
+}
+
+int freeze_lookup_stats_attach(freeze_ctx *ctx, void *counters)
+{
+    if (!ctx || (reinterpret_cast<uintptr_t>(counters) % 8) != 0) return FREEZE_EINVAL;
+    ctx->stats = static_cast<unsigned long long *>(counters);
     return FREEZE_OK;
 }
 

@@ -45,6 +45,13 @@ constexpr int kMaxMergeEntries = 8192;  // n_splits * R gathered per query in th
 constexpr int kSkinnyRows = 16;         // small-batch (bandwidth-bound) path: at most this many queries ...
 constexpr int kSkinnyMaxD = 1024;       // ... and at most this padded activation length
 constexpr uint64_t kSentinel = ~0ull;   // "no entry" in (key, index) lists; larger than every real entry
+// Exactness certificate of the bf16 pre-filter (see finish_kernel): candidates re-scored when the
+// first certificate fails, the width of the error margin in estimated standard deviations, and the
+// fewest (distinct) samples an estimate is taken from.
+constexpr int kTier1 = 256;
+constexpr double kCertZ = 8.0;
+constexpr int kCertMinSamples = 8;
+constexpr int kScanMaxSplits = 512;     // exact scan of a flagged query: at most this many workgroups share it
 
 // One layer's cache inside the caller's storage buffer.
 struct LayerCache {
@@ -146,8 +153,11 @@ hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t
                               uint16_t *c_bf, float *norm, float *c_f32, uint16_t *c_rows, const int32_t *labels_in,
                               int32_t *labels_out, hipStream_t s);
 
+// Also clears what the later kernels of the look-up count in: *flag_count and tickets[0 .. b) (each
+// may be null).
 hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
-                             int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, hipStream_t s);
+                             int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, int32_t *flag_count,
+                             int32_t *tickets, hipStream_t s);
 
 hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t s);
 
@@ -160,6 +170,8 @@ struct SkinnyLaunch {
     const float *norm;
     uint64_t *bmin;         // [b, n_pad / 32] out: smallest (ordered key, index) of every block of 32 entries
     uint64_t *wgmin;        // [b, n_splits] out: smallest block minimum written by each workgroup
+    int32_t *flag_count;    // cleared by the kernel (with tickets[0 .. 2 * kSkinnyRows)) for the kernels after it
+    int32_t *tickets;
     int b, n, d_pad, r, n_splits;
     int64_t n_pad;
 };
@@ -202,15 +214,26 @@ struct FinishArgs {
     int32_t *out_votes;
     int32_t *out_nbr_idx;   // [b, k]
     float *out_nbr_dist;    // [b, k]
+    // queries whose result the certificate could not confirm: their (compact) positions are appended
+    // to flag_list, counted in *flag_count (cleared earlier in the look-up), and redone by the exact scan
+    int32_t *flag_count;
+    int32_t *flag_list;     // [b]
+    unsigned long long *stats;   // device, [3] or null: queries confirmed after the first re-scoring, after
+                                 // the wider one, and queries handed to the exact scan (added to, never cleared)
 };
 
 hipError_t launch_finish(const FinishArgs &a, hipStream_t s);
+// Exact scan of the flagged queries (a.flag_list / a.flag_count): brute-force fp32 distances to every
+// entry, the k nearest, the label and hit decision, written over the outputs of those queries.
+// tickets [b] int32 (zero on entry, zero again afterwards), part_x scan_scratch_entries(b, k, num_cus) u64.
+size_t scan_scratch_entries(int64_t b, int k, int num_cus);
+hipError_t launch_exact_scan(const FinishArgs &a, int32_t *tickets, uint64_t *part_x, int num_cus, hipStream_t s);
 // Small-batch path: from the block minima [b, nb] and the per-group minima to the outputs (takes
-// a.r blocks).  blocks [16, kMaxRescore] int32, nblk [16] int32 and cand are scratch
-// (skinny_finish_workspace_bytes covers the three).
+// a.r blocks).  cand and samp are scratch (skinny_finish_workspace_bytes covers both); tickets
+// [16] int32 must be zero on entry and are left zero.
 size_t skinny_finish_workspace_bytes(int r, size_t align);
 hipError_t launch_skinny_finish(const FinishArgs &a, const uint64_t *bmin, const uint64_t *wgmin, int64_t nb,
-                                int n_groups, int n_tiles, int32_t *blocks, int32_t *nblk, uint64_t *cand, hipStream_t s);
+                                int n_groups, int n_tiles, uint64_t *cand, uint64_t *samp, int32_t *tickets, hipStream_t s);
 
 hipError_t launch_compact(const uint8_t *hit, const int32_t *sel_in, const int32_t *count_in, int64_t count_max,
                           int32_t *sel_out, int32_t *count_out, int64_t *hits_out, hipStream_t s);

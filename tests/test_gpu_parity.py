@@ -88,8 +88,12 @@ def test_hand_example_on_gpu():
     (36000, 2080, 100, 10, 64, torch.float32), # stream-K, ragged d, workgroup ranges that span three tiles' parts
     (600, 16384, 40, 10, 0, torch.bfloat16),   # long activation, few queries: 1024-thread finishing blocks
     (600, 16392, 300, 10, 0, torch.float32),   # fused kernel, fp32 cache, long activation, d not a multiple of 64
-    (5000, 128, 50, 48, 0, torch.bfloat16),    # the largest k on the tiled kernel (R = 64)
+    (5000, 128, 50, 48, 0, torch.bfloat16),    # a large k on the tiled kernel (R = 64)
     (5000, 128, 4, 48, 0, torch.float32),      # ... and on the small-batch kernel
+    (5000, 128, 50, 64, 0, torch.bfloat16),    # k = R = 64: no spare candidate, the bf16 ranking alone gets the 64th wrong for some queries
+    (5000, 128, 4, 64, 0, torch.float32),      # ... and on the small-batch kernel
+    (1585, 6, 2140, 34, 63, torch.bfloat16),   # low-dimensional dense data: many entries within the bf16 rounding of the 34th neighbour
+    (4000, 64, 300, 10, 0, torch.bfloat16),    # (see test_clusters_far_from_the_origin for this shape on offset data)
     (64, 128, 20, 64, 0, torch.bfloat16),      # k = n = the re-scoring width: every entry is a candidate
     (50000, 64, 10000, 10, 0, torch.bfloat16), # 40 x 196 tiles on 256 CUs: balanced decomposition, workgroups that serve two query tiles
     (33000, 96, 7000, 5, 0, torch.float32),    # balanced decomposition, ragged last query tile
@@ -114,6 +118,62 @@ def test_shapes_against_oracle(n, d, b, k, r, dtype):
     data = synth.make_workload(type(wl)(wl.name, (spec,), b, k, (max(1, k - 2),), r, 77 + n + d))
     L = data.layers[0]
     check_case(L.entries, L.labels, data.queries[0], 10, k, max(1, k - 2), r)
+
+
+def _verdicts(fc):
+    c = torch.zeros(3, dtype=torch.int64, device="cuda")
+    binding.freeze_lookup_stats_attach(fc.ctx, c)
+    return c
+
+
+@pytest.mark.parametrize("b,store_bf16", [(300, True), (300, False), (6, True)])
+def test_clusters_far_from_the_origin(b, store_bf16):
+    """Every coordinate offset by +100: the bf16 keys (|c|^2 - 2 q.c, both of order 10^6) cannot tell
+    neighbours whose distances differ by a few units apart, so the coarse candidates miss true
+    neighbours for many queries.  The certificate must notice every such query and the wider
+    re-scoring or the exact scan must repair it: the results equal the oracle's."""
+    wl = synth.scaled(synth.WORKLOADS["c1_tiny"], n=4000, batch=b)
+    spec = type(wl.layers[0])(4000, 64, 10, 1.0, store_bf16=store_bf16)
+    data = synth.make_workload(type(wl)(wl.name, (spec,), b, 10, (8,), 0, 991))
+    L = data.layers[0]
+    ent = (L.entries.float() + 100.0).to(L.entries.dtype)
+    q = data.queries[0] + 100.0
+    fc = binding.FreezeCache(1)
+    try:
+        counters = _verdicts(fc)
+        fc.build_layer(0, ent.cuda(), L.labels.cuda(), 10)
+        out = fc.lookup(0, q.cuda(), 10, 8)
+        torch.cuda.synchronize()
+        got = {key: v.cpu().numpy() for key, v in out.items()}
+        c = counters.cpu().numpy()
+    finally:
+        fc.close()
+    e_h, l_h, q_h = _host_entries(ent), L.labels.numpy(), q.numpy()
+    ref = parity.oracle_reference(q_h, e_h, l_h, 10, 10, 8)
+    parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, 10, 8, rel=TIGHT, dist_rel=TIGHT)
+    assert c.sum() == b
+    assert c[1] + c[2] > 0, "this input is meant to defeat the coarse ranking"
+
+
+def test_certificate_verdicts_on_clustered_data():
+    # the paper's kind of input: nearly every query is confirmed after the first re-scoring
+    wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=20000, d_div=4, batch=2000)
+    data = synth.make_workload(wl)
+    L = data.layers[0]
+    fc = binding.FreezeCache(1)
+    try:
+        counters = _verdicts(fc)
+        fc.build_layer(0, L.entries.cuda(), L.labels.cuda(), 10)
+        fc.lookup(0, data.queries[0].cuda(), wl.k, wl.vote_thresholds[0])
+        torch.cuda.synchronize()
+        c = counters.cpu().numpy()
+        binding.freeze_lookup_stats_attach(fc.ctx, None)
+        fc.lookup(0, data.queries[0].cuda(), wl.k, wl.vote_thresholds[0])
+        torch.cuda.synchronize()
+        assert np.array_equal(counters.cpu().numpy(), c)     # detached: no longer counted
+    finally:
+        fc.close()
+    assert c.sum() == 2000 and c[0] >= 1900 and c[2] <= 5, c
 
 
 def test_random_labels_and_duplicates():
@@ -245,7 +305,7 @@ def test_argument_errors_launch_nothing():
         assert call(layer=1) == binding.FREEZE_ENOTBUILT
         assert call(k=0) == binding.FREEZE_EINVAL
         assert call(k=101) == binding.FREEZE_EINVAL
-        assert call(k=49, thr=3) == binding.FREEZE_EINVAL      # above the largest k (the cache has 100 entries)
+        assert call(k=65, thr=3) == binding.FREEZE_EINVAL      # above the largest k (the cache has 100 entries)
         assert call(thr=0) == binding.FREEZE_EINVAL
         assert call(thr=6) == binding.FREEZE_EINVAL
         assert call(r=3) == binding.FREEZE_EINVAL
