@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
     // scan's tickets) start at zero
     if (blockIdx.y == 0 && threadIdx.x < 2) {
         if (tickets && row0 + (int)threadIdx.x < b) tickets[row0 + threadIdx.x] = 0;
-        if (flag_count && blockIdx.x == 0 && threadIdx.x == 0) *flag_count = 0;
+        if (flag_count && blockIdx.x == 0) flag_count[threadIdx.x] = 0;   // both lists' counts
     }
     const int live_pad = ((nq + bm - 1) / bm) * bm;
     if (row0 >= live_pad) return;
@@ -505,6 +505,34 @@ __device__ __forceinline__ void decide_and_write(const FinishArgs &a, int q, int
     }
 }
 
+// Rank of each of the m re-scored candidates under (distance, index); the first k go to the
+// outputs and to lab_s / dsel_s.  Also counts the candidates that are not preceded by one at the
+// same distance (*distinct_s, zero on entry): how many different samples the certificate has.
+__device__ __forceinline__ void rank_and_emit(const FinishArgs &a, int q, int m, int tid, int nthreads, const float *dist_s,
+                                              const int32_t *idx_s, int32_t *lab_s, float *dsel_s, int32_t *nearest_s,
+                                              int *distinct_s)
+{
+    for (int c = tid; c < m; c += nthreads) {
+        const float dm = dist_s[c];
+        const int32_t im = idx_s[c];
+        int rank = 0, twin = 0;
+        for (int j = 0; j < m; ++j) {
+            const float dj = dist_s[j];
+            const int32_t ij = idx_s[j];
+            rank += (dj < dm) || (dj == dm && ij < im);
+            twin |= (dj == dm && ij < im);
+        }
+        if (!twin) atomicAdd(distinct_s, 1);
+        if (rank < a.k) {
+            a.out_nbr_idx[(int64_t)q * a.k + rank] = im;
+            a.out_nbr_dist[(int64_t)q * a.k + rank] = dm;
+            lab_s[rank] = a.labels[im];
+            dsel_s[rank] = dm;
+            if (rank == 0) *nearest_s = im;
+        }
+    }
+}
+
 struct FinishKernelArgs {
     FinishArgs a;
     int sort_cap;   // power of two >= the largest number of entries gathered per query (LDS allocation)
@@ -569,14 +597,22 @@ __device__ __forceinline__ bool certificate(const uint64_t *ent, const float *di
 // 256-thread blocks are held to four waves per SIMD, i.e. at most 128 registers: the compiler
 // would take 169 and leave two blocks per CU, too few to cover one block's merge and final
 // phases with the other blocks' re-scoring loads (0.55 -> 0.45 ms on 10,000 queries x 8,192).
-template <int NT>
+//
+// WIDER = false: one block per live query, the r best by the coarse key are re-scored; a query
+// the certificate does not confirm goes on list 0 (or straight on list 1 when no further
+// entries were gathered for it).  WIDER = true (a launch of its own, so that its code and registers
+// stay out of the kernel every query runs through; usually it finds list 0 empty): the blocks
+// share the queries of list 0 and re-score up to kTier1 of the gathered entries; what is still
+// unconfirmed goes on list 1, the exact scan's.
+template <int NT, bool WIDER>
 __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKernelArgs fa)
 {
     const FinishArgs &a = fa.a;
+    constexpr int MAXC = WIDER ? kTier1 : kMaxRescore;   // candidates re-scored per query at most
     extern __shared__ uint64_t ent[];   // sort_cap entries (dynamic: small merges keep occupancy high)
     __shared__ float red[NT / 64][8];
-    __shared__ float dist_s[kTier1];
-    __shared__ int32_t idx_s[kTier1];
+    __shared__ float dist_s[MAXC];
+    __shared__ int32_t idx_s[MAXC];
     __shared__ int32_t lab_s[kMaxK];
     __shared__ int32_t cnt_s[kMaxK];
     __shared__ float dsel_s[kMaxK];
@@ -586,152 +622,132 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKer
     __shared__ uint32_t excl_s;
 
     const int nq = a.count ? *a.count : a.b;
-    const int q = blockIdx.x;
-    if (q >= nq) return;
+    const int todo = WIDER ? a.flag_count[0] : nq;   // queries this launch works on
     const int tid = threadIdx.x;
     const int r = a.r;
+    auto one_query = [&](int job) {
+        const int q = WIDER ? a.flag_list[job] : job;
 
-    // 1. merge the per-split lists (or sort the query's candidate list)
-    int n_splits = a.n_splits;
-    if (a.count && !a.part_count)   // cascade: the distance pass derived its splits from the live count
-        n_splits = splits_for((nq + a.bm - 1) / a.bm, a.n_tiles, a.num_cus, a.max_splits);
-    int total = n_splits * r, stride = a.alloc_splits * r;
-    if (a.part_count) {
-        stride = a.part_stride;
-        total = a.part_count[q] < stride ? a.part_count[q] : stride;
-    }
-    int sort_n = 2;
-    while (sort_n < total) sort_n <<= 1;   // <= fa.sort_cap, the LDS allocation
-    const uint64_t *src = a.part + (size_t)q * stride;
-    if (tid == 0) {
-        real_s = 0;
-        excl_s = 0xffffffffu;
-    }
-    __syncthreads();
-    int mine = 0;
-    for (int i = tid; i < sort_n; i += NT) {
-        const uint64_t x = (i < total) ? src[i] : kSentinel;
-        ent[i] = x;
-        mine += (uint32_t)x < (uint32_t)a.n;   // a real cache entry (the "no entry" marker carries index 2^32 - 1)
-    }
-    if (mine) atomicAdd(&real_s, mine);
-    __syncthreads();
-    if (!a.part_count) {
-        // Per-split lists: a split that filled its list kept its r smallest keys, so every entry
-        // of its range that it dropped has a key >= the list's largest.  The smallest of these
-        // bounds bounds every entry outside the gathered lists.  (Slots rotate with the thread
-        // number so that neighbouring threads read different LDS banks.)
-        for (int sp = tid; sp < n_splits; sp += NT) {
-            uint32_t mx = 0;
-            for (int j = 0; j < r; ++j) {
-                int jj = j + sp;
-                jj -= (jj / r) * r;
-                const uint32_t kb = (uint32_t)(ent[sp * r + jj] >> 32);
-                mx = kb > mx ? kb : mx;
-            }
-            atomicMin(&excl_s, mx);   // a list with an empty slot dropped nothing: its largest is the marker
+        // 1. merge the per-split lists (or sort the query's candidate list)
+        int n_splits = a.n_splits;
+        if (a.count && !a.part_count)   // cascade: the distance pass derived its splits from the live count
+            n_splits = splits_for((nq + a.bm - 1) / a.bm, a.n_tiles, a.num_cus, a.max_splits);
+        int total = n_splits * r, stride = a.alloc_splits * r;
+        if (a.part_count) {
+            stride = a.part_stride;
+            total = a.part_count[q] < stride ? a.part_count[q] : stride;
+        }
+        int sort_n = 2;
+        while (sort_n < total) sort_n <<= 1;   // <= fa.sort_cap, the LDS allocation
+        const uint64_t *src = a.part + (size_t)q * stride;
+        if (tid == 0) {
+            real_s = 0;
+            excl_s = 0xffffffffu;
+            distinct_s = 0;
         }
         __syncthreads();
-    }
-    for (int size = 2; size <= sort_n; size <<= 1) {
-        for (int stride2 = size >> 1; stride2 > 0; stride2 >>= 1) {
-            for (int i = tid; i < (sort_n >> 1); i += NT) {
-                const int lo = ((i & ~(stride2 - 1)) << 1) | (i & (stride2 - 1));   // stride2 is a power of two
-                const int hi = lo + stride2;
-                const bool up = ((lo & size) == 0);
-                const uint64_t x = ent[lo], y = ent[hi];
-                if ((x > y) == up) {
-                    ent[lo] = y;
-                    ent[hi] = x;
+        int mine = 0;
+        for (int i = tid; i < sort_n; i += NT) {
+            const uint64_t x = (i < total) ? src[i] : kSentinel;
+            ent[i] = x;
+            mine += (uint32_t)x < (uint32_t)a.n;   // a real cache entry (the "no entry" marker carries index 2^32 - 1)
+        }
+        if (mine) atomicAdd(&real_s, mine);
+        __syncthreads();
+        if (!a.part_count) {
+            // Per-split lists: a split that filled its list kept its r smallest keys, so every entry
+            // of its range that it dropped has a key >= the list's largest.  The smallest of these
+            // bounds every entry outside the gathered lists.  (Slots rotate with the thread
+            // number so that neighbouring threads read different LDS banks.)
+            for (int sp = tid; sp < n_splits; sp += NT) {
+                uint32_t mx = 0;
+                int jj = sp % r;
+                for (int j = 0; j < r; ++j) {
+                    const uint32_t kb = (uint32_t)(ent[sp * r + jj] >> 32);
+                    mx = kb > mx ? kb : mx;
+                    jj = jj + 1 == r ? 0 : jj + 1;
                 }
+                atomicMin(&excl_s, mx);   // a list with an empty slot dropped nothing: its largest is the marker
             }
             __syncthreads();
         }
-    }
-    const int real = real_s;   // real entries gathered: they sort in front of the markers
-    // a candidate list (keys-out selection) holds every entry up to its largest pair
-    const uint32_t excl_outside = a.part_count ? (real >= a.n || real < 1 ? 0xffffffffu : (uint32_t)(ent[real - 1] >> 32))
-                                               : excl_s;
-    const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
+        for (int size = 2; size <= sort_n; size <<= 1) {
+            for (int stride2 = size >> 1; stride2 > 0; stride2 >>= 1) {
+                for (int i = tid; i < (sort_n >> 1); i += NT) {
+                    const int lo = ((i & ~(stride2 - 1)) << 1) | (i & (stride2 - 1));   // stride2 is a power of two
+                    const int hi = lo + stride2;
+                    const bool up = ((lo & size) == 0);
+                    const uint64_t x = ent[lo], y = ent[hi];
+                    if ((x > y) == up) {
+                        ent[lo] = y;
+                        ent[hi] = x;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
+        // candidates of this round: the best by the coarse key (real entries sort in front of the markers)
+        const int m = WIDER ? (real_s < kTier1 ? real_s : kTier1) : r;
 
-    // Two rounds at most: the r best by the coarse key, then (when the certificate does not
-    // confirm the result) up to kTier1 of the gathered entries.
-    int done = 0;   // candidates re-scored so far
-    int m = r;
-    for (int round = 0; round < 2; ++round) {
-        if (tid >= done && tid < m) {
+        for (int c = tid; c < m; c += NT) {
             // With finite inputs every one of the first r entries is a real cache row.  Non-finite
             // inputs (outside the contract) can leave "no entry" markers here: map them to row 0 so
             // that nothing is read out of bounds.
-            const uint32_t ci = (uint32_t)(ent[tid] & 0xffffffffu);
-            idx_s[tid] = ci < (uint32_t)a.n ? (int32_t)ci : 0;
+            const uint32_t ci = (uint32_t)(ent[c] & 0xffffffffu);
+            idx_s[c] = ci < (uint32_t)a.n ? (int32_t)ci : 0;
         }
-        if (tid == 0) distinct_s = 0;
         __syncthreads();
 
         // 2. exact fp32 re-scoring: each wave takes a group of candidates and needs no block barrier
         if (a.d >= 4096 && a.d % 8 == 0)
-            rescore_block<NT>(a, qrow, idx_s + done, dist_s + done, red, m - done, tid);
+            rescore_block<NT>(a, qrow, idx_s, dist_s, red, m, tid);
         else if (tid < 256) {   // short activations: four waves, one group of candidates each
-            if (m - done <= 16)
-                rescore_wave<4>(a, qrow, idx_s + done, dist_s + done, m - done, tid >> 6, tid & 63);
-            else if (m - done <= 32)
-                rescore_wave<8>(a, qrow, idx_s + done, dist_s + done, m - done, tid >> 6, tid & 63);
+            if (m <= 16)
+                rescore_wave<4>(a, qrow, idx_s, dist_s, m, tid >> 6, tid & 63);
+            else if (m <= 32)
+                rescore_wave<8>(a, qrow, idx_s, dist_s, m, tid >> 6, tid & 63);
             else
-                rescore_wave<16>(a, qrow, idx_s + done, dist_s + done, m - done, tid >> 6, tid & 63);
+                rescore_wave<16>(a, qrow, idx_s, dist_s, m, tid >> 6, tid & 63);
         }
         __syncthreads();
 
         // 3. final order (dist, index) and the first k
-        for (int c = tid; c < m; c += NT) {
-            const float dm = dist_s[c];
-            const int32_t im = idx_s[c];
-            int rank = 0, twin = 0;
-            for (int j = 0; j < m; ++j) {
-                const float dj = dist_s[j];
-                const int32_t ij = idx_s[j];
-                rank += (dj < dm) || (dj == dm && ij < im);
-                twin |= (dj == dm && ij < im);
-            }
-            if (!twin) atomicAdd(&distinct_s, 1);
-            if (rank < a.k) {
-                a.out_nbr_idx[(int64_t)q * a.k + rank] = im;
-                a.out_nbr_dist[(int64_t)q * a.k + rank] = dm;
-                lab_s[rank] = a.labels[im];
-                dsel_s[rank] = dm;
-                if (rank == 0) nearest_s = im;
-            }
-        }
+        rank_and_emit(a, q, m, tid, NT, dist_s, idx_s, lab_s, dsel_s, &nearest_s, &distinct_s);
         __syncthreads();
-        done = m;
 
         // the certificate: is any entry that was not re-scored possibly nearer than the k-th?
-        uint32_t excl = excl_outside;
+        const int real = real_s;   // real entries gathered
+        const int wider = real < kTier1 ? real : kTier1;
+        // (a candidate list of the keys-out selection holds every entry up to its largest pair)
+        uint32_t excl = a.part_count ? (real >= a.n || real < 1 ? 0xffffffffu : (uint32_t)(ent[real - 1] >> 32)) : excl_s;
         if (real > m) {
             const uint32_t nxt = (uint32_t)(ent[m] >> 32);
             excl = nxt < excl ? nxt : excl;
         }
         const bool ok = certificate(ent, dist_s, m, dsel_s[a.k - 1], excl, distinct_s, tid, &verdict_s);
-        if (ok) {
-            if (a.stats && tid == 0) atomicAdd(a.stats + round, 1ull);
-            break;
-        }
-        const int wider = real < kTier1 ? real : kTier1;
-        if (round == 1 || wider <= m) {
-            // unconfirmed: the exact scan redoes this query (the outputs written below stand until then)
-            if (tid == 0) {
-                const int pos = atomicAdd(a.flag_count, 1);
-                a.flag_list[pos] = q;
-                if (a.stats) atomicAdd(a.stats + 2, 1ull);
+        if (tid == 0) {
+            // unconfirmed: the wider round, or the exact scan, redoes this query (the outputs written
+            // here stand until then)
+            const int next = (WIDER || wider <= r) ? 1 : 0;
+            if (!ok) {
+                const int pos = atomicAdd(a.flag_count + next, 1);
+                (next ? a.flag_list2 : a.flag_list)[pos] = q;
             }
-            break;
+            if (a.stats && (ok || next == 1)) atomicAdd(a.stats + (ok ? (WIDER ? 1 : 0) : 2), 1ull);
         }
-        m = wider;
-        __syncthreads();   // verdict_s, distinct_s and the lists are rewritten by the next round
-    }
 
-    // 4. vote and hit decision
-    decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s, nearest_s);
+        // 4. vote and hit decision
+        decide_and_write(a, q, tid, lab_s, dsel_s, cnt_s, conf_s, nearest_s);
+    };
+    if constexpr (WIDER) {
+        for (int job = blockIdx.x; job < todo; job += gridDim.x) {
+            one_query(job);
+            __syncthreads();   // the next job reuses the shared arrays
+        }
+    } else {
+        if ((int)blockIdx.x < todo) one_query(blockIdx.x);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -918,12 +934,16 @@ __global__ __launch_bounds__(kThrThreads) void skinny_tail_kernel(SkinnyTailArgs
     }
 
     // ---- 3. the last workgroup of the query finishes it ----
-    __threadfence();
+    // (the barrier orders every thread's stores before thread 0's fence, which publishes them to the
+    // device before the ticket is taken; the last workgroup reads them with device-coherent loads)
     __syncthreads();
-    if (tid == 0) last_s = (atomicAdd(&sa.tickets[q], 1) == sa.pairs - 1);
+    if (tid == 0) {
+        __threadfence();
+        last_s = (atomicAdd(&sa.tickets[q], 1) == sa.pairs - 1);
+        __threadfence();
+    }
     __syncthreads();
     if (!last_s) return;   // uniform
-    __threadfence();
     const int mcand = sa.pairs * sa.keep;   // <= kThrList / 2
     for (int c = tid; c < mcand; c += kThrThreads)
         list[c] = __hip_atomic_load(sa.cand + (size_t)q * mcand + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -972,8 +992,8 @@ __global__ __launch_bounds__(kThrThreads) void skinny_tail_kernel(SkinnyTailArgs
     const bool ok = certificate(gm_s, dist_s, nblk, dsel_s[a.k - 1], excl, distinct_s, tid, &verdict_s);
     if (tid == 0) {
         if (!ok) {
-            const int pos = atomicAdd(a.flag_count, 1);
-            a.flag_list[pos] = q;
+            const int pos = atomicAdd(a.flag_count + 1, 1);
+            a.flag_list2[pos] = q;
         }
         if (a.stats) atomicAdd(a.stats + (ok ? 0 : 2), 1ull);
     }
@@ -993,7 +1013,7 @@ hipError_t launch_skinny_finish(const FinishArgs &a, const uint64_t *bmin, const
     if (a.r < 1 || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r || a.b < 1 || a.b > kSkinnyRows || a.sel || a.count)
         return hipErrorInvalidValue;
     if (n_groups < 1 || n_groups > kThrThreads || n_groups > n_tiles) return hipErrorInvalidValue;
-    if (!a.flag_count || !a.flag_list || !tickets) return hipErrorInvalidValue;
+    if (!a.flag_count || !a.flag_list2 || !tickets) return hipErrorInvalidValue;
     const int64_t bpg = ((int64_t)(n_tiles + n_groups - 1) / n_groups) * (kTileN / 32);
     if (a.r < nb && bpg * a.r > kThrList) return hipErrorInvalidValue;
     const int pairs = (a.r + 1) / 2;   // a.r >= the number of blocks selected
@@ -1003,20 +1023,24 @@ hipError_t launch_skinny_finish(const FinishArgs &a, const uint64_t *bmin, const
     return hipGetLastError();
 }
 
-hipError_t launch_finish(const FinishArgs &a, hipStream_t s)
+hipError_t launch_finish(const FinishArgs &a, int num_cus, hipStream_t s)
 {
     const int total = a.part_count ? a.part_stride : a.alloc_splits * a.r;
     if (total > kMaxMergeEntries || a.r > kMaxRescore || a.k > kMaxK || a.k > a.r) return hipErrorInvalidValue;
-    if (!a.flag_count || !a.flag_list) return hipErrorInvalidValue;
+    if (!a.flag_count || !a.flag_list || !a.flag_list2) return hipErrorInvalidValue;
     FinishKernelArgs fa{a, 2};
     while (fa.sort_cap < total) fa.sort_cap <<= 1;
+    const size_t lds = (size_t)fa.sort_cap * sizeof(uint64_t);
     // a block per query: with few queries and long activations use 1024-thread blocks
     if (a.b <= 1024 && a.d >= 16384 && a.d % 8 == 0)
-        hipLaunchKernelGGL(finish_kernel<1024>, dim3((unsigned)a.b), dim3(1024), (size_t)fa.sort_cap * sizeof(uint64_t), s,
-                           fa);
+        hipLaunchKernelGGL((finish_kernel<1024, false>), dim3((unsigned)a.b), dim3(1024), lds, s, fa);
     else
-        hipLaunchKernelGGL(finish_kernel<256>, dim3((unsigned)a.b), dim3(256), (size_t)fa.sort_cap * sizeof(uint64_t), s,
-                           fa);
+        hipLaunchKernelGGL((finish_kernel<256, false>), dim3((unsigned)a.b), dim3(256), lds, s, fa);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // the wider round for the queries on list 0: a fixed grid shares them (usually there are none)
+    const int grid = a.b < 2 * num_cus ? a.b : 2 * num_cus;
+    hipLaunchKernelGGL((finish_kernel<256, true>), dim3((unsigned)grid), dim3(256), lds, s, fa);
     return hipGetLastError();
 }
 
@@ -1053,7 +1077,7 @@ __global__ __launch_bounds__(256) void exact_scan_kernel(ScanArgs sa)
     __shared__ int32_t nearest_s;
     __shared__ int surv_s, last_s;
 
-    const int nf = *a.flag_count;
+    const int nf = a.flag_count[1];
     if (nf <= 0) return;   // the usual case
     const int tid = threadIdx.x;
     const int grid = (int)gridDim.x, k = a.k;
@@ -1065,7 +1089,7 @@ __global__ __launch_bounds__(256) void exact_scan_kernel(ScanArgs sa)
     const int64_t items = (int64_t)nf * S;
     for (int64_t item = blockIdx.x; item < items; item += grid) {
         const int j = (int)(item / S), sp = (int)(item - (int64_t)j * S);
-        const int q = a.flag_list[j];
+        const int q = a.flag_list2[j];
         const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
         const int row0 = (int)((int64_t)a.n * sp / S), row1 = (int)((int64_t)a.n * (sp + 1) / S);
         if (tid < kMaxK) best_s[tid] = kSentinel;
@@ -1099,12 +1123,14 @@ __global__ __launch_bounds__(256) void exact_scan_kernel(ScanArgs sa)
             }
         }
         if (tid < k) sa.part_x[(size_t)item * k + tid] = best_s[tid];
-        __threadfence();   // the list is visible to the whole device before the ticket is taken
         __syncthreads();
-        if (tid == 0) last_s = (atomicAdd(&sa.tickets[j], 1) == S - 1);
+        if (tid == 0) {
+            __threadfence();   // the list is visible to the whole device before the ticket is taken
+            last_s = (atomicAdd(&sa.tickets[j], 1) == S - 1);
+            __threadfence();
+        }
         __syncthreads();
         if (last_s) {   // uniform: this workgroup finished the query's last range
-            __threadfence();
             const int total = S * k;
             int n2 = 2;
             while (n2 < total) n2 <<= 1;
@@ -1145,7 +1171,7 @@ size_t scan_scratch_entries(int64_t b, int k, int num_cus)
 
 hipError_t launch_exact_scan(const FinishArgs &a, int32_t *tickets, uint64_t *part_x, int num_cus, hipStream_t s)
 {
-    if (!a.flag_count || !a.flag_list || !tickets || !part_x || a.k < 1 || a.k > kMaxK) return hipErrorInvalidValue;
+    if (!a.flag_count || !a.flag_list2 || !tickets || !part_x || a.k < 1 || a.k > kMaxK) return hipErrorInvalidValue;
     ScanArgs sa{a, tickets, part_x, scan_max_splits(a.k)};
     int cap = 512;
     while (cap < sa.max_splits * a.k) cap <<= 1;

@@ -129,9 +129,9 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
                             smem_base + NORMS + ((t & 1) * 8 + w) * 256);
     };
 
-    if (sp == 0 && tid < 2 * kSkinnyRows + 1) {
+    if (sp == 0 && tid < 2 * kSkinnyRows + 2) {
         if (tid < 2 * kSkinnyRows) p.tickets[tid] = 0;
-        else *p.flag_count = 0;
+        else p.flag_count[tid - 2 * kSkinnyRows] = 0;   // both lists' counts
     }
     // the stream starts before the queries are converted: its first stages are on their way meanwhile
     if (total > 0) issue_norms(nt0);

@@ -128,7 +128,7 @@ bool lookup_shape(const freeze_ctx *ctx, const LayerCache &L, int64_t b, int k, 
     out->cascade = cascade;
     // list and count of the queries the certificate flags, the exact scan's tickets and lists
     const size_t bb = (size_t)(b > 0 ? b : 1);
-    const size_t scan_bytes = align_up(4) + 2 * align_up((bb > 2 * kSkinnyRows ? bb : 2 * kSkinnyRows) * 4) +
+    const size_t scan_bytes = align_up(8) + 3 * align_up((bb > 2 * kSkinnyRows ? bb : 2 * kSkinnyRows) * 4) +
                               align_up(scan_scratch_entries(b, k, ctx->num_cus) * 8);
     out->skinny = !cascade && skinny_supported(b, L.n_pad, L.d_pad, r, ctx->num_cus);
     out->keys = false;
@@ -228,8 +228,9 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     Carver ws(workspace);
     uint16_t *q_bf = ws.take<uint16_t>((size_t)sh.plan.b_pad * L.d_pad);
     const size_t bb = (size_t)b > 2 * (size_t)kSkinnyRows ? (size_t)b : 2 * (size_t)kSkinnyRows;
-    int32_t *flag_count = ws.take<int32_t>(1);
+    int32_t *flag_count = ws.take<int32_t>(2);
     int32_t *flag_list = ws.take<int32_t>(bb);
+    int32_t *flag_list2 = ws.take<int32_t>(bb);
     int32_t *tickets = ws.take<int32_t>(bb);   // the exact scan's; the small-batch finishing kernel's follow at + kSkinnyRows
     uint64_t *scan_lists = ws.take<uint64_t>(scan_scratch_entries(b, k, ctx->num_cus));
     StageMarks marks(ctx, s);
@@ -338,12 +339,13 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     fa.out_nbr_dist = out_nbr_dist;
     fa.flag_count = flag_count;
     fa.flag_list = flag_list;
+    fa.flag_list2 = flag_list2;
     fa.stats = ctx->stats;
     if (skinny_bmin) {
         if (launch_skinny_finish(fa, skinny_bmin, skinny_wgmin, L.n_pad / 32, sh.plan.n_splits,
                                  (int)(L.n_pad / kTileN), skinny_cand, skinny_samp, tickets + kSkinnyRows, s) != hipSuccess)
             return FREEZE_EHIP;
-    } else if (launch_finish(fa, s) != hipSuccess) {
+    } else if (launch_finish(fa, ctx->num_cus, s) != hipSuccess) {
         return FREEZE_EHIP;
     }
     // the queries whose result the certificate did not confirm (usually none) are redone exactly

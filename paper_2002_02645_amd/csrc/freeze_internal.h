@@ -153,8 +153,8 @@ hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t
                               uint16_t *c_bf, float *norm, float *c_f32, uint16_t *c_rows, const int32_t *labels_in,
                               int32_t *labels_out, hipStream_t s);
 
-// Also clears what the later kernels of the look-up count in: *flag_count and tickets[0 .. b) (each
-// may be null).
+// Also clears what the later kernels of the look-up count in: flag_count[0 .. 2) and tickets[0 .. b)
+// (each may be null).
 hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
                              int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, int32_t *flag_count,
                              int32_t *tickets, hipStream_t s);
@@ -214,16 +214,18 @@ struct FinishArgs {
     int32_t *out_votes;
     int32_t *out_nbr_idx;   // [b, k]
     float *out_nbr_dist;    // [b, k]
-    // queries whose result the certificate could not confirm: their (compact) positions are appended
-    // to flag_list, counted in *flag_count (cleared earlier in the look-up), and redone by the exact scan
-    int32_t *flag_count;
+    // Queries whose result the certificate could not confirm, by their (compact) positions: list 0
+    // (flag_list, counted in flag_count[0]) is redone by the wider re-scoring, list 1 (flag_list2,
+    // flag_count[1]) by the exact scan.  The first kernel of the look-up clears both counts.
+    int32_t *flag_count;    // [2]
     int32_t *flag_list;     // [b]
+    int32_t *flag_list2;    // [b]
     unsigned long long *stats;   // device, [3] or null: queries confirmed after the first re-scoring, after
                                  // the wider one, and queries handed to the exact scan (added to, never cleared)
 };
 
-hipError_t launch_finish(const FinishArgs &a, hipStream_t s);
-// Exact scan of the flagged queries (a.flag_list / a.flag_count): brute-force fp32 distances to every
+hipError_t launch_finish(const FinishArgs &a, int num_cus, hipStream_t s);
+// Exact scan of the flagged queries (a.flag_list2 / a.flag_count[1]): brute-force fp32 distances to every
 // entry, the k nearest, the label and hit decision, written over the outputs of those queries.
 // tickets [b] int32 (zero on entry, zero again afterwards), part_x scan_scratch_entries(b, k, num_cus) u64.
 size_t scan_scratch_entries(int64_t b, int k, int num_cus);
