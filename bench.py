@@ -8,7 +8,9 @@ workspace already resident in HBM.
 
 Prints ONE JSON line: queries/s of the whole look-up, the roofline figures of the dominant
 kernel (the distance pass, timed with HIP events on its own stream inside the timed region)
-and the CPU oracle timed on a bounded sample of the same workload.
+and the CPU oracle timed on a bounded sample of the same workload.  The headline workload is
+c2_batched; without --workload the line also carries, under "other_workloads", the same block
+(timing, roofline, cpu_baseline, parity sample) for every other benchmark configuration.
 """
 from __future__ import annotations
 
@@ -91,50 +93,25 @@ def time_next_rows(torch, binding, dev):
     return res
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2_batched")
-    ap.add_argument("--cache-copies", type=int, default=0,
-                    help="identical copies of a single-layer cache the steps alternate between (0 = 2 when the cache is at most 2 GiB)")
-    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (profiling runs)")
-    ap.add_argument("--cpu-sample", type=int, default=0, help="queries in the oracle sample (0 = per workload)")
-    ap.add_argument("--calibrate", action="store_true",
-                    help="also measure what this GPU sustains on a pure MFMA loop and on a pure 1 GiB read")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 1 GiB device copy three times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--next-rows", action="store_true",
-                    help="instead of a look-up workload, time the k-means cache (Sec. 4 of the paper) and the "
-                         "projection in front of the look-up (Sec. 3) at the paper's scale; prints one JSON line")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (one-GPU boxes; the path has no multi-GPU part); "
-              "run with --gpus 1", file=sys.stderr)
-        return 2
+# oracle sample sizes: about 3-5 s of oracle time each on the machine's host cores (the run prints how
+# many threads the oracle actually used)
+CPU_SAMPLE = {"c1_tiny": 256, "c2_batched": 256, "c3_wide": 32, "c4_cascade": 16, "c4_cascade_noisy": 16,
+              "c5_latency_b1": 1, "c5_latency_b8": 8}
+STEPS = {"c1_tiny": 200, "c2_batched": 20, "c3_wide": 20, "c4_cascade": 6, "c4_cascade_noisy": 6,
+         "c5_latency_b1": 200, "c5_latency_b8": 200}
+ALL_WORKLOADS = ["c2_batched", "c1_tiny", "c3_wide", "c4_cascade", "c4_cascade_noisy", "c5_latency_b1", "c5_latency_b8"]
 
-    import numpy as np
-    import torch
 
-    from paper_2002_02645_amd import binding, synth
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 3
-    binding.lib()   # fail loudly if the HIP library is not built
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    if args.next_rows:
-        print(json.dumps(time_next_rows(torch, binding, dev)))
-        return 0
-
-    wl = synth.WORKLOADS[args.workload]
+def run_workload(torch, np, binding, synth, dev, name, steps, warmup, cache_copies=0, cpu_baseline=True, cpu_sample=0,
+                 data=None):
+    """Times one workload and returns (result block, data).  `data` lets the two cascade variants,
+    which differ in the cache labels only, share the generated activations."""
+    wl = synth.WORKLOADS[name]
     nl = len(wl.layers)
     cascade = nl > 1
     t0 = time.time()
-    data = synth.make_workload(wl, device=dev)
+    if data is None:
+        data = synth.make_workload(wl, device=dev)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
@@ -142,10 +119,12 @@ def main() -> int:
     # alternate between the copies, so that no step finds its cache in the memory-side cache
     # because the step before left it there.
     cache_gib = data.layers[0].spec.n * data.layers[0].spec.d * 2 / 2**30
-    copies = args.cache_copies if args.cache_copies > 0 else (2 if (not cascade and cache_gib <= 2.0) else 1)
+    copies = cache_copies if cache_copies > 0 else (2 if (not cascade and cache_gib <= 2.0) else 1)
     if cascade:
         copies = 1
     fc = binding.FreezeCache(nl if cascade else copies, dev)
+    verdicts = torch.zeros(3, dtype=torch.int64, device=dev)
+    binding.freeze_lookup_stats_attach(fc.ctx, verdicts)
     t0 = time.time()
     for l, L in enumerate(data.layers):
         for c in range(copies):
@@ -171,9 +150,10 @@ def main() -> int:
             fc.lookup(turn[0] % copies, data.queries[0], k, wl.vote_thresholds[0], r, out=out)
             turn[0] += 1
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    verdicts.zero_()
 
     binding.freeze_profile_enable(fc.ctx, True)
     ev0 = torch.cuda.Event(enable_timing=True)
@@ -181,24 +161,25 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev0.record(stream)
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     ev1.record(stream)
     torch.cuda.synchronize()
     wall_s = time.perf_counter() - t0
     calls = binding.freeze_profile_read_calls(fc.ctx)
     binding.freeze_profile_enable(fc.ctx, False)
+    verdict_counts = [int(v) for v in verdicts.cpu().numpy()]
     # the same K steps once more without the stage events (four event records per look-up, which
     # matter next to a 0.2 ms look-up and not otherwise); reported beside the timed region's figure
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    ms_per_step_plain = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_per_step = wall_s * 1e3 / args.steps
-    ev_ms_per_step = ev0.elapsed_time(ev1) / args.steps
-    qps = b * args.steps / wall_s
+    ms_per_step_plain = (time.perf_counter() - t0) * 1e3 / steps
+    ms_per_step = wall_s * 1e3 / steps
+    ev_ms_per_step = ev0.elapsed_time(ev1) / steps
+    qps = b * steps / wall_s
 
     # per-layer stage times: the recorded look-ups cycle through the layers
     per_layer = [[0.0, 0.0, 0.0] for _ in range(nl)]
@@ -230,6 +211,8 @@ def main() -> int:
     roofline["kernel"] = "dist_skinny_kernel" if skinny else "dist_topr_kernel"
     roofline["kernel_ms"] = round(dist_ms, 4)
     roofline["traffic"] = measured_traffic(roofline["kernel"], wl.name)
+    roofline["traffic_source"] = (f"profiles/{roofline['kernel']}_{wl.name}.txt (rocprofv3 counters of an earlier run of "
+                                  "this command; not measured in this run)") if roofline["traffic"] else None
     roofline["stage_ms"] = {"query_prep": round(per_layer[0][0], 4), "dist": round(dist_ms, 4),
                             "select_rescore_vote": round(per_layer[0][2], 4)}
 
@@ -241,7 +224,10 @@ def main() -> int:
               "stage_sum_ms_median": round(step_ms[len(step_ms) // 2], 4) if step_ms else None,
               "stage_sum_ms_min": round(step_ms[0], 4) if step_ms else None,
               "ms_per_step_without_stage_events": round(ms_per_step_plain, 4), "cache_build_s": round(build_s, 3), "cache_copies": copies,
-              "input_gen_s": round(gen_s, 2)}
+              "input_gen_s": round(gen_s, 2),
+              # how the timed look-ups were confirmed exact: at once / after the wider re-scoring / by the exact scan
+              "certificate_verdicts": {"first_rescoring": verdict_counts[0], "wider_rescoring": verdict_counts[1],
+                                       "exact_scan": verdict_counts[2]}}
     if cascade:
         hits = out["hits_per_layer"].cpu().numpy().astype(np.int64)
         entering = [b]
@@ -257,29 +243,39 @@ def main() -> int:
             "layer_dist_tflops": [round(2.0 * entering[l] * wl.layers[l].n * wl.layers[l].d
                                         / max(per_layer[l][1] * 1e-3, 1e-9) / 1e12, 1) for l in range(nl)],
         }
+        step_flops = sum(2.0 * entering[l] * wl.layers[l].n * wl.layers[l].d for l in range(nl))
+    else:
+        step_flops = flops
+    # the whole step (every stage of every layer) against the same roof
+    if skinny:
+        roofline["frac_whole_step"] = round(cache_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+    else:
+        roofline["frac_whole_step"] = round(step_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)
 
     result = {
         "metric": "queries/sec per layer lookup",
         "value": round(qps, 1),
         "unit": "queries/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
+        # the distance pass multiplies bf16 operands with fp32 accumulation; the re-scoring that decides
+        # the reported neighbours and distances is fp32 against the stored values (bf16, or fp32 for C1)
         "dtype": "bf16",
+        "rescoring_dtype": "f32",
+        "cache_dtype": "bf16" if spec.store_bf16 else "f32",
         "data": "synthetic",
         "config": config,
         "roofline": roofline,
     }
 
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         from oracle import freeze_oracle as fo
-        # sized for about 10-20 s of oracle time on the box's 16 host cores
-        default_sample = {"c2_batched": 768, "c3_wide": 96, "c1_tiny": 256, "c4_cascade": 48, "c4_cascade_noisy": 48}
-        sample = min(args.cpu_sample or default_sample.get(wl.name, min(b, 64)), b)
+        sample = min(cpu_sample or CPU_SAMPLE.get(wl.name, min(b, 64)), b)
         g = torch.Generator().manual_seed(wl.seed + 999)
         pick = torch.randperm(b, generator=g)[:sample].sort().values
         host_entries = [synth.bf16_bits(L.entries) if L.entries.dtype == torch.bfloat16 else L.entries.cpu().numpy()
@@ -313,6 +309,77 @@ def main() -> int:
             what = f"{sample} of the {b} queries (seeded subset) against the full cache"
         result["cpu_baseline"] = {"value": round(sample / cpu_s, 3), "unit": "queries/s", "cores": int(o_threads),
                                   "kind": "oracle", "sample": f"{what}, {cpu_s:.1f} s"}
+        del host_entries, host_q
+    fc.close()
+    return result, data
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps of the headline workload (0 = 20)")
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="",
+                    help="time this workload only; by default the headline workload c2_batched is followed by every "
+                         "other benchmark configuration, reported under other_workloads of the same JSON line")
+    ap.add_argument("--cache-copies", type=int, default=0,
+                    help="identical copies of a single-layer cache the steps alternate between (0 = 2 when the cache is at most 2 GiB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle leg (profiling runs)")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="queries in the oracle sample (0 = per workload)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also measure what this GPU sustains on a pure MFMA loop and on a pure 1 GiB read")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--next-rows", action="store_true",
+                    help="instead of a look-up workload, time the k-means cache (Sec. 4 of the paper) and the "
+                         "projection in front of the look-up (Sec. 3) at the paper's scale; prints one JSON line")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (one-GPU boxes; the path has no multi-GPU part); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2002_02645_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    binding.lib()   # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if args.next_rows:
+        print(json.dumps(time_next_rows(torch, binding, dev)))
+        return 0
+
+    head = args.workload or "c2_batched"
+    result, data = run_workload(torch, np, binding, synth, dev, head, args.steps or STEPS.get(head, 20), args.warmup,
+                                args.cache_copies, not args.no_cpu_baseline, args.cpu_sample)
+    del data
+    if not args.workload:
+        # every other configuration, each with its own roofline / cpu_baseline / parity_sample block
+        others, shared = [], None
+        for name in ALL_WORKLOADS:
+            if name == head:
+                continue
+            torch.cuda.empty_cache()
+            reuse = shared if name == "c4_cascade_noisy" else None
+            if reuse is not None:
+                # same seeds, same activations: only the cache labels differ
+                noisy = synth.make_workload_labels(synth.WORKLOADS[name])
+                for L, lab in zip(reuse.layers, noisy):
+                    L.labels = lab.to(dev)
+            block, d = run_workload(torch, np, binding, synth, dev, name, STEPS.get(name, 20), args.warmup, 0,
+                                    not args.no_cpu_baseline, 0, data=reuse)
+            shared = d if name == "c4_cascade" else None
+            del d
+            for key in ("n_gpus", "higher_is_better", "scaling", "vs_baseline", "data"):
+                block.pop(key, None)
+            others.append(block)
+        result["other_workloads"] = others
 
     if args.calibrate:
         scratch = torch.empty(1 << 22, dtype=torch.uint8, device=dev)
@@ -329,8 +396,7 @@ def main() -> int:
         for _ in range(3):
             torch.bitwise_not(src, out=dst)   # a plain elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
-        config["copy_calibration_bytes"] = 1 << 30
-    fc.close()
+        result["config"]["copy_calibration_bytes"] = 1 << 30
     print(json.dumps(result))
     return 0
 

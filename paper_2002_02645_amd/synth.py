@@ -136,14 +136,25 @@ def make_layer(spec: LayerSpec, seed: int, device="cpu") -> LayerData:
     clean = balanced_labels(spec.n, spec.num_classes, seed + 1)
     dt = torch.bfloat16 if spec.store_bf16 else torch.float32
     entries = _draw_rows(cent, clean, spec.sigma, spec.relu, dt, _gen(device, seed + 2))
-    labels = clean.clone()
-    if spec.label_flip_p > 0.0:
-        g = _gen("cpu", seed + 3)
-        flip = torch.rand(spec.n, generator=g) < spec.label_flip_p
-        shift = torch.randint(1, spec.num_classes, (spec.n,), generator=g, dtype=torch.int64)
-        flipped = ((clean.to(torch.int64) + shift) % spec.num_classes).to(torch.int32)
-        labels = torch.where(flip, flipped, clean)
+    labels = make_layer_labels(spec, seed)
     return LayerData(spec, entries, labels.to(device), cent, clean.to(device))
+
+
+def make_layer_labels(spec: LayerSpec, seed: int) -> torch.Tensor:
+    """The labels make_layer(spec, seed) gives the entries, without drawing the entries (CPU tensor)."""
+    clean = balanced_labels(spec.n, spec.num_classes, seed + 1)
+    if spec.label_flip_p <= 0.0:
+        return clean
+    g = _gen("cpu", seed + 3)
+    flip = torch.rand(spec.n, generator=g) < spec.label_flip_p
+    shift = torch.randint(1, spec.num_classes, (spec.n,), generator=g, dtype=torch.int64)
+    flipped = ((clean.to(torch.int64) + shift) % spec.num_classes).to(torch.int32)
+    return torch.where(flip, flipped, clean)
+
+
+def make_workload_labels(wl: Workload) -> List[torch.Tensor]:
+    """Per layer, the cache labels make_workload(wl) would produce."""
+    return [make_layer_labels(spec, wl.seed + 100 * li + 10) for li, spec in enumerate(wl.layers)]
 
 
 def make_queries(layer: LayerData, classes: torch.Tensor, seed: int) -> torch.Tensor:
