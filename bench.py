@@ -75,8 +75,17 @@ def time_next_rows(torch, binding, dev):
     q = (cent[torch.randint(0, classes, (nq,), device=dev, generator=g)] +
          0.8 * torch.randn(nq, d, device=dev, generator=g)).contiguous()
     tl = timed(lambda: fc.lookup_confidence(0, q, 1, 0.01), 10)
+    per_round = (t5 - t1) / 4
+    # algorithmic bytes: a round reads every point twice in fp32 (assignment, update); a look-up reads its queries once
+    round_bytes, lookup_bytes = 2.0 * n * d * 4, float(nq) * d * 4 + float(kc) * d * 2
     res["kmeans"] = {"points": n, "d": d, "centres": kc, "build_ms_1_round": round(t1, 3), "build_ms_5_rounds": round(t5, 3),
-                     "ms_per_round": round((t5 - t1) / 4, 3), "lookup_queries": nq, "lookup_ms": round(tl, 3)}
+                     "ms_per_round": round(per_round, 3), "lookup_queries": nq, "lookup_ms": round(tl, 3),
+                     "roofline_round": {"bound": "hbm", "achieved": round(round_bytes / per_round / 1e6, 1), "peak": PEAK_HBM_GBS,
+                                        "unit": "GB/s", "frac": round(round_bytes / per_round / 1e6 / PEAK_HBM_GBS, 4),
+                                        "bytes": round_bytes, "what": "whole round: centres -> cache, assignment look-up (k = 1) of every point, update"},
+                     "roofline_lookup": {"bound": "hbm", "achieved": round(lookup_bytes / tl / 1e6, 1), "peak": PEAK_HBM_GBS,
+                                         "unit": "GB/s", "frac": round(lookup_bytes / tl / 1e6 / PEAK_HBM_GBS, 4),
+                                         "bytes": lookup_bytes, "what": "whole look-up with the k-means confidence"}}
     fc.close()
     del pts, q
     for (b, dd, m) in [(10000, 8192, 1024), (4096, 65536, 1024), (256, 65536, 1024)]:
@@ -86,8 +95,14 @@ def time_next_rows(torch, binding, dev):
         fc = binding.FreezeCache(1, dev)
         fc.build_projection(0, w, bias)
         ms = timed(lambda: fc.project(0, x, True), 10)
-        res["projection"].append({"inputs": b, "d": dd, "outputs": m, "ms": round(ms, 3),
-                                  "TFLOPs": round(2.0 * b * dd * m / ms / 1e9, 1)})
+        tf = 2.0 * b * dd * m / ms / 1e9
+        io_bytes = float(b) * dd * 4 + float(m) * dd * 2 + float(b) * m * 4
+        res["projection"].append({"inputs": b, "d": dd, "outputs": m, "ms": round(ms, 3), "TFLOPs": round(tf, 1),
+                                  "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                               "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+                                               "hbm_view": {"GBs": round(io_bytes / ms / 1e6, 1),
+                                                            "frac_of_hbm_peak": round(io_bytes / ms / 1e6 / PEAK_HBM_GBS, 4)},
+                                               "what": "whole call: fp32 -> bf16 conversion of x, MFMA product (stream-K), bias / ReLU"}})
         fc.close()
         del x, w
     return res

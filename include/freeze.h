@@ -98,8 +98,8 @@ size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b
  *   vote_threshold hit iff the winning label holds >= vote_threshold of the k
  *                  neighbours; 1 <= vote_threshold <= k.
  *   rescore_r      candidates per query kept by the bf16 matrix-core pass and
- *                  re-scored exactly in fp32; 0 = library default (16 for k <= 10,
- *                  32 for k <= 24, else 64), else k <= rescore_r <= FREEZE_MAX_RESCORE
+ *                  re-scored exactly in fp32; 0 = library default (8 for k = 1, 16 for
+ *                  k <= 10, 32 for k <= 24, else 64), else k <= rescore_r <= FREEZE_MAX_RESCORE
  *                  (clamped to n).  The width changes the speed, never the result: after
  *                  the re-scoring the library checks, per query, that no entry outside the
  *                  candidates can be nearer than the k-th neighbour found (from the spread

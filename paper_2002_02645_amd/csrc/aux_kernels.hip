@@ -1049,7 +1049,7 @@ hipError_t launch_finish(const FinishArgs &a, int num_cus, hipStream_t s)
 // returns THE k nearest neighbours): brute-force fp32 distances sum (q_i - c_i)^2 to every
 // stored entry, the same arithmetic as the re-scoring above, no bf16 anywhere.  A fixed grid of
 // workgroups shares the flagged queries: with nf of them, each is cut into S = grid / nf
-// ranges of entries (at least one, at most max_splits); a workgroup scans its range 256 entries
+// ranges of at least 16 entries (at least one range, at most max_splits); a workgroup scans its range 256 entries
 // at a time and keeps the k nearest by (distance, index); the last workgroup of a query to finish
 // (a ticket per query) merges the S lists and writes the neighbours, the label and the hit
 // decision over that query's outputs.  Nothing is flagged on the paper's kind of data, and then
@@ -1082,7 +1082,7 @@ __global__ __launch_bounds__(256) void exact_scan_kernel(ScanArgs sa)
     const int tid = threadIdx.x;
     const int grid = (int)gridDim.x, k = a.k;
     int S = grid / nf;
-    const int by_size = (a.n + 255) / 256;   // a range holds at least one 256-entry chunk
+    const int by_size = (a.n + 15) / 16;   // a range holds at least 16 entries
     S = S > sa.max_splits ? sa.max_splits : S;
     S = S > by_size ? by_size : S;
     S = S < 1 ? 1 : S;

@@ -96,7 +96,8 @@ bool cache_layout(int64_t n, int64_t d, int dtype, CacheLayout *out)
     return true;
 }
 
-int default_rescore(int k) { return k <= 10 ? 16 : (k <= 24 ? 32 : 64); }
+// (k = 1, the nearest centre of a k-means cache: eight candidates, the fewest the certificate takes its estimate from)
+int default_rescore(int k) { return k == 1 ? 8 : (k <= 10 ? 16 : (k <= 24 ? 32 : 64)); }
 
 // Validated parameters of one look-up on one layer.
 struct LookupShape {
@@ -221,9 +222,12 @@ struct HitRule {
     float *out_conf;   // [b], weighted rule only
 };
 
+// `prepared`: the workspace still holds the bf16 copy of these very queries from an earlier call
+// with the same shape (the k-means build looks the same points up round after round).
 int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, const float *queries, const int32_t *sel,
                    const int32_t *count, int64_t b, int k, const HitRule &rule, int32_t *out_labels, uint8_t *out_hit,
-                   int32_t *out_votes, int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace, hipStream_t s)
+                   int32_t *out_votes, int32_t *out_nbr_idx, float *out_nbr_dist, void *workspace, hipStream_t s,
+                   bool prepared = false)
 {
     Carver ws(workspace);
     uint16_t *q_bf = ws.take<uint16_t>((size_t)sh.plan.b_pad * L.d_pad);
@@ -238,9 +242,13 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
     marks.mark(0);
     // (the small-batch streaming kernel converts its few queries itself); the first kernel of the
     // look-up also clears the flag count and the tickets
-    if (!sh.skinny && launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf, flag_count,
-                                        tickets, s) != hipSuccess)
+    if (!sh.skinny && prepared) {
+        // only the flag counts start over (the exact scan leaves its tickets at zero)
+        if (launch_fill_i32(flag_count, 0, 2, s) != hipSuccess) return FREEZE_EHIP;
+    } else if (!sh.skinny && launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf,
+                                               flag_count, tickets, s) != hipSuccess) {
         return FREEZE_EHIP;
+    }
 
     FinishArgs fa{};
     marks.mark(1);
@@ -507,7 +515,8 @@ bool kmeans_layout(const freeze_ctx *ctx, int64_t n, int64_t d, int64_t kc, Kmea
     if (!lookup_shape(ctx, tmp, n, 1, 0, false, &sh)) return false;
     out->lookup_ws = sh.ws_bytes;
     out->bytes = sh.ws_bytes + 2 * align_up((size_t)kc * d * 4) + align_up((size_t)kc * 4) + 3 * align_up((size_t)n * 4) +
-                 align_up((size_t)n) + 2 * align_up((size_t)n * 4);
+                 align_up((size_t)n) + 2 * align_up((size_t)n * 4) +
+                 align_up((size_t)kc * 4) + align_up((size_t)(kc + 1) * 4) + align_up((size_t)n * 4);   // grouping by centre
     return true;
 }
 
@@ -805,6 +814,9 @@ int freeze_kmeans_build(freeze_ctx *ctx, int layer, const float *points, int64_t
     float *t_dist = ws.take<float>((size_t)n);
     float *t_conf = ws.take<float>((size_t)n);
     (void)t_conf;
+    int32_t *grp_sizes = ws.take<int32_t>((size_t)kc);
+    int32_t *grp_offsets = ws.take<int32_t>((size_t)kc + 1);
+    int32_t *grp_members = ws.take<int32_t>((size_t)n);
 
     CacheLayout cl;
     cache_layout(kc, d, FREEZE_F32, &cl);
@@ -822,11 +834,14 @@ int freeze_kmeans_build(freeze_ctx *ctx, int layer, const float *points, int64_t
         const LayerCache &L = ctx->layers[layer];
         LookupShape sh;
         if (!lookup_shape(ctx, L, n, 1, 0, false, &sh)) return FREEZE_EINVAL;
+        // the points do not change from round to round: their bf16 copy is made once (the shape of
+        // the look-up, and with it the layout of its workspace, is the same in every round)
         rc = enqueue_lookup(ctx, L, sh, points, nullptr, nullptr, n, 1, rule, t_labels, t_hit, t_votes, assign, t_dist,
-                            lookup_ws, s);
+                            lookup_ws, s, it > 0);
         if (rc != FREEZE_OK) return rc;
         if (it < iters &&
-            launch_kmeans_update(points, assign, n, d, kc, cur, cen[(it + 1) & 1], s) != hipSuccess)
+            launch_kmeans_update(points, assign, n, d, kc, cur, cen[(it + 1) & 1], grp_sizes, grp_offsets, grp_members, s) !=
+                hipSuccess)
             return FREEZE_EHIP;
     }
     LayerCache &L = ctx->layers[layer];

@@ -247,8 +247,10 @@ hipError_t launch_cascade_scatter(const int32_t *labels, const uint8_t *hit, con
                                   int32_t *out_exit, hipStream_t s);
 
 // k-means cache build (the assignment step is the look-up itself)
+// sizes [k], offsets [k + 1] and members [n] int32 are scratch
 hipError_t launch_kmeans_update(const float *points, const int32_t *assign, int64_t n, int64_t d, int64_t k,
-                                const float *old_centers, float *new_centers, hipStream_t s);
+                                const float *old_centers, float *new_centers, int32_t *sizes, int32_t *offsets,
+                                int32_t *members, hipStream_t s);
 hipError_t launch_kmeans_majority(const int32_t *assign, const int32_t *labels, int64_t n, int num_classes, int64_t k,
                                   int32_t *majority, float *fraction, int64_t *sizes, hipStream_t s);
 hipError_t launch_copy_rows_f32(const float *src, int64_t src_stride, float *dst, int64_t rows, int64_t d, hipStream_t s);

@@ -9,39 +9,112 @@
 
 namespace fz {
 
-// New centre of cluster c = blockIdx.x, dimensions blockIdx.y * 256 + threadIdx.x: the mean of
-// the points assigned to it, summed in point order in fp64 and rounded once to fp32 (so the
-// result does not depend on scheduling); a cluster without points keeps its centre.
-// The block walks the assignment list in LDS-sized pieces; whether a point belongs to the
-// cluster is uniform over the block, so the row reads are whole coalesced pieces.
-__global__ __launch_bounds__(256) void kmeans_update_kernel(const float *points, const int32_t *assign, int64_t n,
+// Update step of Lloyd's iterations.  The points are first grouped by the centre they were
+// assigned to, each group in point order (integer work only: the grouping is the same in every
+// run): sizes by a histogram, offsets by a scan, and one workgroup per centre that walks the
+// assignment list and writes its members' ids in order (ballot / popcount compaction; the list is
+// n ints and stays in L2).  Then one workgroup per (centre, 256 dimensions) adds up its members'
+// rows in that order in fp64 and rounds the mean once to fp32, so the result does not depend on
+// scheduling; every point row is read exactly once, in 1 KiB pieces, eight rows in flight per
+// thread.  A cluster without points keeps its centre.
+__global__ __launch_bounds__(256) void kmeans_count_kernel(const int32_t *assign, int64_t n, int64_t k, int32_t *sizes)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) {
+        const int32_t c = assign[i];
+        if ((uint32_t)c < (uint64_t)k) atomicAdd(&sizes[c], 1);
+    }
+}
+
+// offsets[c] = sizes[0] + .. + sizes[c-1], offsets[k] = total; one workgroup
+__global__ __launch_bounds__(1024) void kmeans_offsets_kernel(const int32_t *sizes, int64_t k, int32_t *offsets)
+{
+    __shared__ int wave_tot[16];
+    __shared__ int base_s;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (tid == 0) base_s = 0;
+    __syncthreads();
+    for (int64_t start = 0; start < k; start += 1024) {
+        const int64_t c = start + tid;
+        const int v = c < k ? sizes[c] : 0;
+        int incl = v;   // inclusive scan within the wave
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += o;
+        }
+        if (lane == 63) wave_tot[w] = incl;
+        __syncthreads();
+        int before = base_s;
+        for (int i = 0; i < w; ++i) before += wave_tot[i];
+        if (c < k) offsets[c] = before + incl - v;
+        __syncthreads();
+        if (tid == 1023) base_s = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) offsets[k] = base_s;
+}
+
+// members[offsets[c] ..) = the ids of the points assigned to centre c = blockIdx.x, ascending
+__global__ __launch_bounds__(1024) void kmeans_members_kernel(const int32_t *assign, int64_t n, const int32_t *offsets,
+                                                              int32_t *members)
+{
+    __shared__ int wave_tot[16];
+    const int c = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    int base = offsets[c];
+    if (offsets[c + 1] == base) return;   // uniform: an empty cluster
+    for (int64_t start = 0; start < n; start += 1024) {
+        const int64_t i = start + tid;
+        const bool mine = i < n && assign[i] == c;
+        const uint64_t bal = __ballot(mine);
+        if (lane == 0) wave_tot[w] = __builtin_popcountll(bal);
+        __syncthreads();
+        int before = 0, all = 0;
+        for (int j = 0; j < 16; ++j) {
+            before += j < w ? wave_tot[j] : 0;
+            all += wave_tot[j];
+        }
+        if (mine) members[base + before + __builtin_popcountll(bal & ((1ull << lane) - 1ull))] = (int32_t)i;
+        base += all;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void kmeans_update_kernel(const float *points, const int32_t *offsets, const int32_t *members,
                                                             int64_t d, const float *old_centers, float *new_centers)
 {
-    __shared__ int32_t a_s[2048];
     const int c = blockIdx.x;
     const int64_t dim = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    if (dim >= d) return;
+    const int m0 = offsets[c], m1 = offsets[c + 1];
     double acc = 0.0;
-    int64_t count = 0;
-    for (int64_t base = 0; base < n; base += 2048) {
-        const int len = (int)(n - base < 2048 ? n - base : 2048);
-        __syncthreads();
-        for (int i = threadIdx.x; i < len; i += 256) a_s[i] = assign[base + i];
-        __syncthreads();
-        for (int i = 0; i < len; ++i) {
-            if (a_s[i] == c) {
-                ++count;
-                if (dim < d) acc += (double)points[(base + i) * d + dim];
-            }
-        }
+    int j = m0;
+    for (; j + 8 <= m1; j += 8) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = points[(int64_t)members[j + e] * d + dim];   // eight rows in flight
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc += (double)v[e];                                 // ... added in point order
     }
-    if (dim < d) new_centers[(int64_t)c * d + dim] = count ? (float)(acc / (double)count) : old_centers[(int64_t)c * d + dim];
+    for (; j < m1; ++j) acc += (double)points[(int64_t)members[j] * d + dim];
+    new_centers[(int64_t)c * d + dim] = m1 > m0 ? (float)(acc / (double)(m1 - m0)) : old_centers[(int64_t)c * d + dim];
 }
 
 hipError_t launch_kmeans_update(const float *points, const int32_t *assign, int64_t n, int64_t d, int64_t k,
-                                const float *old_centers, float *new_centers, hipStream_t s)
+                                const float *old_centers, float *new_centers, int32_t *sizes, int32_t *offsets,
+                                int32_t *members, hipStream_t s)
 {
+    hipError_t e = launch_fill_i32(sizes, 0, k, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kmeans_count_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, assign, n, k, sizes);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(kmeans_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes, k, offsets);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(kmeans_members_kernel, dim3((unsigned)k), dim3(1024), 0, s, assign, n, offsets, members);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(kmeans_update_kernel, dim3((unsigned)k, (unsigned)((d + 255) / 256)), dim3(256), 0, s, points,
-                       assign, n, d, old_centers, new_centers);
+                       offsets, members, d, old_centers, new_centers);
     return hipGetLastError();
 }
 
