@@ -22,15 +22,26 @@ _LIB = os.path.join(_HERE, "libfreeze_oracle.so")
 F32, BF16 = 0, 1
 
 
+_LIB_SAN = os.path.join(_HERE, "libfreeze_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc -O2 (no fast-math, no BLAS)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    """Compile the oracle with gcc -O2 (no fast-math, no BLAS).
+
+    With FREEZE_ORACLE_SANITIZE=1 in the environment the same source is built with the address and
+    undefined-behaviour sanitizers instead (the process must then have the sanitizer runtime
+    preloaded: tests/test_oracle_sanitized.py runs the pins that way)."""
+    san = os.environ.get("FREEZE_ORACLE_SANITIZE") == "1"
+    target = _LIB_SAN if san else _LIB
+    stale = (not os.path.exists(target)) or os.path.getmtime(target) < os.path.getmtime(_SRC)
     if force or stale:
-        tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-pthread", "-Wall",
+        tmp = target + ".tmp%d" % os.getpid()
+        flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                 "-fno-sanitize-recover=undefined"] if san else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-std=c11", "-fPIC", "-shared", "-pthread", "-Wall",
                                "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+        os.replace(tmp, target)
+    return target
 
 
 _lib = None
