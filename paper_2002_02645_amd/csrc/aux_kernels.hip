@@ -365,73 +365,84 @@ __device__ __forceinline__ void rescore_short(const FinishArgs &a, const float *
     }
 }
 
-// Exact re-scoring by the whole block of NT threads, 8 candidates at a time (long activations:
-// the query row is read once per 8 candidates and every thread keeps 10 loads in flight; small
-// batches use 1024-thread blocks so that a block per query still fills the memory system).  Same arithmetic as
-// rescore_wave; partial sums are combined wave by wave in a fixed order.
-template <int NT>
-__device__ __forceinline__ void rescore_block(const FinishArgs &a, const float *qrow, const int32_t *idx_s,
-                                              float *dist_s, float (*red)[8], int r, int tid)
+// Exact re-scoring by the whole block of NT threads for long activations, up to RG candidates at
+// once (r <= RG, RG a multiple of 8).  The loop over the activation is the outer one: a thread
+// reads its 8-element pieces of the query row once and applies each to all candidates (a 256 KB
+// query row of a 64 x 32 x 32 activation does not survive in L2 between passes while the candidate
+// rows stream through it: with the row re-read per eight candidates a tenth of the traffic was
+// those re-reads), at the price of RG accumulators per thread.  Small batches use 1024-thread
+// blocks so that a block per query still fills the memory system.  Same arithmetic as
+// rescore_wave: per-thread partial sums in index order, a butterfly over the lanes, then the waves'
+// sums combined in a fixed order.
+template <int NT, int RG>
+__device__ __forceinline__ void rescore_block_all(const FinishArgs &a, const float *qrow, const int32_t *idx_s,
+                                                  float *dist_s, float (*red)[8], int r, int tid)
 {
-    for (int r0 = 0; r0 < r; r0 += 8) {
-        float acc[8];
-        int64_t cand[8];
+    float acc[RG];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            acc[j] = 0.f;
-            cand[j] = idx_s[(r0 + j < r) ? r0 + j : r - 1];
-        }
-#pragma unroll 4
-        for (int64_t i = (int64_t)tid * 8; i < a.d; i += NT * 8) {   // four rounds of loads in flight
-            const f32x4 q0 = *reinterpret_cast<const f32x4 *>(qrow + i);
-            const f32x4 q1 = *reinterpret_cast<const f32x4 *>(qrow + i + 4);
-            const float qv[8] = {q0[0], q0[1], q0[2], q0[3], q1[0], q1[1], q1[2], q1[3]};
-            if (a.c_f32) {
+    for (int j = 0; j < RG; ++j) acc[j] = 0.f;
+    for (int64_t i = (int64_t)tid * 8; i < a.d; i += NT * 8) {
+        const f32x4 q0 = *reinterpret_cast<const f32x4 *>(qrow + i);
+        const f32x4 q1 = *reinterpret_cast<const f32x4 *>(qrow + i + 4);
+        const float qv[8] = {q0[0], q0[1], q0[2], q0[3], q1[0], q1[1], q1[2], q1[3]};
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float *c = a.c_f32 + cand[j] * a.d_pad + i;
-                    const f32x4 c0v = *reinterpret_cast<const f32x4 *>(c);
-                    const f32x4 c1v = *reinterpret_cast<const f32x4 *>(c + 4);
-                    const float cv[8] = {c0v[0], c0v[1], c0v[2], c0v[3], c1v[0], c1v[1], c1v[2], c1v[3]};
+        for (int g = 0; g < RG; g += 8) {
+            if (g < r) {   // uniform
+                if (a.c_f32) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float df = qv[e] - cv[e];
-                        acc[j] = __builtin_fmaf(df, df, acc[j]);
+                    for (int j = 0; j < 8; ++j) {
+                        const float *c = a.c_f32 + (int64_t)idx_s[(g + j < r) ? g + j : r - 1] * a.d_pad + i;
+                        const f32x4 c0v = *reinterpret_cast<const f32x4 *>(c);
+                        const f32x4 c1v = *reinterpret_cast<const f32x4 *>(c + 4);
+                        const float cv[8] = {c0v[0], c0v[1], c0v[2], c0v[3], c1v[0], c1v[1], c1v[2], c1v[3]};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float df = qv[e] - cv[e];
+                            acc[g + j] = __builtin_fmaf(df, df, acc[g + j]);
+                        }
                     }
-                }
-            } else {
+                } else {
+                    uint4 cb[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint4 cb = *reinterpret_cast<const uint4 *>(a.c_rows + cand[j] * a.d_pad + i);
-                    const uint32_t wv[4] = {cb.x, cb.y, cb.z, cb.w};
+                    for (int j = 0; j < 8; ++j)
+                        cb[j] = *reinterpret_cast<const uint4 *>(a.c_rows + (int64_t)idx_s[(g + j < r) ? g + j : r - 1] * a.d_pad + i);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float c_lo = __uint_as_float(wv[e] << 16);
-                        const float c_hi = __uint_as_float(wv[e] & 0xffff0000u);
-                        const float d0 = qv[2 * e] - c_lo;
-                        acc[j] = __builtin_fmaf(d0, d0, acc[j]);
-                        const float d1 = qv[2 * e + 1] - c_hi;
-                        acc[j] = __builtin_fmaf(d1, d1, acc[j]);
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t wv[4] = {cb[j].x, cb[j].y, cb[j].z, cb[j].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float c_lo = __uint_as_float(wv[e] << 16);
+                            const float c_hi = __uint_as_float(wv[e] & 0xffff0000u);
+                            const float d0 = qv[2 * e] - c_lo;
+                            acc[g + j] = __builtin_fmaf(d0, d0, acc[g + j]);
+                            const float d1 = qv[2 * e + 1] - c_hi;
+                            acc[g + j] = __builtin_fmaf(d1, d1, acc[g + j]);
+                        }
                     }
                 }
             }
         }
+    }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            float v = acc[j];
+    for (int g = 0; g < RG; g += 8) {
+        if (g < r) {   // uniform
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-            if ((tid & 63) == 0) red[tid >> 6][j] = v;
+            for (int j = 0; j < 8; ++j) {
+                float v = acc[g + j];
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+                if ((tid & 63) == 0) red[tid >> 6][j] = v;
+            }
+            __syncthreads();
+            if (tid < 8 && g + tid < r) {
+                float t = 0.f;
+#pragma unroll
+                for (int wv = 0; wv < NT / 64; wv += 4)   // fixed order: groups of four waves
+                    t += (red[wv][tid] + red[wv + 1][tid]) + (red[wv + 2][tid] + red[wv + 3][tid]);
+                dist_s[g + tid] = t;
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        if (tid < 8 && r0 + tid < r) {
-            float t = 0.f;
-#pragma unroll
-            for (int wv = 0; wv < NT / 64; wv += 4)   // fixed order: groups of four waves
-                t += (red[wv][tid] + red[wv + 1][tid]) + (red[wv + 2][tid] + red[wv + 3][tid]);
-            dist_s[r0 + tid] = t;
-        }
-        __syncthreads();
     }
 }
 
@@ -700,9 +711,21 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKer
         __syncthreads();
 
         // 2. exact fp32 re-scoring: each wave takes a group of candidates and needs no block barrier
-        if (a.d >= 4096 && a.d % 8 == 0)
-            rescore_block<NT>(a, qrow, idx_s, dist_s, red, m, tid);
-        else if (tid < 256) {   // short activations: four waves, one group of candidates each
+        if (a.d >= 4096 && a.d % 8 == 0) {
+            // long activations: the whole block per candidate, the query row read once
+            if (WIDER) {
+                for (int c0 = 0; c0 < m; c0 += 32)
+                    rescore_block_all<NT, 32>(a, qrow, idx_s + c0, dist_s + c0, red, m - c0 < 32 ? m - c0 : 32, tid);
+            } else if (m <= 16) {
+                rescore_block_all<NT, 16>(a, qrow, idx_s, dist_s, red, m, tid);
+            } else if (m <= 32) {
+                rescore_block_all<NT, 32>(a, qrow, idx_s, dist_s, red, m, tid);
+            } else {
+                // (two passes of 32: 64 accumulators per thread spill, and the pass is 8 % slower for it)
+                rescore_block_all<NT, 32>(a, qrow, idx_s, dist_s, red, 32, tid);
+                rescore_block_all<NT, 32>(a, qrow, idx_s + 32, dist_s + 32, red, m - 32, tid);
+            }
+        } else if (tid < 256) {   // short activations: four waves, one group of candidates each
             if (m <= 16)
                 rescore_wave<4>(a, qrow, idx_s, dist_s, m, tid >> 6, tid & 63);
             else if (m <= 32)
@@ -1099,9 +1122,10 @@ __global__ __launch_bounds__(256) void exact_scan_kernel(ScanArgs sa)
             if (tid < m) idx_s[tid] = base + tid;
             if (tid == 0) surv_s = 0;
             __syncthreads();
-            if (a.d >= 4096 && a.d % 8 == 0)
-                rescore_block<256>(a, qrow, idx_s, dist_s, red, m, tid);
-            else
+            if (a.d >= 4096 && a.d % 8 == 0) {
+                for (int c0 = 0; c0 < m; c0 += 32)
+                    rescore_block_all<256, 32>(a, qrow, idx_s + c0, dist_s + c0, red, m - c0 < 32 ? m - c0 : 32, tid);
+            } else
                 rescore_wave<16>(a, qrow, idx_s, dist_s, m, tid >> 6, tid & 63);
             __syncthreads();
             // entries that beat the k-th best so far, then the k best of those and the list
