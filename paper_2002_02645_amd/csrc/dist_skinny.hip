@@ -44,28 +44,12 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
 namespace {
 
-// LDS-direct 16-byte load: lane i reads 16 bytes at sbase + voff (scalar 64-bit base, 32-bit
-// per-lane offset) and they land in LDS at lds_byte_addr + 16 i (M0 = wave-uniform destination).
-__device__ __forceinline__ void load16_global_to_lds(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
-}
-__device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
-{
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
 __device__ __forceinline__ void load4_global_to_lds(const void *g, uint32_t lds_byte_addr)
 {
     // lane i lands at +4*i
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_byte_addr), "v"(g)
                  : "memory", "m0");
 }
-template <int N>
-__device__ __forceinline__ void wait_global_loads_le() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
 constexpr int kQRows = kSkinnyRows;        // query rows held in LDS (the MFMA's rows 16..31 are zero registers)
 constexpr int kStage = kTileN * kKB * 2;   // 16 KiB: one k-block of one cache tile
 constexpr int kNormBuf = 2 * 8 * 256;      // 4 KiB: per tile parity and wave, 64 floats
@@ -119,8 +103,8 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
         // 16 KiB = 16 wave-instructions of 1 KiB: two per wave
         const uint64_t src = stream + (size_t)gstep * kStage;
         const uint32_t dst = smem_base + RING + slot * kStage + w * 1024;
-        load16_global_to_lds(src, lane_off, dst);
-        load16_global_to_lds(src + 8192, lane_off, dst + 8192);
+        load16_global_to_lds_nt(src, lane_off, dst);   // every byte of the cache is read once
+        load16_global_to_lds_nt(src + 8192, lane_off, dst + 8192);
     };
     constexpr int LPS = 2;   // loads per wave and stage
     // norms of this wave's 32 entries of tile `t` -> normbuf[t & 1][w][lane] (lanes 32..63 duplicate)

@@ -50,31 +50,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 
-// LDS-direct 16-byte load: lane i reads 16 bytes at sbase + voff (scalar 64-bit base, 32-bit
-// per-lane offset: half the address traffic of a 64-bit per-lane pointer) and they land in LDS at
-// lds_byte_addr + 16 i.  M0 carries the wave-uniform LDS destination.
-__device__ __forceinline__ void load16_global_to_lds(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
-}
-// the same with the non-temporal hint (data that no other workgroup will ask for again)
-__device__ __forceinline__ void load16_global_to_lds_nt(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
-                 : "memory", "m0");
-}
-__device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
-{
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-
-// Wait until at most N of this wave's global loads are outstanding (loads complete in order).
-template <int N>
-__device__ __forceinline__ void wait_global_loads_le() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
 template <int BM_, int BK_, int RMAX_, int NS_, int WN_ = 4, bool B_ONCE_ = false>
 struct DistCfg {
     static constexpr int BM = BM_, BN = kTileN, BK = BK_, RMAX = RMAX_;

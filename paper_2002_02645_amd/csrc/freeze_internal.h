@@ -39,6 +39,32 @@ __device__ __forceinline__ uint16_t bf16_rne(float x)
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
+// LDS-direct 16-byte load: lane i reads 16 bytes at sbase + voff (scalar 64-bit base, 32-bit
+// per-lane offset: half the address traffic of a 64-bit per-lane pointer) and they land in LDS at
+// lds_byte_addr + 16 i.  M0 carries the wave-uniform LDS destination.  Issued through inline asm:
+// the compiler would otherwise order every LDS read behind the outstanding direct loads; the
+// kernels count their loads themselves (wait_global_loads_le).
+__device__ __forceinline__ void load16_global_to_lds(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+// the same with the non-temporal hint (data that no other workgroup will ask for again)
+__device__ __forceinline__ void load16_global_to_lds_nt(uint64_t sbase, uint32_t voff, uint32_t lds_byte_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_byte_addr), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t x)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+// Wait until at most N of this wave's global loads are outstanding (loads complete in order).
+template <int N>
+__device__ __forceinline__ void wait_global_loads_le() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
 constexpr int kMaxRescore = 64;  // largest re-scoring width R
 constexpr int kMaxK = 64;
 constexpr int kMaxMergeEntries = 8192;  // n_splits * R gathered per query in the finishing kernel

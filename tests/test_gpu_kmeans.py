@@ -24,47 +24,100 @@ def _points(n, d, classes, seed, sigma=1.0):
     return pts.contiguous(), lab.contiguous()
 
 
-def _no_assignment_near_tie(pts, centers, rel=3e-6):
-    d2 = ((pts[:, None, :].astype(np.float64) - centers[None].astype(np.float64)) ** 2).sum(-1)
-    part = np.partition(d2, 1, axis=1)
-    return bool(((part[:, 1] - part[:, 0]) > rel * part[:, 1]).all())
+REL = 1e-4   # the look-up's near-tie tolerance: two distances closer than this may rank either way
 
 
-@pytest.mark.parametrize("n,d,kc,classes,iters", [
-    (3002, 96, 20, 5, 3),       # several cache tiles of points, one tile of centres
-    (5000, 520, 300, 7, 2),     # more than one tile of centres, d not a multiple of 64
-    (700, 40, 700, 3, 1),       # as many centres as points: every cluster is its own point
-    (2000, 64, 8, 4, 0),        # no iteration: labels and shares for the given centres
+def _subset_means(pts, fixed, free):
+    """Means (float32) of the rows `fixed` plus every subset of the rows `free`, summed in point order in fp64."""
+    out = []
+    for mask in range(1 << len(free)):
+        members = sorted(list(fixed) + [free[j] for j in range(len(free)) if mask >> j & 1])
+        if not members:
+            out.append(None)
+            continue
+        acc = np.zeros(pts.shape[1], dtype=np.float64)
+        for i in members:
+            acc += pts[i].astype(np.float64)
+        out.append((members, (acc / float(len(members))).astype(np.float32)))
+    return out
+
+
+def _check_round(pts, lab, classes, cen_prev, cen_next=None, majority=None, fraction=None):
+    """One round of Lloyd's iteration from the centres `cen_prev`, by the oracle's distances, under a
+    defined rule for near-ties: a point whose two nearest centres are within REL (relative) of each
+    other may be assigned to either of the two; every other point goes to its nearest centre (lower
+    index on exactly equal distances cannot occur outside the tolerance).  A cluster no such point
+    can reach must come out exactly as the oracle computes it; a cluster some can reach must equal
+    the oracle's result for ONE choice of which of them it receives (every subset is tried).
+    Checks the next centres (cen_next) and / or the majority labels and shares.  Returns the number
+    of points that were free to go either way."""
+    K = cen_prev.shape[0]
+    idx2, d2, _ = fo.knn(pts, np.ascontiguousarray(cen_prev, dtype=np.float32), min(2, K))
+    free = np.zeros(pts.shape[0], bool) if K == 1 else (d2[:, 1] - d2[:, 0]) <= REL * d2[:, 1]
+    nearest = idx2[:, 0]
+    for c in range(K):
+        fixed = np.nonzero(~free & (nearest == c))[0].tolist()
+        reach = np.nonzero(free & ((idx2[:, 0] == c) | (idx2[:, min(1, K - 1)] == c)))[0].tolist()
+        assert len(reach) <= 10, "too many near-tie points around one centre for an exhaustive check"
+        options = _subset_means(pts, fixed, reach)
+        if cen_next is not None:
+            ok = False
+            for opt in options:
+                want = cen_prev[c] if opt is None else opt[1]      # an empty cluster keeps its centre
+                ok = ok or np.allclose(cen_next[c], want, rtol=1e-6, atol=1e-7)
+            assert ok, f"centre {c}: no assignment of its {len(reach)} near-tie points gives the reported mean"
+        if majority is not None:
+            ok = False
+            for opt in options:
+                if opt is None:
+                    ok = ok or (majority[c] == 0 and fraction[c] == 0.0)
+                    continue
+                counts = np.bincount(lab[opt[0]], minlength=classes)
+                best = int(np.argmax(counts))                       # first maximum: the smaller label
+                ok = ok or (majority[c] == best and fraction[c] == np.float32(float(counts[best]) / float(len(opt[0]))))
+            assert ok, f"centre {c}: majority label / share match no assignment of its near-tie points"
+    return int(free.sum())
+
+
+@pytest.mark.parametrize("n,d,kc,classes,iters,plant", [
+    (3002, 96, 20, 5, 3, False),      # several cache tiles of points, one tile of centres
+    (5000, 520, 300, 7, 2, False),    # more than one tile of centres, d not a multiple of 64
+    (700, 40, 700, 3, 1, False),      # as many centres as points: every cluster is its own point
+    (2000, 64, 8, 4, 0, False),       # no iteration: labels and shares for the given centres
+    (1500, 48, 12, 4, 2, True),       # points planted (nearly) halfway between two centres: near-tie assignments
 ])
-def test_kmeans_build_and_lookup_against_oracle(n, d, kc, classes, iters):
-    pts, lab = _points(n, d, classes, 900 + n + kc)   # (sizes chosen so that the seeded run has no near-tie)
+def test_kmeans_build_and_lookup_against_oracle(n, d, kc, classes, iters, plant):
+    pts, lab = _points(n, d, classes, 900 + n + kc)
     init = pts[:kc].clone()
-    ref = fo.kmeans_build(pts.numpy(), lab.numpy(), classes, init.numpy(), iters)
-    # the comparison below needs the same assignments on both sides: no point may sit (nearly)
-    # halfway between two centres in any round of the oracle's run
-    cen = init.numpy().copy()
-    for _ in range(iters + 1):
-        assert _no_assignment_near_tie(pts.numpy(), cen), "choose another seed: an assignment is a near-tie"
-        a, _ = fo.kmeans_assign(pts.numpy(), cen)
-        new = cen.copy()
-        for c in range(kc):
-            m = np.nonzero(a == c)[0]
-            if m.size:
-                new[c] = (pts.numpy()[m].astype(np.float64).sum(axis=0) / m.size).astype(np.float32)
-        cen = new
+    if plant:
+        for j in range(4):     # within 1e-6 of the midpoint of two initial centres: either assignment is right
+            pts[kc + j] = (init[2 * j] + init[2 * j + 1]) * 0.5 + 1e-6 * (j - 1.5) * (init[2 * j + 1] - init[2 * j])
+    pts_h, lab_h = pts.numpy(), lab.numpy().astype(np.int64)
     fc = binding.FreezeCache(1)
     try:
-        got = fc.build_kmeans_layer(0, pts.cuda(), lab.cuda(), classes, init.cuda(), iters)
+        # round by round: the library's centres after t rounds are the start of the oracle's round t + 1
+        runs = [fc.build_kmeans_layer(0, pts.cuda(), lab.cuda(), classes, init.cuda(), t) for t in range(iters + 1)]
         torch.cuda.synchronize()
-        cen_g = got["centers"].cpu().numpy()
-        # same assignments, sums in the same order in fp64, one rounding: the centres agree to the last bit or two
-        assert np.allclose(cen_g, ref["centers"], rtol=1e-6, atol=1e-7)
-        assert np.array_equal(got["majority"].cpu().numpy(), ref["majority"])
-        assert np.array_equal(got["fraction"].cpu().numpy(), ref["fraction"])
+        cens = [r["centers"].cpu().numpy() for r in runs]
+        assert np.array_equal(cens[0], init.numpy())
+        free_total = 0
+        for t in range(iters):
+            free_total += _check_round(pts_h, lab_h, classes, cens[t], cen_next=cens[t + 1])
+        got = runs[iters]
+        free_total += _check_round(pts_h, lab_h, classes, cens[iters], majority=got["majority"].cpu().numpy(),
+                                   fraction=got["fraction"].cpu().numpy())
+        assert free_total > 0 or not plant       # the planted case exercises the near-tie rule
+        cen_g = cens[iters]
+        ref = dict(majority=got["majority"].cpu().numpy(), fraction=got["fraction"].cpu().numpy())
+        if free_total == 0:
+            # no near-tie anywhere: the whole build equals the oracle's own run from the same start
+            full = fo.kmeans_build(pts_h, lab_h, classes, init.numpy(), iters)
+            assert np.allclose(cen_g, full["centers"], rtol=1e-6, atol=1e-7)
+            assert np.array_equal(ref["majority"], full["majority"]) and np.array_equal(ref["fraction"], full["fraction"])
         # look-ups: fresh points, and some exactly on a centre
         q, _ = _points(300, d, classes, 77 + n)
         q[:5] = got["centers"][:5].cpu()
-        exp = fo.kmeans_lookup(q.numpy(), ref["centers"], ref["majority"], ref["fraction"], 0.0)
+        exp = fo.kmeans_lookup(q.numpy(), cen_g, ref["majority"], ref["fraction"], 0.0)
         finite = np.isfinite(exp["conf"])
         thr = float(np.float32(np.median(exp["conf"][finite])))
         exp = fo.kmeans_lookup(q.numpy(), cen_g, ref["majority"], ref["fraction"], thr)
