@@ -298,9 +298,11 @@ int freeze_lookup_stats_attach(freeze_ctx *ctx, void *counters);
 /*
  * Stage timing for benchmarks (measurement aid; the look-up results do not depend on it).
  * While enabled, freeze_lookup records HIP events on its stream around its three stages
- * (query preparation, distance pass, finishing kernel) for up to FREEZE_PROFILE_MAX_CALLS
- * calls.  freeze_profile_read waits for the recorded events, adds up the stage durations
- * and clears the record.
+ * (query preparation, distance pass, finishing kernels) for up to FREEZE_PROFILE_MAX_CALLS
+ * calls; enable = 1: all four stage boundaries; enable = 2: only the two around the distance
+ * pass (an event costs a few microseconds of stream time, which shows next to a 0.2 ms look-up;
+ * the other two stages then read 0); enable = 0: off.  freeze_profile_read waits for the recorded
+ * events, adds up the stage durations and clears the record.
  *   stage_ms  host array [3]: summed milliseconds of {prep, distance pass, finish}.
  *   calls     host: number of look-ups the sums cover.
  * Events are host-side objects; no device memory is allocated.

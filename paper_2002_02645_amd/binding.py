@@ -324,7 +324,8 @@ def freeze_lookup_stats_attach(ctx, counters: Optional[torch.Tensor]) -> None:
     _check(lib().freeze_lookup_stats_attach(ctx, _ptr(counters)), "freeze_lookup_stats_attach")
 
 
-def freeze_profile_enable(ctx, enable: bool) -> None:
+def freeze_profile_enable(ctx, enable) -> None:
+    """enable: 0 / False off, 1 / True events at every stage boundary, 2 events around the distance pass only."""
     _check(lib().freeze_profile_enable(ctx, int(enable)), "freeze_profile_enable")
 
 

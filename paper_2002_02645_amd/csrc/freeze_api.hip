@@ -15,7 +15,8 @@ struct freeze_ctx {
     std::vector<LayerCache> layers;
     int num_cus = 256;
     // stage timing (measurement aid): 4 events per recorded look-up
-    bool profile = false;
+    int profile = 0;          // 0: off; 1: events at all four stage boundaries; 2: around the distance pass only
+    int profile_recorded = 0; // mode the recorded look-ups were taken in
     std::vector<hipEvent_t> events;
     int profiled_calls = 0;
     unsigned long long *stats = nullptr;   // device counters of the certificate's verdicts, or null
@@ -205,7 +206,7 @@ struct StageMarks {
     }
     void mark(int i)
     {
-        if (slot >= 0) (void)hipEventRecord(ctx->events[slot + i], s);
+        if (slot >= 0 && (ctx->profile == 1 || i == 1 || i == 2)) (void)hipEventRecord(ctx->events[slot + i], s);
     }
     void done()
     {
@@ -979,7 +980,9 @@ int freeze_lookup_stats_attach(freeze_ctx *ctx, void *counters)
 int freeze_profile_enable(freeze_ctx *ctx, int enable)
 {
     if (!ctx) return FREEZE_EINVAL;
-    ctx->profile = enable != 0;
+    if (enable < 0 || enable > 2) return FREEZE_EINVAL;
+    ctx->profile = enable;
+    if (enable) ctx->profile_recorded = enable;
     ctx->profiled_calls = 0;
     return FREEZE_OK;
 }
@@ -988,9 +991,10 @@ int freeze_profile_read(freeze_ctx *ctx, float *stage_ms, int *calls)
 {
     if (!ctx || !stage_ms || !calls) return FREEZE_EINVAL;
     stage_ms[0] = stage_ms[1] = stage_ms[2] = 0.f;
+    const bool light = ctx->profile_recorded == 2;   // only the distance pass was bracketed
     for (int c = 0; c < ctx->profiled_calls; ++c) {
-        if (hipEventSynchronize(ctx->events[4 * c + 3]) != hipSuccess) return FREEZE_EHIP;
-        for (int i = 0; i < 3; ++i) {
+        if (hipEventSynchronize(ctx->events[4 * c + (light ? 2 : 3)]) != hipSuccess) return FREEZE_EHIP;
+        for (int i = light ? 1 : 0; i < (light ? 2 : 3); ++i) {
             float ms = 0.f;
             if (hipEventElapsedTime(&ms, ctx->events[4 * c + i], ctx->events[4 * c + i + 1]) != hipSuccess)
                 return FREEZE_EHIP;
@@ -1006,12 +1010,16 @@ int freeze_profile_read_calls(freeze_ctx *ctx, float *call_ms, int max_calls, in
 {
     if (!ctx || !call_ms || !calls || max_calls < 0) return FREEZE_EINVAL;
     const int n = ctx->profiled_calls < max_calls ? ctx->profiled_calls : max_calls;
+    const bool light = ctx->profile_recorded == 2;
     for (int c = 0; c < n; ++c) {
-        if (hipEventSynchronize(ctx->events[4 * c + 3]) != hipSuccess) return FREEZE_EHIP;
-        for (int i = 0; i < 3; ++i)
+        if (hipEventSynchronize(ctx->events[4 * c + (light ? 2 : 3)]) != hipSuccess) return FREEZE_EHIP;
+        for (int i = 0; i < 3; ++i) {
+            call_ms[3 * c + i] = 0.f;
+            if (light && i != 1) continue;
             if (hipEventElapsedTime(&call_ms[3 * c + i], ctx->events[4 * c + i], ctx->events[4 * c + i + 1]) !=
                 hipSuccess)
                 return FREEZE_EHIP;
+        }
     }
     *calls = n;
     ctx->profiled_calls = 0;
