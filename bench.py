@@ -380,8 +380,19 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    def copy_calibration():
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.bitwise_not(src, out=dst)   # a plain elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        return 1 << 30
+
     if args.next_rows:
-        print(json.dumps(time_next_rows(torch, binding, dev)))
+        res = time_next_rows(torch, binding, dev)
+        if args.copy_calibration:
+            res["copy_calibration_bytes"] = copy_calibration()
+        print(json.dumps(res))
         return 0
 
     head = args.workload or "c2_batched"
@@ -420,12 +431,7 @@ def main() -> int:
                                  "pure_mfma_loop_TFLOPs": round(tf, 1), "shader_clock_MHz_under_mfma": round(mhz),
                                  "pure_read_1GiB_GBs": round(gbs, 1)}
     if args.copy_calibration:
-        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.bitwise_not(src, out=dst)   # a plain elementwise kernel: reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        result["config"]["copy_calibration_bytes"] = 1 << 30
+        result["config"]["copy_calibration_bytes"] = copy_calibration()
     print(json.dumps(result))
     return 0
 

@@ -1184,22 +1184,24 @@ __global__ __launch_bounds__(256) void exact_scan_kernel(ScanArgs sa)
 }
 
 static int scan_max_splits(int k) { return kMaxMergeEntries / k < kScanMaxSplits ? kMaxMergeEntries / k : kScanMaxSplits; }
-static int scan_grid(int num_cus) { return 2 * num_cus; }
+// (a small-batch look-up flags at most 16 queries and pays for this launch out of 0.2 ms: a smaller grid)
+static int scan_grid(int num_cus, int64_t b) { return b <= kSkinnyRows ? (num_cus >= 4 ? num_cus / 2 : 2) : 2 * num_cus; }
 
 size_t scan_scratch_entries(int64_t b, int k, int num_cus)
 {
     // items = flagged queries x ranges <= max(b, grid)
-    const int64_t items = b > scan_grid(num_cus) ? b : scan_grid(num_cus);
+    const int64_t items = b > scan_grid(num_cus, b) ? b : scan_grid(num_cus, b);
     return (size_t)items * (size_t)k;
 }
 
 hipError_t launch_exact_scan(const FinishArgs &a, int32_t *tickets, uint64_t *part_x, int num_cus, hipStream_t s)
 {
     if (!a.flag_count || !a.flag_list2 || !tickets || !part_x || a.k < 1 || a.k > kMaxK) return hipErrorInvalidValue;
-    ScanArgs sa{a, tickets, part_x, scan_max_splits(a.k)};
+    const int grid = scan_grid(num_cus, a.b);
+    ScanArgs sa{a, tickets, part_x, scan_max_splits(a.k) < grid ? scan_max_splits(a.k) : grid};
     int cap = 512;
     while (cap < sa.max_splits * a.k) cap <<= 1;
-    hipLaunchKernelGGL(exact_scan_kernel, dim3((unsigned)scan_grid(num_cus)), dim3(256), (size_t)cap * sizeof(uint64_t), s, sa);
+    hipLaunchKernelGGL(exact_scan_kernel, dim3((unsigned)grid), dim3(256), (size_t)cap * sizeof(uint64_t), s, sa);
     return hipGetLastError();
 }
 

@@ -114,3 +114,32 @@ def test_certificate_confirms_the_papers_kind_of_data_at_the_default_width():
     missed, confirmed, wrong = _run(q, c, True, 10, 16)
     assert missed == 0 and wrong == 0
     assert confirmed >= 114, confirmed       # >= 95 %: the slower paths stay rare
+
+
+def _misses_with_centring(q, c, k, r, centre):
+    """Queries whose coarse top-r misses a true neighbour when both sides are shifted by the cache's
+    mean vector before the bf16 rounding (distances do not change under a common shift; the stored
+    values are still the cache, so the shifted bf16 copy is a second, rounded copy of it)."""
+    n = c.shape[0]
+    mu = c.astype(np.float64).mean(axis=0).astype(np.float32) if centre else np.float32(0.0)
+    kap = _coarse_keys(q - mu, _bf16(c - mu), True)
+    true_idx, _ = _exact_order(q, c, k)
+    ar = np.arange(n)
+    missed = 0
+    for i in range(q.shape[0]):
+        cand = np.lexsort((ar, kap[i]))[:r]
+        missed += not set(true_idx[i].tolist()) <= set(cand.tolist())
+    return missed
+
+
+def test_centring_trial_helps_offset_data_only():
+    """The trial behind the decision not to centre: subtracting the cache's mean before rounding removes
+    the misses on clusters far from the origin, and gains nothing on post-ReLU class-clustered
+    activations stored in bf16 (there the shifted copy has a rounding error the stored one does not)."""
+    rng = np.random.default_rng(21)
+    q, c = _clustered(rng, 4000, 64, 150, 1.0, False, 100.0, True)
+    assert _misses_with_centring(q, c, 10, 16, False) > 0
+    assert _misses_with_centring(q, c, 10, 16, True) == 0
+    q, c = _clustered(rng, 8000, 1024, 100, 0.8, True, 0.0, True)
+    plain, centred = _misses_with_centring(q, c, 10, 11, False), _misses_with_centring(q, c, 10, 11, True)
+    assert centred >= plain - 2, (plain, centred)       # no gain worth a second copy of the cache
