@@ -237,7 +237,8 @@ def run_workload(torch, np, binding, synth, dev, name, steps, warmup, cache_copi
                         frac=round(achieved / PEAK_HBM_GBS, 4), traffic=None)
     roofline["kernel"] = "dist_skinny_kernel" if skinny else "dist_topr_kernel"
     roofline["kernel_ms"] = round(dist_ms, 4)
-    roofline["traffic"] = measured_traffic(roofline["kernel"], wl.name)
+    # (a cascade's profile averages the kernel over its four layers: no per-layer traffic figure)
+    roofline["traffic"] = None if cascade else measured_traffic(roofline["kernel"], wl.name)
     roofline["traffic_source"] = (f"profiles/{roofline['kernel']}_{wl.name}.txt (rocprofv3 counters of an earlier run of "
                                   "this command; not measured in this run)") if roofline["traffic"] else None
     # stage breakdown from the run with events at every stage boundary (after the timed region)

@@ -10,11 +10,12 @@
 //     and writes, per block of 32 entries, only the smallest (key, index) pair of the block
 //     (8 bytes per 32 entries and query against 64 d bytes read): stores share the counter the
 //     kernel waits on for its loads, so every store it does not make keeps the stream running.
-//  2. The finishing kernel of this path (skinny_finish_kernel, with the other finishing code)
+//  2. The finishing kernel of this path (skinny_tail_kernel, with the other finishing code)
 //     finds the R-th smallest block minimum T.  R blocks hold an entry <= T, so the R-th
 //     smallest entry overall is <= T, and every entry <= T lies in one of exactly those R
 //     blocks: their 32 R entries are a superset of the R best.  It re-scores all of them
-//     exactly in fp32 (d <= 1024: one KiB or two per entry) and keeps the k nearest.
+//     exactly in fp32 (d <= 1024: one KiB or two per entry), keeps the k nearest, and checks
+//     that no entry outside those blocks can be nearer (every one has a key >= T).
 // The threshold kernel at the end of this file serves the keys-out variant of the tiled kernel
 // (one query tile), where the keys are materialised: block_threshold_kernel finds, per query, the
 // R-th smallest block minimum T and collects the entries with (key, index) <= T (at most 32 R,
