@@ -150,7 +150,40 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
     const int64_t pair_chunks = d_pad / 4;   // 16-byte chunks of the two rows together
     const int64_t per = ((pair_chunks + gridDim.y - 1) / gridDim.y + 255) / 256 * 256;   // chunks per block of the pair
     const int64_t jj_end = (blockIdx.y + 1) * per < pair_chunks ? (blockIdx.y + 1) * per : pair_chunks;
-    for (int64_t jj = blockIdx.y * per + threadIdx.x; jj < jj_end; jj += 256) {
+    // one 16-byte chunk of the bf16 copy from 8 fp32 values
+    auto convert_store = [&](int64_t j, const float (&x)[8]) {
+        uint16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = bf16_rne(x[e]);
+        uint4 v;
+        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
+        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+        tile_base[tiled_chunk_offset(rit, j, bm)] = v;
+    };
+    int64_t jj = blockIdx.y * per + threadIdx.x;
+    // whole rows of 16-byte aligned values: four steps' loads are issued before the first is
+    // converted, so that a thread keeps 128 bytes of reads in flight
+    if (src && vec && d == d_pad) {
+        for (; jj + 3 * 256 < jj_end; jj += 4 * 256) {
+            f32x4 v0[4], v1[4];
+            int64_t jc[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t ju = jj + u * 256;
+                jc[u] = (ju >> 3) * 4 + (ju & 3);
+                v0[u] = *reinterpret_cast<const f32x4 *>(src + jc[u] * 8);
+                v1[u] = *reinterpret_cast<const f32x4 *>(src + jc[u] * 8 + 4);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float x[8] = {v0[u][0], v0[u][1], v0[u][2], v0[u][3], v1[u][0], v1[u][1], v1[u][2], v1[u][3]};
+                convert_store(jc[u], x);
+            }
+        }
+    }
+    for (; jj < jj_end; jj += 256) {
         const int64_t j = (jj >> 3) * 4 + (jj & 3);   // chunk of 8 elements within the row
         const int64_t i0 = j * 8;
         float x[8];
@@ -166,15 +199,7 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] = (src && i0 + e < d) ? src[i0 + e] : 0.f;
         }
-        uint16_t h[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = bf16_rne(x[e]);
-        uint4 v;
-        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
-        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
-        tile_base[tiled_chunk_offset(rit, j, bm)] = v;
+        convert_store(j, x);
     }
 }
 
