@@ -1,6 +1,9 @@
 // Kernels around the distance pass: cache ingest, query preparation, the finishing
-// kernel (merge of per-split candidate lists, exact fp32 re-scoring, final top-k, label
-// vote, hit decision), miss compaction and the cascade's scatter.  gfx950 only.
+// kernels (merge of per-split candidate lists, exact fp32 re-scoring, final top-k, the
+// certificate that no entry outside the candidates can be nearer, label vote, hit decision;
+// the wider re-scoring and the exact fp32 scan for queries the certificate does not confirm;
+// the one-launch finish of the small-batch path), miss compaction, the cascade's scatter, the
+// row gather and the threshold calibration.  gfx950 only.
 #include "freeze_internal.h"
 #include "select_common.h"
 

@@ -126,15 +126,24 @@ def _verdicts(fc):
     return c
 
 
-@pytest.mark.parametrize("b,store_bf16", [(300, True), (300, False), (6, True)])
-def test_clusters_far_from_the_origin(b, store_bf16):
+@pytest.mark.parametrize("b,store_bf16,n,d,k", [
+    (300, True, 4000, 64, 10),      # fused kernel; most queries need the wider re-scoring or the exact scan
+    (300, False, 4000, 64, 10),     # ... with the cache stored in fp32
+    (6, True, 4000, 64, 10),        # small-batch kernel: few flagged queries, each scanned by many workgroups
+    (3000, True, 20000, 64, 10),    # more flagged queries than the exact scan has workgroups: several per workgroup
+    (40, True, 3000, 2048, 10),     # keys-out kernel, long rows: the scan's whole-block re-scoring
+    (25, False, 2500, 4104, 5),     # ... fp32 cache, ragged depth
+    (200, True, 5000, 96, 64),      # k = 64: the scan's lists at their longest
+])
+def test_clusters_far_from_the_origin(b, store_bf16, n, d, k):
     """Every coordinate offset by +100: the bf16 keys (|c|^2 - 2 q.c, both of order 10^6) cannot tell
     neighbours whose distances differ by a few units apart, so the coarse candidates miss true
     neighbours for many queries.  The certificate must notice every such query and the wider
     re-scoring or the exact scan must repair it: the results equal the oracle's."""
-    wl = synth.scaled(synth.WORKLOADS["c1_tiny"], n=4000, batch=b)
-    spec = type(wl.layers[0])(4000, 64, 10, 1.0, store_bf16=store_bf16)
-    data = synth.make_workload(type(wl)(wl.name, (spec,), b, 10, (8,), 0, 991))
+    wl = synth.scaled(synth.WORKLOADS["c1_tiny"], n=n, batch=b)
+    spec = type(wl.layers[0])(n, d, 10, 1.0, store_bf16=store_bf16)
+    thr = max(1, k - 2)
+    data = synth.make_workload(type(wl)(wl.name, (spec,), b, k, (thr,), 0, 991))
     L = data.layers[0]
     ent = (L.entries.float() + 100.0).to(L.entries.dtype)
     q = data.queries[0] + 100.0
@@ -142,17 +151,44 @@ def test_clusters_far_from_the_origin(b, store_bf16):
     try:
         counters = _verdicts(fc)
         fc.build_layer(0, ent.cuda(), L.labels.cuda(), 10)
-        out = fc.lookup(0, q.cuda(), 10, 8)
+        out = fc.lookup(0, q.cuda(), k, thr)
         torch.cuda.synchronize()
         got = {key: v.cpu().numpy() for key, v in out.items()}
         c = counters.cpu().numpy()
     finally:
         fc.close()
     e_h, l_h, q_h = _host_entries(ent), L.labels.numpy(), q.numpy()
-    ref = parity.oracle_reference(q_h, e_h, l_h, 10, 10, 8)
-    parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, 10, 8, rel=TIGHT, dist_rel=TIGHT)
+    ref = parity.oracle_reference(q_h, e_h, l_h, 10, k, thr)
+    parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, k, thr, rel=TIGHT, dist_rel=TIGHT)
     assert c.sum() == b
     assert c[1] + c[2] > 0, "this input is meant to defeat the coarse ranking"
+
+
+def test_cascade_on_clusters_far_from_the_origin():
+    """The cascade's later layers run on the device-side miss list: the flagged queries' positions go
+    through that list on their way to the wider re-scoring and the exact scan."""
+    wl = synth.scaled(synth.WORKLOADS["c4_cascade_noisy"], n=2500, d_div=512, batch=400)
+    data = synth.make_workload(wl)
+    nl = len(wl.layers)
+    ents = [(L.entries.float() + 100.0).to(L.entries.dtype) for L in data.layers]
+    qs = [q + 100.0 for q in data.queries]
+    fc = binding.FreezeCache(nl)
+    try:
+        counters = _verdicts(fc)
+        for l, L in enumerate(data.layers):
+            fc.build_layer(l, ents[l].cuda(), L.labels.cuda(), L.spec.num_classes)
+        out = fc.lookup_cascade(list(range(nl)), [q.cuda() for q in qs], wl.k, list(wl.vote_thresholds), wl.rescore_r)
+        torch.cuda.synchronize()
+        got = {key: v.cpu().numpy() for key, v in out.items()}
+        c = counters.cpu().numpy()
+    finally:
+        fc.close()
+    exp_l, exp_x, exp_h, _ = fo.cascade([q.numpy() for q in qs], [_host_entries(e) for e in ents],
+                                        [L.labels.numpy() for L in data.layers],
+                                        [L.spec.num_classes for L in data.layers], wl.k, wl.vote_thresholds)
+    assert np.array_equal(got["exit_layer"], exp_x) and np.array_equal(got["label"], exp_l)
+    assert got["hits_per_layer"].tolist() == exp_h.tolist()
+    assert len(set(exp_x.tolist())) >= 3 and c[1] + c[2] > 0
 
 
 def test_certificate_verdicts_on_clustered_data():
