@@ -588,7 +588,7 @@ struct FinishKernelArgs {
 // the entries when the cache is stored in fp32; fp32 accumulation), so e_j = kappa_j - dist_j
 // samples (error - |q|^2) on entries as near to the query as any that could have been missed.  With
 // mean and standard deviation sd of the e_j, an excluded entry has, under that error distribution,
-//     distance >= kappa_excl - mean - z sd sqrt(1 + 1/m),
+//     distance >= kappa_excl - mean - z (1 + 4/m) sd sqrt(1 + 1/m),
 // and when this exceeds dk no excluded entry can be among the k nearest: the result is the exact
 // one.  z = kCertZ; the estimate needs kCertMinSamples samples from as many distinct distances
 // (duplicated rows repeat one sample).  Otherwise the verdict is "unconfirmed" and the caller
@@ -621,7 +621,9 @@ __device__ __forceinline__ bool certificate(const uint64_t *ent, const float *di
                 var = var > 0.0 ? var : 0.0;
                 const double mean = e0 + mean_rel;
                 const double kex = (double)from_ordered_bits(excl_bits);
-                double margin = kCertZ * __builtin_sqrt(var * (1.0 + 1.0 / m));
+                // z standard deviations of (an excluded entry's error minus the sample mean), widened by
+                // 1 + 4/m for the uncertainty of a standard deviation estimated from m samples
+                double margin = kCertZ * (1.0 + 4.0 / m) * __builtin_sqrt(var * (1.0 + 1.0 / m));
                 const double floor_ = 4.0 * 5.9604644775390625e-8 * (__builtin_fabs(kex) + __builtin_fabs(mean) + (double)dk);
                 margin = margin > floor_ ? margin : floor_;
                 ok = (kex - mean - margin > (double)dk) ? 1 : 0;   // false for NaN

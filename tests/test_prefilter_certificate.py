@@ -8,7 +8,8 @@ inputs that defeat it (low-dimensional dense data, clusters far from the origin,
     top-k, and the share of queries affected falls as R grows;
   * that the certificate as the kernels compute it (sample mean / standard deviation of
     coarse key minus exact distance over the re-scored candidates, margin of 8 standard
-    deviations, at least 8 distinct samples, bound = smallest coarse key left out) never
+    deviations widened by 1 + 4/m for m samples, at least 8 distinct samples, bound = smallest
+    coarse key left out) never
     confirms a query whose coarse candidates miss a true neighbour, while it confirms nearly
     every query of the class-clustered high-dimensional data the paper's caches hold.
 
@@ -59,7 +60,7 @@ def _certify(kappa, dist, k, kappa_excl):
         return False
     e = kappa.astype(np.float64) - dist.astype(np.float64)
     mean, sd = e.mean(), e.std(ddof=1)
-    margin = max(Z * sd * np.sqrt(1.0 + 1.0 / m), 4 * 2.0 ** -24 * (abs(kappa_excl) + abs(mean) + dk))
+    margin = max(Z * (1.0 + 4.0 / m) * sd * np.sqrt(1.0 + 1.0 / m), 4 * 2.0 ** -24 * (abs(kappa_excl) + abs(mean) + dk))
     return bool(kappa_excl - mean - margin > dk)
 
 
