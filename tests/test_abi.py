@@ -63,6 +63,17 @@ def test_host_side_checks_without_gpu():
         assert L.freeze_cache_build(h, 0, dummy, 0, 10, 10, dummy, 2, dummy, 16, None) == binding.FREEZE_EWORKSPACE
         assert L.freeze_cache_build(h, 0, None, 0, 10, 10, dummy, 2, dummy, 1 << 20, None) == binding.FREEZE_EINVAL
         assert L.freeze_compact_misses(None, None, 4, dummy, dummy, None) == binding.FREEZE_EINVAL
+        # the entry point with the built-in scratch checks its arguments the same way, before touching the GPU
+        sargs = (dummy, 4, 5, 3, 0, dummy, dummy, dummy, dummy, dummy, None)
+        assert L.freeze_lookup_static(h, 9, *sargs) == binding.FREEZE_ELAYER
+        assert L.freeze_lookup_static(h, 1, *sargs) == binding.FREEZE_ENOTBUILT
+        assert L.freeze_lookup_static(None, 0, *sargs) == binding.FREEZE_EINVAL
+        assert L.freeze_lookup_static(h, 0, dummy, 4, 5, 9, 0, dummy, dummy, dummy, dummy, dummy, None) == binding.FREEZE_EINVAL
+        assert L.freeze_lookup_stats_attach(None, None) == binding.FREEZE_EINVAL
+        assert L.freeze_lookup_stats_attach(h, ctypes.c_void_p(12)) == binding.FREEZE_EINVAL     # misaligned
+        assert L.freeze_lookup_stats_attach(h, None) == binding.FREEZE_OK
+        assert L.freeze_profile_enable(h, 3) == binding.FREEZE_EINVAL
+        assert L.freeze_profile_enable(h, 2) == binding.FREEZE_OK and L.freeze_profile_enable(h, 0) == binding.FREEZE_OK
     finally:
         assert L.freeze_destroy(h) == binding.FREEZE_OK
     assert L.freeze_destroy(None) == binding.FREEZE_EINVAL
