@@ -1214,8 +1214,9 @@ __global__ __launch_bounds__(256) void exact_scan_kernel(ScanArgs sa)
 }
 
 static int scan_max_splits(int k) { return kMaxMergeEntries / k < kScanMaxSplits ? kMaxMergeEntries / k : kScanMaxSplits; }
-// (a small-batch look-up flags at most 16 queries and pays for this launch out of 0.2 ms: a smaller grid)
-static int scan_grid(int num_cus, int64_t b) { return b <= kSkinnyRows ? (num_cus >= 4 ? num_cus / 2 : 2) : 2 * num_cus; }
+// (an empty launch costs the same 4 us whatever its grid: no smaller grid for small batches, whose
+// flagged queries then get all the workgroups)
+static int scan_grid(int num_cus, int64_t) { return 2 * num_cus; }
 
 size_t scan_scratch_entries(int64_t b, int k, int num_cus)
 {
