@@ -65,9 +65,10 @@ int freeze_create(freeze_ctx **out, int num_layers);
 int freeze_destroy(freeze_ctx *ctx);
 
 /* Bytes of device memory freeze_cache_build needs in `storage` for an n x d cache
- * (bf16 rows tiled and padded for the matrix cores, fp32 squared norms, labels, and a
- * row-major copy of the stored values for exact re-scoring: about 2x the bf16 size of the
- * cache, 3x when the entries are given in fp32).  0 on invalid arguments. */
+ * (bf16 rows tiled and padded for the matrix cores, fp32 squared norms, labels, a
+ * row-major copy of the stored values for exact re-scoring, and the mean vector with its column
+ * statistics: about 2x the bf16 size of the cache, 3x when the entries are given in fp32).
+ * 0 on invalid arguments. */
 size_t freeze_cache_storage_bytes(int64_t n, int64_t d, int entries_dtype);
 
 /*
@@ -85,6 +86,21 @@ size_t freeze_cache_storage_bytes(int64_t n, int64_t d, int entries_dtype);
 int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entries_dtype, int64_t n,
                        int64_t d, const int32_t *labels, int32_t num_classes, void *storage,
                        size_t storage_bytes, void *stream);
+
+/*
+ * Centring of the caches built from now on with freeze_cache_build (host-side setting of the
+ * context; the look-up results do not depend on it, only their speed on caches that sit far from
+ * the origin).  The bf16 copy of a cache that the matrix cores rank with, and the bf16 copy of the
+ * queries, may be taken relative to the cache's mean vector: distances are unchanged by a common
+ * shift, while the ranking key |c|^2 - 2 q.c loses the large common terms whose rounding otherwise
+ * hides the differences between neighbours (such queries are still answered exactly, through the
+ * slower paths described at freeze_lookup).  The stored values, which distances are measured
+ * to, are never altered.
+ *   mode 0: never;  1 (default): when the cache's mean dominates its spread, |mean|^2 > 4 x the
+ *   summed column variances, decided on the device at build time;  2: always.
+ * k-means caches and projections are never centred.
+ */
+int freeze_set_centring(freeze_ctx *ctx, int mode);
 
 /* Bytes of workspace freeze_lookup needs for a batch of b queries. 0 on invalid arguments. */
 size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b, int k, int rescore_r);

@@ -48,6 +48,8 @@ def lib():
     L.freeze_cache_storage_bytes.argtypes = [i64, i64, i32]
     L.freeze_cache_build.restype = i32
     L.freeze_cache_build.argtypes = [p, i32, p, i32, i64, i64, p, ctypes.c_int32, p, sz, p]
+    L.freeze_set_centring.restype = i32
+    L.freeze_set_centring.argtypes = [p, i32]
     L.freeze_lookup_workspace_bytes.restype = sz
     L.freeze_lookup_workspace_bytes.argtypes = [p, i32, i64, i32, i32]
     L.freeze_lookup.restype = i32
@@ -145,6 +147,11 @@ def freeze_cache_build(ctx, layer: int, entries: torch.Tensor, labels: torch.Ten
     assert labels.numel() == n
     _check(lib().freeze_cache_build(ctx, layer, _ptr(entries), dt, n, d, _ptr(labels), num_classes, _ptr(storage),
                                     storage.numel() * storage.element_size(), _stream(stream)), "freeze_cache_build")
+
+
+def freeze_set_centring(ctx, mode: int) -> None:
+    """0: caches built from now on are never centred, 1: when their mean dominates their spread (default), 2: always."""
+    _check(lib().freeze_set_centring(ctx, mode), "freeze_set_centring")
 
 
 def freeze_lookup_workspace_bytes(ctx, layer: int, b: int, k: int, rescore_r: int = 0) -> int:

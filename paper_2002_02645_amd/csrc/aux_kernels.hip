@@ -32,9 +32,88 @@ __device__ __forceinline__ float block_sum_256(float v, float *scratch4)
 // values for exact re-scoring (fp32 rows when the cache was given in fp32, else bf16 rows): the
 // re-scoring gathers whole rows, which the tiled layout would serve in half-used cache lines.
 // ---------------------------------------------------------------------------------------
+// Centring of the matrix-core copy.  Distances do not change when the same vector is subtracted
+// from entries and queries, but the coarse key |c|^2 - 2 q.c does: for a cache that sits far from
+// the origin both of its terms are huge next to the distance and their bf16 / fp32 rounding swamps
+// the differences between neighbours.  So the bf16 copy the matrix cores read (and the queries'
+// bf16 copy) may be taken relative to the cache's mean vector mu; the stored values, which the exact
+// re-scoring reads, stay as they are.  Whether to do so is decided on the device from the column
+// statistics: only when the mean dominates the spread (|mu|^2 > 4 * total variance); otherwise mu is
+// all zeros, the subtraction is exact and the copy is the plain rounding of the stored values (for
+// a cache stored in bf16 centring adds a rounding error the plain copy does not have).
+//
+// Column sums and sums of squares in fp64: block (x, y) takes 256 columns and a range of rows.
+__global__ __launch_bounds__(256) void col_stats_kernel(const void *entries, int dtype, int64_t n, int64_t d, int64_t d_pad,
+                                                        double *stats)
+{
+    const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t rows_per = (n + gridDim.y - 1) / gridDim.y;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per, r1 = r0 + rows_per < n ? r0 + rows_per : n;
+    if (col >= d || r0 >= r1) return;
+    double s1 = 0.0, s2 = 0.0;
+    int64_t r = r0;
+    for (; r + 8 <= r1; r += 8) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            v[e] = dtype == 0 ? reinterpret_cast<const float *>(entries)[(r + e) * d + col]
+                              : bf16_to_f32(reinterpret_cast<const uint16_t *>(entries)[(r + e) * d + col]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            s1 += (double)v[e];
+            s2 += (double)v[e] * (double)v[e];
+        }
+    }
+    for (; r < r1; ++r) {
+        const float v = dtype == 0 ? reinterpret_cast<const float *>(entries)[r * d + col]
+                                   : bf16_to_f32(reinterpret_cast<const uint16_t *>(entries)[r * d + col]);
+        s1 += (double)v;
+        s2 += (double)v * (double)v;
+    }
+    atomicAdd(&stats[col], s1);
+    atomicAdd(&stats[d_pad + col], s2);
+}
+
+// mu[i] = column mean (or 0 everywhere when the cache is not worth centring); one workgroup
+__global__ __launch_bounds__(1024) void col_mean_kernel(const double *stats, int64_t n, int64_t d, int64_t d_pad, int mode,
+                                                        float *mu)
+{
+    __shared__ double red_m[16], red_v[16];
+    __shared__ int centre_s;
+    const int tid = threadIdx.x;
+    double m2 = 0.0, var = 0.0;
+    for (int64_t i = tid; i < d; i += 1024) {
+        const double mean = stats[i] / (double)n;
+        const double v = stats[d_pad + i] / (double)n - mean * mean;
+        m2 += mean * mean;
+        var += v > 0.0 ? v : 0.0;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        m2 += __shfl_xor(m2, off, 64);
+        var += __shfl_xor(var, off, 64);
+    }
+    if ((tid & 63) == 0) {
+        red_m[tid >> 6] = m2;
+        red_v[tid >> 6] = var;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double a = 0.0, b = 0.0;
+        for (int w = 0; w < 16; ++w) {
+            a += red_m[w];
+            b += red_v[w];
+        }
+        centre_s = mode == 2 || (mode == 1 && a > 4.0 * b);
+    }
+    __syncthreads();
+    const bool centre = centre_s != 0;
+    for (int64_t i = tid; i < d_pad; i += 1024) mu[i] = (centre && i < d) ? (float)(stats[i] / (double)n) : 0.f;
+}
+
 __global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, int dtype, int64_t n, int64_t d,
                                                           int64_t d_pad, uint16_t *c_bf, float *norm, float *c_f32,
-                                                          uint16_t *c_rows)
+                                                          uint16_t *c_rows, const float *mu)
 {
     __shared__ float red[4];
     const int64_t row = blockIdx.x;
@@ -86,19 +165,32 @@ __global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, i
                 }
             }
         }
+        uint4 v;   // the stored values (bf16 input) for the row-major copy
+        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
+        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+        if (c_rows && row < n) reinterpret_cast<uint4 *>(c_rows + row * d_pad)[j] = v;
+        if (mu && row < n) {
+            // the matrix cores' copy relative to mu (all zeros unless the cache is centred: then exact)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int64_t i = j * 8 + e;
+                const float stored = dtype == 0 ? f[e] : bf16_to_f32(h[e]);
+                h[e] = i < d ? bf16_rne(stored - mu[i]) : (uint16_t)0;
+            }
+            v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+            v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+            v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
+            v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             if (c_f32 && row < n) c_f32[row * d_pad + j * 8 + e] = f[e];
             const float x = bf16_to_f32(h[e]);
             ss = __builtin_fmaf(x, x, ss);
         }
-        uint4 v;
-        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
-        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
         tile_base[tiled_chunk_offset(rit, j, kTileN)] = v;
-        if (c_rows && row < n) reinterpret_cast<uint4 *>(c_rows + row * d_pad)[j] = v;
     }
     const float tot = block_sum_256(ss, red);
     if (threadIdx.x == 0) norm[row] = (row < n) ? tot : __builtin_inff();
@@ -112,11 +204,26 @@ __global__ void copy_i32_kernel(const int32_t *src, int32_t *dst, int64_t n)
 
 hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t d, int64_t n_pad, int64_t d_pad,
                               uint16_t *c_bf, float *norm, float *c_f32, uint16_t *c_rows, const int32_t *labels_in,
-                              int32_t *labels_out, hipStream_t s)
+                              int32_t *labels_out, float *mu, double *stats, int centre_mode, hipStream_t s)
 {
+    hipError_t e;
+    if (mu) {
+        // column statistics -> mu (zeros unless the cache is to be centred)
+        if ((e = launch_fill_i32(reinterpret_cast<int32_t *>(stats), 0, 4 * d_pad, s)) != hipSuccess) return e;
+        const int64_t col_blocks = (d + 255) / 256;
+        int64_t row_chunks = 2048 / col_blocks;
+        if (row_chunks > (n + 63) / 64) row_chunks = (n + 63) / 64;
+        if (row_chunks < 1) row_chunks = 1;
+        if (row_chunks > 65535) row_chunks = 65535;
+        hipLaunchKernelGGL(col_stats_kernel, dim3((unsigned)col_blocks, (unsigned)row_chunks), dim3(256), 0, s, entries,
+                           dtype, n, d, d_pad, stats);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL(col_mean_kernel, dim3(1), dim3(1024), 0, s, stats, n, d, d_pad, centre_mode, mu);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(cache_build_kernel, dim3((unsigned)n_pad), dim3(256), 0, s, entries, dtype, n, d, d_pad, c_bf,
-                       norm, c_f32, c_rows);
-    hipError_t e = hipGetLastError();
+                       norm, c_f32, c_rows, mu);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(copy_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, labels_in, labels_out, n);
     return hipGetLastError();
@@ -133,7 +240,7 @@ hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, const int32_t *sel, const int32_t *count,
                                                          int b, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf,
-                                                         int32_t *flag_count, int32_t *tickets)
+                                                         int32_t *flag_count, int32_t *tickets, const float *mu)
 {
     const int nq = count ? *count : b;
     const int row0 = blockIdx.x * 2;   // bm is even: both rows lie in one tile
@@ -154,10 +261,22 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
     const int64_t per = ((pair_chunks + gridDim.y - 1) / gridDim.y + 255) / 256 * 256;   // chunks per block of the pair
     const int64_t jj_end = (blockIdx.y + 1) * per < pair_chunks ? (blockIdx.y + 1) * per : pair_chunks;
     // one 16-byte chunk of the bf16 copy from 8 fp32 values
+    // (relative to the cache's mean vector when the cache is centred; mu is zero past d and all zeros
+    // when it is not)
     auto convert_store = [&](int64_t j, const float (&x)[8]) {
         uint16_t h[8];
+        if (mu && src) {
+            const f32x4 m0 = *reinterpret_cast<const f32x4 *>(mu + j * 8);
+            const f32x4 m1 = *reinterpret_cast<const f32x4 *>(mu + j * 8 + 4);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = bf16_rne(x[e]);
+            for (int e = 0; e < 4; ++e) {
+                h[e] = bf16_rne(x[e] - m0[e]);
+                h[4 + e] = bf16_rne(x[4 + e] - m1[e]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = bf16_rne(x[e]);
+        }
         uint4 v;
         v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
         v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
@@ -208,7 +327,7 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float *queries, c
 
 hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
                              int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, int32_t *flag_count,
-                             int32_t *tickets, hipStream_t s)
+                             int32_t *tickets, const float *mu, hipStream_t s)
 {
     if (bm % 2 != 0 || b_pad % 2 != 0) return hipErrorInvalidValue;
     // about 2048 blocks in all, at least four rounds of 256 chunks each
@@ -217,7 +336,7 @@ hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int
     if (ysplit > rounds / 4) ysplit = rounds / 4;
     if (ysplit < 1) ysplit = 1;
     hipLaunchKernelGGL(query_prep_kernel, dim3((unsigned)pairs, (unsigned)ysplit), dim3(256), 0, s, queries, sel, count,
-                       (int)b, bm, d, d_pad, q_bf, flag_count, tickets);
+                       (int)b, bm, d, d_pad, q_bf, flag_count, tickets, mu);
     return hipGetLastError();
 }
 

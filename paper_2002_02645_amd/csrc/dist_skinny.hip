@@ -70,6 +70,7 @@ struct SkinnyArgs {
     int64_t d;
     const uint16_t *c_bf;
     const float *norm;
+    const float *mu;        // [d_pad] the cache's mean vector when its matrix-core copy is centred (zeros when not), or null
     uint64_t *bmin;         // [b, n_pad / 32] smallest (ordered key, index) of each block of 32 entries
     uint64_t *wgmin;        // [b, n_splits] smallest of the block minima each workgroup wrote
     int32_t *flag_count;    // cleared here for the finishing kernels: the count of flagged queries ...
@@ -144,6 +145,10 @@ __global__ __launch_bounds__(512) void dist_skinny_kernel(SkinnyArgs p)
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[e] = (row < p.b && i0 + e < p.d) ? src[i0 + e] : 0.f;
+            }
+            if (p.mu && row < p.b) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] -= p.mu[i0 + e];   // (zero past d)
             }
             uint4 v;
             v.x = (uint32_t)bf16_rne(x[0]) | ((uint32_t)bf16_rne(x[1]) << 16);
@@ -342,6 +347,7 @@ hipError_t launch_skinny_stream(const SkinnyLaunch &a, hipStream_t s)
     k.d = a.d;
     k.c_bf = a.c_bf;
     k.norm = a.norm;
+    k.mu = a.mu;
     k.bmin = a.bmin;
     k.wgmin = a.wgmin;
     k.flag_count = a.flag_count;

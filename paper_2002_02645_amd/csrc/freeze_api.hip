@@ -20,6 +20,7 @@ struct freeze_ctx {
     std::vector<hipEvent_t> events;
     int profiled_calls = 0;
     unsigned long long *stats = nullptr;   // device counters of the certificate's verdicts, or null
+    int centring = 1;   // caches built from now on: 0 never centred, 1 when the mean dominates the spread, 2 always
 };
 
 // Scratch of freeze_lookup_static: the look-up's workspace for callers that cannot allocate.
@@ -93,6 +94,7 @@ bool cache_layout(int64_t n, int64_t d, int dtype, CacheLayout *out)
     size_t bytes = align_up((size_t)out->n_pad * out->d_pad * 2) + align_up((size_t)out->n_pad * 4) +
                    align_up((size_t)n * 4);
     bytes += align_up((size_t)n * out->d_pad * (dtype == FREEZE_F32 ? 4 : 2));   // row-major copy for re-scoring
+    bytes += align_up((size_t)out->d_pad * 4) + align_up((size_t)out->d_pad * 16);    // centring vector and its column statistics
     out->bytes = bytes;
     return true;
 }
@@ -247,7 +249,7 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
         // only the flag counts start over (the exact scan leaves its tickets at zero)
         if (launch_fill_i32(flag_count, 0, 2, s) != hipSuccess) return FREEZE_EHIP;
     } else if (!sh.skinny && launch_query_prep(queries, sel, count, b, sh.plan.b_pad, sh.plan.bm, L.d, L.d_pad, q_bf,
-                                               flag_count, tickets, s) != hipSuccess) {
+                                               flag_count, tickets, L.mu, s) != hipSuccess) {
         return FREEZE_EHIP;
     }
 
@@ -262,6 +264,7 @@ int enqueue_lookup(freeze_ctx *ctx, const LayerCache &L, const LookupShape &sh, 
         sl.d = L.d;
         sl.c_bf = L.c_bf;
         sl.norm = L.norm;
+        sl.mu = L.mu;
         sl.bmin = ws.take<uint64_t>((size_t)kSkinnyRows * (L.n_pad / 32));
         sl.wgmin = ws.take<uint64_t>((size_t)kSkinnyRows * (L.n_pad / kTileN));
         sl.flag_count = flag_count;
@@ -596,8 +599,15 @@ size_t freeze_cache_storage_bytes(int64_t n, int64_t d, int entries_dtype)
     return cache_layout(n, d, entries_dtype, &cl) ? cl.bytes : 0;
 }
 
-int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entries_dtype, int64_t n, int64_t d,
-                       const int32_t *labels, int32_t num_classes, void *storage, size_t storage_bytes, void *stream)
+}  // extern "C"
+
+namespace {
+// allow_centre: false for what is not a cache of its own (the rows of a projection: a product is not
+// invariant under a shift) and for the k-means rounds (the prepared copy of the points is reused
+// across rounds, while the centres, and with them their mean, move)
+int cache_build_impl(freeze_ctx *ctx, int layer, const void *entries, int entries_dtype, int64_t n, int64_t d,
+                     const int32_t *labels, int32_t num_classes, void *storage, size_t storage_bytes, void *stream,
+                     bool allow_centre)
 {
     if (!ctx || !entries || !labels || !storage || num_classes < 1) return FREEZE_EINVAL;
     if (layer < 0 || layer >= (int)ctx->layers.size()) return FREEZE_ELAYER;
@@ -611,11 +621,14 @@ int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entr
     int32_t *lab = st.take<int32_t>((size_t)n);
     float *c_f32 = entries_dtype == FREEZE_F32 ? st.take<float>((size_t)n * cl.d_pad) : nullptr;
     uint16_t *c_rows = entries_dtype == FREEZE_BF16 ? st.take<uint16_t>((size_t)n * cl.d_pad) : nullptr;
+    float *mu = st.take<float>((size_t)cl.d_pad);
+    double *col_stats = st.take<double>(2 * (size_t)cl.d_pad);
+    const bool centre = allow_centre && ctx->centring != 0;
 
     LayerCache &L = ctx->layers[layer];
     L.built = false;
     if (launch_cache_build(entries, entries_dtype, n, d, cl.n_pad, cl.d_pad, c_bf, norm, c_f32, c_rows, labels, lab,
-                           static_cast<hipStream_t>(stream)) != hipSuccess)
+                           centre ? mu : nullptr, col_stats, ctx->centring, static_cast<hipStream_t>(stream)) != hipSuccess)
         return FREEZE_EHIP;
     L.n = n;
     L.d = d;
@@ -630,7 +643,25 @@ int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entr
     L.c_rows = c_rows;
     L.fraction = nullptr;
     L.bias = nullptr;
+    L.mu = centre ? mu : nullptr;
     L.built = true;
+    return FREEZE_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entries_dtype, int64_t n, int64_t d,
+                       const int32_t *labels, int32_t num_classes, void *storage, size_t storage_bytes, void *stream)
+{
+    return cache_build_impl(ctx, layer, entries, entries_dtype, n, d, labels, num_classes, storage, storage_bytes, stream,
+                            true);
+}
+
+int freeze_set_centring(freeze_ctx *ctx, int mode)
+{
+    if (!ctx || mode < 0 || mode > 2) return FREEZE_EINVAL;
+    ctx->centring = mode;
     return FREEZE_OK;
 }
 
@@ -830,7 +861,7 @@ int freeze_kmeans_build(freeze_ctx *ctx, int layer, const float *points, int64_t
     const HitRule rule{0, 1, 0.f, nullptr};
     for (int it = 0; it <= iters; ++it) {
         const float *cur = cen[it & 1];
-        int rc = freeze_cache_build(ctx, layer, cur, FREEZE_F32, kc, d, zero_labels, num_classes, storage, cl.bytes, stream);
+        int rc = cache_build_impl(ctx, layer, cur, FREEZE_F32, kc, d, zero_labels, num_classes, storage, cl.bytes, stream, false);
         if (rc != FREEZE_OK) return rc;
         const LayerCache &L = ctx->layers[layer];
         LookupShape sh;
@@ -891,7 +922,7 @@ int freeze_projection_build(freeze_ctx *ctx, int slot, const void *weights, int 
     // the rows of W go through the cache ingest (bf16, tiled); its labels are not used
     int32_t *dummy_labels = static_cast<int32_t *>(workspace);
     if (launch_fill_i32(dummy_labels, 0, m, s) != hipSuccess) return FREEZE_EHIP;
-    int rc = freeze_cache_build(ctx, slot, weights, weights_dtype, m, d, dummy_labels, 1, storage, cl.bytes, stream);
+    int rc = cache_build_impl(ctx, slot, weights, weights_dtype, m, d, dummy_labels, 1, storage, cl.bytes, stream, false);
     if (rc != FREEZE_OK) return rc;
     float *bias_pad = reinterpret_cast<float *>(static_cast<unsigned char *>(storage) + cl.bytes);
     if (launch_fill_i32(reinterpret_cast<int32_t *>(bias_pad), 0, cl.n_pad, s) != hipSuccess) return FREEZE_EHIP;
@@ -930,7 +961,7 @@ int freeze_project(freeze_ctx *ctx, int slot, const float *x, int64_t b, int rel
     uint16_t *x_bf = ws.take<uint16_t>((size_t)pl.b_pad * P->d_pad);
     float *tmp = ws.take<float>((size_t)b * P->n_pad);
     float *partial = pl.sk_wgs > 0 ? ws.take<float>(dist_partial_bytes(pl) / 4) : nullptr;
-    if (launch_query_prep(x, nullptr, nullptr, b, pl.b_pad, pl.bm, P->d, P->d_pad, x_bf, nullptr, nullptr, s) != hipSuccess)
+    if (launch_query_prep(x, nullptr, nullptr, b, pl.b_pad, pl.bm, P->d, P->d_pad, x_bf, nullptr, nullptr, nullptr, s) != hipSuccess)
         return FREEZE_EHIP;
     const bool direct = P->n == P->n_pad;   // the output rows are then exactly what the kernel writes
     DistArgs da{};

@@ -95,6 +95,8 @@ struct LayerCache {
     const float *fraction = nullptr;  // [n] the share of each cluster that carries its majority label (else null)
     // projection (a dense layer in front of the look-up): the entries are the rows of W and
     const float *bias = nullptr;      // [n_pad] its bias, zero padded (else null); not a cache: look-ups reject it
+    // the matrix-core copy c_bf (and norm) is taken relative to this vector, and so must the queries' bf16
+    const float *mu = nullptr;        // [d_pad] copy be: the cache's mean, or all zeros (decided on the device); null: none
 };
 
 // Number of splits of the cache tiles for `live_mt` live query tiles.  Units (query tile, split)
@@ -175,15 +177,18 @@ struct DistArgs {
     int d_pad;
 };
 
+// mu [d_pad] float and stats [2 d_pad] double: the centring vector and its scratch, or null (no centring);
+// centre_mode 1: centre when the cache's mean dominates its spread, 2: always
 hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t d, int64_t n_pad, int64_t d_pad,
                               uint16_t *c_bf, float *norm, float *c_f32, uint16_t *c_rows, const int32_t *labels_in,
-                              int32_t *labels_out, hipStream_t s);
+                              int32_t *labels_out, float *mu, double *stats, int centre_mode, hipStream_t s);
 
 // Also clears what the later kernels of the look-up count in: flag_count[0 .. 2) and tickets[0 .. b)
 // (each may be null).
+// mu: the cache's centring vector [d_pad] (subtracted before the rounding) or null.
 hipError_t launch_query_prep(const float *queries, const int32_t *sel, const int32_t *count, int64_t b,
                              int64_t b_pad, int bm, int64_t d, int64_t d_pad, uint16_t *q_bf, int32_t *flag_count,
-                             int32_t *tickets, hipStream_t s);
+                             int32_t *tickets, const float *mu, hipStream_t s);
 
 hipError_t launch_dist_topr(const DistPlan &plan, const DistArgs &a, hipStream_t s);
 
@@ -194,6 +199,7 @@ struct SkinnyLaunch {
     int64_t d;
     const uint16_t *c_bf;
     const float *norm;
+    const float *mu;        // the cache's centring vector or null
     uint64_t *bmin;         // [b, n_pad / 32] out: smallest (ordered key, index) of every block of 32 entries
     uint64_t *wgmin;        // [b, n_splits] out: smallest block minimum written by each workgroup
     int32_t *flag_count;    // cleared by the kernel (with tickets[0 .. 2 * kSkinnyRows)) for the kernels after it

@@ -46,7 +46,7 @@ def test_host_side_checks_without_gpu():
         n, d = 1000, 100
         n_pad, d_pad = 1024, 128
         up = lambda x: (x + 255) // 256 * 256
-        base = up(n_pad * d_pad * 2) + up(n_pad * 4) + up(n * 4)
+        base = up(n_pad * d_pad * 2) + up(n_pad * 4) + up(n * 4) + up(d_pad * 4) + up(d_pad * 16)   # ... mean vector, column statistics
         assert L.freeze_cache_storage_bytes(n, d, binding.FREEZE_BF16) == base + up(n * d_pad * 2)
         assert L.freeze_cache_storage_bytes(n, d, binding.FREEZE_F32) == base + up(n * d_pad * 4)
         assert L.freeze_cache_storage_bytes(0, d, binding.FREEZE_BF16) == 0
@@ -72,6 +72,8 @@ def test_host_side_checks_without_gpu():
         assert L.freeze_lookup_stats_attach(None, None) == binding.FREEZE_EINVAL
         assert L.freeze_lookup_stats_attach(h, ctypes.c_void_p(12)) == binding.FREEZE_EINVAL     # misaligned
         assert L.freeze_lookup_stats_attach(h, None) == binding.FREEZE_OK
+        assert L.freeze_set_centring(h, 3) == binding.FREEZE_EINVAL and L.freeze_set_centring(None, 1) == binding.FREEZE_EINVAL
+        assert L.freeze_set_centring(h, 0) == binding.FREEZE_OK and L.freeze_set_centring(h, 1) == binding.FREEZE_OK
         assert L.freeze_profile_enable(h, 3) == binding.FREEZE_EINVAL
         assert L.freeze_profile_enable(h, 2) == binding.FREEZE_OK and L.freeze_profile_enable(h, 0) == binding.FREEZE_OK
     finally:

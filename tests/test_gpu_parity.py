@@ -147,21 +147,36 @@ def test_clusters_far_from_the_origin(b, store_bf16, n, d, k):
     L = data.layers[0]
     ent = (L.entries.float() + 100.0).to(L.entries.dtype)
     q = data.queries[0] + 100.0
+    e_h, l_h, q_h = _host_entries(ent), L.labels.numpy(), q.numpy()
+    ref = parity.oracle_reference(q_h, e_h, l_h, 10, k, thr)
     fc = binding.FreezeCache(1)
     try:
         counters = _verdicts(fc)
+        # 1. without centring: the plain bf16 copy cannot rank these entries, the slower paths must
+        binding.freeze_set_centring(fc.ctx, 0)
         fc.build_layer(0, ent.cuda(), L.labels.cuda(), 10)
         out = fc.lookup(0, q.cuda(), k, thr)
         torch.cuda.synchronize()
         got = {key: v.cpu().numpy() for key, v in out.items()}
         c = counters.cpu().numpy()
+        parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, k, thr, rel=TIGHT, dist_rel=TIGHT)
+        assert c.sum() == b
+        assert c[1] + c[2] > 0, "this input is meant to defeat the coarse ranking"
+        # 2. the default: the library sees at build time that the mean dominates the spread and ranks
+        #    relative to it; the same exact result, now without the slower paths (k = R leaves no spare)
+        counters.zero_()
+        binding.freeze_set_centring(fc.ctx, 1)
+        fc.build_layer(0, ent.cuda(), L.labels.cuda(), 10)
+        out = fc.lookup(0, q.cuda(), k, thr)
+        torch.cuda.synchronize()
+        got = {key: v.cpu().numpy() for key, v in out.items()}
+        c2 = counters.cpu().numpy()
+        parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, k, thr, rel=TIGHT, dist_rel=TIGHT)
+        assert c2.sum() == b
+        if k < 64:
+            assert c2[0] >= 0.98 * b and c2[2] <= c[2], (c, c2)
     finally:
         fc.close()
-    e_h, l_h, q_h = _host_entries(ent), L.labels.numpy(), q.numpy()
-    ref = parity.oracle_reference(q_h, e_h, l_h, 10, k, thr)
-    parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, k, thr, rel=TIGHT, dist_rel=TIGHT)
-    assert c.sum() == b
-    assert c[1] + c[2] > 0, "this input is meant to defeat the coarse ranking"
 
 
 def test_cascade_on_clusters_far_from_the_origin():
@@ -175,6 +190,7 @@ def test_cascade_on_clusters_far_from_the_origin():
     fc = binding.FreezeCache(nl)
     try:
         counters = _verdicts(fc)
+        binding.freeze_set_centring(fc.ctx, 0)      # keep the plain copy: this test is about the slower paths
         for l, L in enumerate(data.layers):
             fc.build_layer(l, ents[l].cuda(), L.labels.cuda(), L.spec.num_classes)
         out = fc.lookup_cascade(list(range(nl)), [q.cuda() for q in qs], wl.k, list(wl.vote_thresholds), wl.rescore_r)
@@ -189,6 +205,32 @@ def test_cascade_on_clusters_far_from_the_origin():
     assert np.array_equal(got["exit_layer"], exp_x) and np.array_equal(got["label"], exp_l)
     assert got["hits_per_layer"].tolist() == exp_h.tolist()
     assert len(set(exp_x.tolist())) >= 3 and c[1] + c[2] > 0
+
+
+@pytest.mark.parametrize("n,d,b,k,dtype", [
+    (3000, 256, 300, 10, torch.bfloat16),    # fused kernel
+    (20000, 512, 8, 20, torch.bfloat16),     # small-batch kernel (the queries are converted inside the streaming kernel)
+    (2500, 4160, 100, 10, torch.float32),    # keys-out kernel, fp32 cache, ragged depth
+])
+def test_forced_centring_keeps_results_exact(n, d, b, k, dtype):
+    # centring changes which copy the matrix cores rank with, never the answer
+    wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
+    spec = type(wl.layers[0])(n, d, 10, 0.8, relu=True, store_bf16=(dtype == torch.bfloat16))
+    thr = max(1, k - 2)
+    data = synth.make_workload(type(wl)(wl.name, (spec,), b, k, (thr,), 0, 5150 + n))
+    L = data.layers[0]
+    e_h, l_h, q_h = _host_entries(L.entries), L.labels.numpy(), data.queries[0].numpy()
+    ref = parity.oracle_reference(q_h, e_h, l_h, 10, k, thr)
+    fc = binding.FreezeCache(1)
+    try:
+        binding.freeze_set_centring(fc.ctx, 2)
+        fc.build_layer(0, L.entries.cuda(), L.labels.cuda(), 10)
+        out = fc.lookup(0, data.queries[0].cuda(), k, thr)
+        torch.cuda.synchronize()
+        got = {key: v.cpu().numpy() for key, v in out.items()}
+    finally:
+        fc.close()
+    parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, k, thr, rel=TIGHT, dist_rel=TIGHT)
 
 
 def test_certificate_verdicts_on_clustered_data():

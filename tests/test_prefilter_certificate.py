@@ -134,9 +134,10 @@ def _misses_with_centring(q, c, k, r, centre):
 
 
 def test_centring_trial_helps_offset_data_only():
-    """The trial behind the decision not to centre: subtracting the cache's mean before rounding removes
-    the misses on clusters far from the origin, and gains nothing on post-ReLU class-clustered
-    activations stored in bf16 (there the shifted copy has a rounding error the stored one does not)."""
+    """The trial behind the library's rule to centre a cache only when its mean dominates its spread:
+    subtracting the cache's mean before rounding removes the misses on clusters far from the origin,
+    and gains nothing on post-ReLU class-clustered activations stored in bf16 (there the shifted
+    copy has a rounding error the stored one does not)."""
     rng = np.random.default_rng(21)
     q, c = _clustered(rng, 4000, 64, 150, 1.0, False, 100.0, True)
     assert _misses_with_centring(q, c, 10, 16, False) > 0
