@@ -173,11 +173,12 @@ __global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, i
         if (c_rows && row < n) reinterpret_cast<uint4 *>(c_rows + row * d_pad)[j] = v;
         if (mu && row < n) {
             // the matrix cores' copy relative to mu (all zeros unless the cache is centred: then exact)
+            const f32x4 m0 = *reinterpret_cast<const f32x4 *>(mu + j * 8), m1 = *reinterpret_cast<const f32x4 *>(mu + j * 8 + 4);
+            const float mv[8] = {m0[0], m0[1], m0[2], m0[3], m1[0], m1[1], m1[2], m1[3]};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int64_t i = j * 8 + e;
                 const float stored = dtype == 0 ? f[e] : bf16_to_f32(h[e]);
-                h[e] = i < d ? bf16_rne(stored - mu[i]) : (uint16_t)0;
+                h[e] = j * 8 + e < d ? bf16_rne(stored - mv[e]) : (uint16_t)0;
             }
             v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
             v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
