@@ -174,7 +174,7 @@ def test_clusters_far_from_the_origin(b, store_bf16, n, d, k):
         parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, k, thr, rel=TIGHT, dist_rel=TIGHT)
         assert c2.sum() == b
         if k < 64:
-            assert c2[0] >= 0.98 * b and c2[2] <= c[2], (c, c2)
+            assert c2[0] >= 0.98 * b - 1 and c2[2] <= c[2], (c, c2)
     finally:
         fc.close()
 
