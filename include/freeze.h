@@ -97,7 +97,8 @@ int freeze_cache_build(freeze_ctx *ctx, int layer, const void *entries, int entr
  * slower paths described at freeze_lookup).  The stored values, which distances are measured
  * to, are never altered.
  *   mode 0: never;  1 (default): when the cache's mean dominates its spread, |mean|^2 > 4 x the
- *   summed column variances, decided on the device at build time;  2: always.
+ *   summed column variances, decided on the device at build time (mean and variances are taken
+ *   over a sample of at most 8,192 evenly spaced entries);  2: always.
  * k-means caches and projections are never centred.
  */
 int freeze_set_centring(freeze_ctx *ctx, int mode);

@@ -42,36 +42,77 @@ __device__ __forceinline__ float block_sum_256(float v, float *scratch4)
 // all zeros, the subtraction is exact and the copy is the plain rounding of the stored values (for
 // a cache stored in bf16 centring adds a rounding error the plain copy does not have).
 //
-// Column sums and sums of squares in fp64: block (x, y) takes 256 columns and a range of rows.
+// The statistics come from a sample of at most kStatRows rows, evenly spaced over the cache (all
+// rows of a smaller cache): mu may be any vector, the results never depend on it, and the
+// decision needs no more precision than that.
+//
+// Column sums and sums of squares of the sampled rows in fp64: block (x, y) takes 512 columns (eight
+// per lane, so that a wave reads 1 KiB, or 2 KiB of fp32, of a row at a time) and a range of the
+// sample; its four waves take every fourth row of that range.
+constexpr int kStatRows = 8192;
 __global__ __launch_bounds__(256) void col_stats_kernel(const void *entries, int dtype, int64_t n, int64_t d, int64_t d_pad,
-                                                        double *stats)
+                                                        int64_t ns, double *stats)
 {
-    const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t rows_per = (n + gridDim.y - 1) / gridDim.y;
-    const int64_t r0 = (int64_t)blockIdx.y * rows_per, r1 = r0 + rows_per < n ? r0 + rows_per : n;
-    if (col >= d || r0 >= r1) return;
-    double s1 = 0.0, s2 = 0.0;
-    int64_t r = r0;
-    for (; r + 8 <= r1; r += 8) {
-        float v[8];
+    __shared__ double comb[3][64][16];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t col = ((int64_t)blockIdx.x * 64 + lane) * 8;
+    const int64_t per = (ns + gridDim.y - 1) / gridDim.y;
+    const int64_t i0 = (int64_t)blockIdx.y * per, i1 = i0 + per < ns ? i0 + per : ns;
+    const bool vec = (reinterpret_cast<uintptr_t>(entries) % 16) == 0 && (dtype == 0 ? d % 4 == 0 : d % 8 == 0) && col + 8 <= d;
+    double s1[8], s2[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            v[e] = dtype == 0 ? reinterpret_cast<const float *>(entries)[(r + e) * d + col]
-                              : bf16_to_f32(reinterpret_cast<const uint16_t *>(entries)[(r + e) * d + col]);
+    for (int e = 0; e < 8; ++e) s1[e] = s2[e] = 0.0;
+    if (col < d) {
+        for (int64_t i = i0 + w; i < i1; i += 4) {
+            const int64_t r = i * n / ns;   // sample i of ns (distinct rows: ns <= n)
+            float v[8];
+            if (vec && dtype == 0) {
+                const float *src = reinterpret_cast<const float *>(entries) + r * d + col;
+                const f32x4 v0 = *reinterpret_cast<const f32x4 *>(src), v1 = *reinterpret_cast<const f32x4 *>(src + 4);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            s1 += (double)v[e];
-            s2 += (double)v[e] * (double)v[e];
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = v0[e];
+                    v[4 + e] = v1[e];
+                }
+            } else if (vec) {
+                const uint4 u = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(entries) + r * d + col);
+                const uint32_t wv[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[2 * e] = __uint_as_float(wv[e] << 16);
+                    v[2 * e + 1] = __uint_as_float(wv[e] & 0xffff0000u);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    v[e] = col + e >= d ? 0.f
+                                        : (dtype == 0 ? reinterpret_cast<const float *>(entries)[r * d + col + e]
+                                                      : bf16_to_f32(reinterpret_cast<const uint16_t *>(entries)[r * d + col + e]));
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                s1[e] += (double)v[e];
+                s2[e] += (double)v[e] * (double)v[e];
+            }
         }
     }
-    for (; r < r1; ++r) {
-        const float v = dtype == 0 ? reinterpret_cast<const float *>(entries)[r * d + col]
-                                   : bf16_to_f32(reinterpret_cast<const uint16_t *>(entries)[r * d + col]);
-        s1 += (double)v;
-        s2 += (double)v * (double)v;
+    if (w > 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            comb[w - 1][lane][e] = s1[e];
+            comb[w - 1][lane][8 + e] = s2[e];
+        }
     }
-    atomicAdd(&stats[col], s1);
-    atomicAdd(&stats[d_pad + col], s2);
+    __syncthreads();
+    if (w == 0 && col < d) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (col + e < d) {
+                atomicAdd(&stats[col + e], s1[e] + (comb[0][lane][e] + comb[1][lane][e] + comb[2][lane][e]));
+                atomicAdd(&stats[d_pad + col + e], s2[e] + (comb[0][lane][8 + e] + comb[1][lane][8 + e] + comb[2][lane][8 + e]));
+            }
+        }
+    }
 }
 
 // mu[i] = column mean (or 0 everywhere when the cache is not worth centring); one workgroup
@@ -111,90 +152,149 @@ __global__ __launch_bounds__(1024) void col_mean_kernel(const double *stats, int
     for (int64_t i = tid; i < d_pad; i += 1024) mu[i] = (centre && i < d) ? (float)(stats[i] / (double)n) : 0.f;
 }
 
+// RB rows per workgroup (16; 4 for caches of few rows, which would otherwise leave most CUs without work)
+template <int RB>
 __global__ __launch_bounds__(256) void cache_build_kernel(const void *entries, int dtype, int64_t n, int64_t d,
                                                           int64_t d_pad, uint16_t *c_bf, float *norm, float *c_f32,
                                                           uint16_t *c_rows, const float *mu)
 {
-    __shared__ float red[4];
-    const int64_t row = blockIdx.x;
-    const int64_t tile = row / kTileN;
-    const int rit = (int)(row % kTileN);
+    // the matrix cores' copy of the block's rows, 64 chunks (512 elements) of every row at a time, on its
+    // way from row order to the tiled order (rows padded by one chunk against bank conflicts)
+    static_assert(RB == 4 || RB == 16, "rows per workgroup");
+    __shared__ uint4 stage[RB][65];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * RB;
+    const int64_t tile = row0 / kTileN;
+    const int rit0 = (int)(row0 % kTileN);
     uint4 *tile_base = reinterpret_cast<uint4 *>(c_bf + tile * kTileN * d_pad);
-    float ss = 0.f;
+    const int64_t chunks = d_pad / 8;
     // rows start 16-byte aligned when the batch does and d is a multiple of 8 (bf16) or 4 (fp32):
     // whole chunks are then fetched with 16-byte loads
-    const bool vec = row < n && (reinterpret_cast<uintptr_t>(entries) % 16) == 0 && (dtype == 0 ? d % 4 == 0 : d % 8 == 0);
-    for (int64_t j = threadIdx.x; j < d_pad / 8; j += 256) {   // one 16-byte chunk (8 elements) per step
-        uint16_t h[8];
-        float f[8];
-        if (vec && j * 8 + 8 <= d) {
-            if (dtype == 0) {
-                const float *src = reinterpret_cast<const float *>(entries) + row * d + j * 8;
-                const f32x4 v0 = *reinterpret_cast<const f32x4 *>(src), v1 = *reinterpret_cast<const f32x4 *>(src + 4);
+    const bool vec = (reinterpret_cast<uintptr_t>(entries) % 16) == 0 && (dtype == 0 ? d % 4 == 0 : d % 8 == 0);
+    constexpr int RPW = RB / 4;   // rows per wave
+    float ss[RPW];
+#pragma unroll
+    for (int q = 0; q < RPW; ++q) ss[q] = 0.f;
+    for (int64_t c0 = 0; c0 < chunks; c0 += 64) {
+        const int64_t j = c0 + lane;   // this lane's chunk (elements 8 j .. 8 j + 7) of each of the wave's rows
+        if (j < chunks) {
+            float mv[8];
+            if (mu) {
+                const f32x4 m0 = *reinterpret_cast<const f32x4 *>(mu + j * 8), m1 = *reinterpret_cast<const f32x4 *>(mu + j * 8 + 4);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    f[e] = v0[e];
-                    f[4 + e] = v1[e];
+                    mv[e] = m0[e];
+                    mv[4 + e] = m1[e];
                 }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) h[e] = bf16_rne(f[e]);
-            } else {
-                const uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(entries) + row * d + j * 8);
-                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    h[2 * e] = (uint16_t)(wv[e] & 0xffffu);
-                    h[2 * e + 1] = (uint16_t)(wv[e] >> 16);
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) f[e] = 0.f;   // (fp32 rows are kept only for fp32 input)
             }
-        } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int64_t i = j * 8 + e;
-                f[e] = 0.f;
-                h[e] = 0;
-                if (row < n && i < d) {
+            for (int q = 0; q < RPW; ++q) {
+                const int rl = w * RPW + q;
+                const int64_t row = row0 + rl;
+                uint16_t h[8];
+                float f[8];
+                if (row >= n) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        h[e] = 0;
+                        f[e] = 0.f;
+                    }
+                } else if (vec && j * 8 + 8 <= d) {
                     if (dtype == 0) {
-                        f[e] = reinterpret_cast<const float *>(entries)[row * d + i];
-                        h[e] = bf16_rne(f[e]);
+                        const float *src = reinterpret_cast<const float *>(entries) + row * d + j * 8;
+                        const f32x4 v0 = *reinterpret_cast<const f32x4 *>(src), v1 = *reinterpret_cast<const f32x4 *>(src + 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            f[e] = v0[e];
+                            f[4 + e] = v1[e];
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) h[e] = bf16_rne(f[e]);
                     } else {
-                        h[e] = reinterpret_cast<const uint16_t *>(entries)[row * d + i];
+                        const uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(entries) + row * d + j * 8);
+                        const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            h[2 * e] = (uint16_t)(wv[e] & 0xffffu);
+                            h[2 * e + 1] = (uint16_t)(wv[e] >> 16);
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) f[e] = 0.f;   // (fp32 rows are kept only for fp32 input)
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int64_t i = j * 8 + e;
+                        f[e] = 0.f;
+                        h[e] = 0;
+                        if (i < d) {
+                            if (dtype == 0) {
+                                f[e] = reinterpret_cast<const float *>(entries)[row * d + i];
+                                h[e] = bf16_rne(f[e]);
+                            } else {
+                                h[e] = reinterpret_cast<const uint16_t *>(entries)[row * d + i];
+                            }
+                        }
                     }
                 }
+                uint4 v;   // the stored values (bf16 input) for the row-major copy
+                v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
+                v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+                if (row < n) {
+                    if (c_rows) reinterpret_cast<uint4 *>(c_rows + row * d_pad)[j] = v;
+                    if (c_f32) {
+                        f32x4 o0, o1;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            o0[e] = f[e];
+                            o1[e] = f[4 + e];
+                        }
+                        *reinterpret_cast<f32x4 *>(c_f32 + row * d_pad + j * 8) = o0;
+                        *reinterpret_cast<f32x4 *>(c_f32 + row * d_pad + j * 8 + 4) = o1;
+                    }
+                    if (mu) {
+                        // the matrix cores' copy relative to mu (all zeros unless the cache is centred: then exact)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float stored = dtype == 0 ? f[e] : bf16_to_f32(h[e]);
+                            h[e] = j * 8 + e < d ? bf16_rne(stored - mv[e]) : (uint16_t)0;
+                        }
+                        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+                        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+                        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
+                        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = bf16_to_f32(h[e]);
+                    ss[q] = __builtin_fmaf(x, x, ss[q]);
+                }
+                stage[rl][lane] = v;
             }
         }
-        uint4 v;   // the stored values (bf16 input) for the row-major copy
-        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
-        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
-        if (c_rows && row < n) reinterpret_cast<uint4 *>(c_rows + row * d_pad)[j] = v;
-        if (mu && row < n) {
-            // the matrix cores' copy relative to mu (all zeros unless the cache is centred: then exact)
-            const f32x4 m0 = *reinterpret_cast<const f32x4 *>(mu + j * 8), m1 = *reinterpret_cast<const f32x4 *>(mu + j * 8 + 4);
-            const float mv[8] = {m0[0], m0[1], m0[2], m0[3], m1[0], m1[1], m1[2], m1[3]};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float stored = dtype == 0 ? f[e] : bf16_to_f32(h[e]);
-                h[e] = j * 8 + e < d ? bf16_rne(stored - mv[e]) : (uint16_t)0;
-            }
-            v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-            v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-            v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
-            v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+        __syncthreads();
+        // out in tiled order: for one k-block (4 chunks) the RB rows of the block are RB * 64 bytes in a
+        // row; a wave writes 64 / (4 RB) k-blocks at a time
+        const int64_t kb0 = c0 / 4;
+        constexpr int KPW = 64 / (4 * RB);
+        for (int qb = w * KPW + lane / (4 * RB); qb < 16 && (kb0 + qb) * 4 < chunks; qb += 4 * KPW) {
+            const int rl = (lane >> 2) % RB, c = lane & 3;
+            tile_base[tiled_chunk_offset(rit0 + rl, (kb0 + qb) * 4 + c, kTileN)] = stage[rl][qb * 4 + c];
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if (c_f32 && row < n) c_f32[row * d_pad + j * 8 + e] = f[e];
-            const float x = bf16_to_f32(h[e]);
-            ss = __builtin_fmaf(x, x, ss);
-        }
-        tile_base[tiled_chunk_offset(rit, j, kTileN)] = v;
+        __syncthreads();
     }
-    const float tot = block_sum_256(ss, red);
-    if (threadIdx.x == 0) norm[row] = (row < n) ? tot : __builtin_inff();
+    // |c|^2 of the bf16 row: the lanes' partial sums in a fixed order
+#pragma unroll
+    for (int q = 0; q < RPW; ++q) {
+        float v = ss[q];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+        const int64_t row = row0 + w * RPW + q;
+        if (lane == 0) norm[row] = (row < n) ? v : __builtin_inff();
+    }
 }
 
 __global__ void copy_i32_kernel(const int32_t *src, int32_t *dst, int64_t n)
@@ -211,19 +311,25 @@ hipError_t launch_cache_build(const void *entries, int dtype, int64_t n, int64_t
     if (mu) {
         // column statistics -> mu (zeros unless the cache is to be centred)
         if ((e = launch_fill_i32(reinterpret_cast<int32_t *>(stats), 0, 4 * d_pad, s)) != hipSuccess) return e;
-        const int64_t col_blocks = (d + 255) / 256;
+        const int64_t ns = n < kStatRows ? n : kStatRows;   // sampled rows
+        const int64_t col_blocks = (d + 511) / 512;
         int64_t row_chunks = 2048 / col_blocks;
-        if (row_chunks > (n + 63) / 64) row_chunks = (n + 63) / 64;
+        if (row_chunks > (ns + 31) / 32) row_chunks = (ns + 31) / 32;
         if (row_chunks < 1) row_chunks = 1;
         if (row_chunks > 65535) row_chunks = 65535;
         hipLaunchKernelGGL(col_stats_kernel, dim3((unsigned)col_blocks, (unsigned)row_chunks), dim3(256), 0, s, entries,
-                           dtype, n, d, d_pad, stats);
+                           dtype, n, d, d_pad, ns, stats);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL(col_mean_kernel, dim3(1), dim3(1024), 0, s, stats, n, d, d_pad, centre_mode, mu);
+        hipLaunchKernelGGL(col_mean_kernel, dim3(1), dim3(1024), 0, s, stats, ns, d, d_pad, centre_mode, mu);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(cache_build_kernel, dim3((unsigned)n_pad), dim3(256), 0, s, entries, dtype, n, d, d_pad, c_bf,
-                       norm, c_f32, c_rows, mu);
+    static_assert(kTileN % 16 == 0, "a workgroup's rows lie in one tile");
+    if (n_pad / 16 >= 512)
+        hipLaunchKernelGGL(cache_build_kernel<16>, dim3((unsigned)(n_pad / 16)), dim3(256), 0, s, entries, dtype, n, d, d_pad,
+                           c_bf, norm, c_f32, c_rows, mu);
+    else
+        hipLaunchKernelGGL(cache_build_kernel<4>, dim3((unsigned)(n_pad / 4)), dim3(256), 0, s, entries, dtype, n, d, d_pad,
+                           c_bf, norm, c_f32, c_rows, mu);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(copy_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, labels_in, labels_out, n);
