@@ -955,7 +955,13 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKer
         }
         const float *qrow = a.queries + (int64_t)(a.sel ? a.sel[q] : q) * a.d;
         // candidates of this round: the best by the coarse key (real entries sort in front of the markers)
-        const int m = WIDER ? (real_s < kTier1 ? real_s : kTier1) : r;
+        int m = WIDER ? (real_s < kTier1 ? real_s : kTier1) : r;
+        // Long activations, a width of 16 (or 32) that leaves room: the last quarter of the candidates
+        // is re-scored only when the certificate over the first twelve (24), which then counts the
+        // others among the excluded entries, does not confirm the result; most queries are spared a
+        // quarter of the rows (C2: 92 % of the queries, 0.42 -> 0.36 ms for the batch).
+        const bool two_steps = !WIDER && (r == 16 || r == 32) && a.k <= r / 2 + r / 8 && a.d >= 4096 && a.d % 8 == 0;
+        const int m_first = two_steps ? r - r / 4 : m;
 
         for (int c = tid; c < m; c += NT) {
             // With finite inputs every one of the first r entries is a real cache row.  Non-finite
@@ -973,9 +979,9 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKer
                 for (int c0 = 0; c0 < m; c0 += 32)
                     rescore_block_all<NT, 32>(a, qrow, idx_s + c0, dist_s + c0, red, m - c0 < 32 ? m - c0 : 32, tid);
             } else if (m <= 16) {
-                rescore_block_all<NT, 16>(a, qrow, idx_s, dist_s, red, m, tid);
+                rescore_block_all<NT, 16>(a, qrow, idx_s, dist_s, red, m_first, tid);
             } else if (m <= 32) {
-                rescore_block_all<NT, 32>(a, qrow, idx_s, dist_s, red, m, tid);
+                rescore_block_all<NT, 32>(a, qrow, idx_s, dist_s, red, m_first, tid);
             } else {
                 // (two passes of 32: 64 accumulators per thread spill, and the pass is 8 % slower for it)
                 rescore_block_all<NT, 32>(a, qrow, idx_s, dist_s, red, 32, tid);
@@ -992,19 +998,33 @@ __global__ __launch_bounds__(NT, NT == 256 ? 4 : 1) void finish_kernel(FinishKer
         __syncthreads();
 
         // 3. final order (dist, index) and the first k
-        rank_and_emit(a, q, m, tid, NT, dist_s, idx_s, lab_s, dsel_s, &nearest_s, &distinct_s);
-        __syncthreads();
-
-        // the certificate: is any entry that was not re-scored possibly nearer than the k-th?
         const int real = real_s;   // real entries gathered
         const int wider = real < kTier1 ? real : kTier1;
+        // the certificate: is any entry that was not re-scored possibly nearer than the k-th?
         // (a candidate list of the keys-out selection holds every entry up to its largest pair)
-        uint32_t excl = a.part_count ? (real >= a.n || real < 1 ? 0xffffffffu : (uint32_t)(ent[real - 1] >> 32)) : excl_s;
-        if (real > m) {
-            const uint32_t nxt = (uint32_t)(ent[m] >> 32);
-            excl = nxt < excl ? nxt : excl;
+        const uint32_t excl0 = a.part_count ? (real >= a.n || real < 1 ? 0xffffffffu : (uint32_t)(ent[real - 1] >> 32)) : excl_s;
+        bool ok = false;
+        if (two_steps) {
+            rank_and_emit(a, q, m_first, tid, NT, dist_s, idx_s, lab_s, dsel_s, &nearest_s, &distinct_s);
+            __syncthreads();
+            const uint32_t nxt = (uint32_t)(ent[m_first] >> 32);   // (real >= r > m_first with finite inputs; else the marker)
+            ok = certificate(ent, dist_s, m_first, dsel_s[a.k - 1], nxt < excl0 ? nxt : excl0, distinct_s, tid, &verdict_s);
+            if (!ok) {   // uniform
+                rescore_block_all<NT, 16>(a, qrow, idx_s + m_first, dist_s + m_first, red, m - m_first, tid);
+                if (tid == 0) distinct_s = 0;
+                __syncthreads();
+            }
         }
-        const bool ok = certificate(ent, dist_s, m, dsel_s[a.k - 1], excl, distinct_s, tid, &verdict_s);
+        if (!ok) {
+            rank_and_emit(a, q, m, tid, NT, dist_s, idx_s, lab_s, dsel_s, &nearest_s, &distinct_s);
+            __syncthreads();
+            uint32_t excl = excl0;
+            if (real > m) {
+                const uint32_t nxt = (uint32_t)(ent[m] >> 32);
+                excl = nxt < excl ? nxt : excl;
+            }
+            ok = certificate(ent, dist_s, m, dsel_s[a.k - 1], excl, distinct_s, tid, &verdict_s);
+        }
         if (tid == 0) {
             // unconfirmed: the wider round, or the exact scan, redoes this query (the outputs written
             // here stand until then)

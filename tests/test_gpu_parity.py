@@ -233,6 +233,39 @@ def test_forced_centring_keeps_results_exact(n, d, b, k, dtype):
     parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, k, thr, rel=TIGHT, dist_rel=TIGHT)
 
 
+@pytest.mark.parametrize("n,d,b,k,offset,dtype", [
+    (3000, 4096, 300, 10, 0.0, torch.bfloat16),   # width 16: twelve candidates first, four more when unconfirmed
+    (3000, 4096, 300, 10, 3.0, torch.float32),    # ... fp32 cache, a mean the automatic rule leaves alone
+    (2500, 4104, 280, 20, 1.0, torch.bfloat16),   # width 32: 24 first, then 8; ragged depth
+    (3000, 4096, 60, 10, 2.0, torch.bfloat16),    # one query tile: the keys-out selection in front of the same finish
+])
+def test_two_step_rescoring_on_dense_data(n, d, b, k, offset, dtype):
+    """Long activations are re-scored in two steps (three quarters of the width, the rest only when
+    the certificate over those does not confirm).  One dense Gaussian cloud: the distances of the
+    k-th and the following neighbours are within the bf16 keys' noise of each other for some queries,
+    so both outcomes occur: most queries are confirmed after the first step, and a few (2 to 33 of
+    them in these cases, measured with the width set to the first step's alone) need the second."""
+    g = torch.Generator().manual_seed(4242 + n + d + b)
+    ent = (torch.randn(n, d, generator=g) + offset).to(dtype)
+    lab = torch.randint(0, 10, (n,), generator=g, dtype=torch.int32)
+    q = torch.randn(b, d, generator=g) * 0.7 + offset
+    thr = max(1, k - 3)
+    e_h, l_h, q_h = _host_entries(ent), lab.numpy(), q.numpy()
+    ref = parity.oracle_reference(q_h, e_h, l_h, 10, k, thr)
+    fc = binding.FreezeCache(1)
+    try:
+        counters = _verdicts(fc)
+        fc.build_layer(0, ent.cuda(), lab.cuda(), 10)
+        out = fc.lookup(0, q.cuda(), k, thr)
+        torch.cuda.synchronize()
+        got = {key: v.cpu().numpy() for key, v in out.items()}
+        c = counters.cpu().numpy()
+    finally:
+        fc.close()
+    parity.assert_lookup_matches(got, ref, q_h, e_h, l_h, 10, k, thr, rel=TIGHT, dist_rel=TIGHT)
+    assert c.sum() == b, c
+
+
 def test_certificate_verdicts_on_clustered_data():
     # the paper's kind of input: nearly every query is confirmed after the first re-scoring
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=20000, d_div=4, batch=2000)
