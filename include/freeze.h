@@ -123,7 +123,10 @@ size_t freeze_lookup_workspace_bytes(const freeze_ctx *ctx, int layer, int64_t b
  *                  between coarse keys and exact distances of the candidates themselves, with
  *                  a margin of 8 standard deviations); a query that fails the check is
  *                  re-scored over a wider candidate set (up to 256), and if that fails too it
- *                  is scanned against every entry in fp32 inside the same call.  A width
+ *                  is scanned against every entry in fp32 inside the same call.  (With a
+ *                  width of 16 or 32 and activations of 4,096 values or more, the last quarter
+ *                  of the candidates is itself fetched only when the same check over the
+ *                  first three quarters does not already confirm the result.)  A width
  *                  close to k (or data whose bf16 keys cannot tell the neighbours apart:
  *                  clusters far from the origin, k = R) sends more queries down those slower
  *                  paths.
