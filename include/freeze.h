@@ -321,13 +321,16 @@ int freeze_lookup_stats_attach(freeze_ctx *ctx, void *counters);
  * (query preparation, distance pass, finishing kernels) for up to FREEZE_PROFILE_MAX_CALLS
  * calls; enable = 1: all four stage boundaries; enable = 2: only the two around the distance
  * pass (an event costs a few microseconds of stream time, which shows next to a 0.2 ms look-up;
- * the other two stages then read 0); enable = 0: off.  freeze_profile_read waits for the recorded
+ * the other two stages then read 0); enable = 3: as 2, for every FREEZE_PROFILE_SAMPLE-th look-up
+ * only, starting with the first (for look-ups so short that even two events per call show);
+ * enable = 0: off.  freeze_profile_read waits for the recorded
  * events, adds up the stage durations and clears the record.
  *   stage_ms  host array [3]: summed milliseconds of {prep, distance pass, finish}.
  *   calls     host: number of look-ups the sums cover.
  * Events are host-side objects; no device memory is allocated.
  */
 #define FREEZE_PROFILE_MAX_CALLS 256
+#define FREEZE_PROFILE_SAMPLE 8
 int freeze_profile_enable(freeze_ctx *ctx, int enable);
 int freeze_profile_read(freeze_ctx *ctx, float *stage_ms, int *calls);
 /* Same, per look-up: call_ms is a host array [max_calls][3], filled in call order (a cascade

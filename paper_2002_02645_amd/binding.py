@@ -332,7 +332,8 @@ def freeze_lookup_stats_attach(ctx, counters: Optional[torch.Tensor]) -> None:
 
 
 def freeze_profile_enable(ctx, enable) -> None:
-    """enable: 0 / False off, 1 / True events at every stage boundary, 2 events around the distance pass only."""
+    """enable: 0 / False off, 1 / True events at every stage boundary, 2 events around the distance pass only,
+    3 the same for every eighth look-up."""
     _check(lib().freeze_profile_enable(ctx, int(enable)), "freeze_profile_enable")
 
 

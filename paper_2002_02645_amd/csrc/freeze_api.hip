@@ -15,7 +15,9 @@ struct freeze_ctx {
     std::vector<LayerCache> layers;
     int num_cus = 256;
     // stage timing (measurement aid): 4 events per recorded look-up
-    int profile = 0;          // 0: off; 1: events at all four stage boundaries; 2: around the distance pass only
+    int profile = 0;          // 0: off; 1: events at all four stage boundaries; 2: around the distance pass only;
+                              // 3: as 2, for every eighth look-up
+    unsigned profile_seen = 0;   // look-ups since profiling was enabled (mode 3 samples them)
     int profile_recorded = 0; // mode the recorded look-ups were taken in
     std::vector<hipEvent_t> events;
     int profiled_calls = 0;
@@ -194,6 +196,7 @@ struct StageMarks {
     int slot;   // event index of this call's first mark, or -1
     StageMarks(freeze_ctx *c, hipStream_t st) : ctx(c), s(st), slot(-1)
     {
+        if (c && c->profile == 3 && (c->profile_seen++ % FREEZE_PROFILE_SAMPLE) != 0) return;
         if (c && c->profile && c->profiled_calls < FREEZE_PROFILE_MAX_CALLS) {
             slot = 4 * c->profiled_calls;
             while ((int)c->events.size() < slot + 4) {
@@ -1011,10 +1014,11 @@ int freeze_lookup_stats_attach(freeze_ctx *ctx, void *counters)
 int freeze_profile_enable(freeze_ctx *ctx, int enable)
 {
     if (!ctx) return FREEZE_EINVAL;
-    if (enable < 0 || enable > 2) return FREEZE_EINVAL;
+    if (enable < 0 || enable > 3) return FREEZE_EINVAL;
     ctx->profile = enable;
-    if (enable) ctx->profile_recorded = enable;
+    if (enable) ctx->profile_recorded = enable == 3 ? 2 : enable;
     ctx->profiled_calls = 0;
+    ctx->profile_seen = 0;
     return FREEZE_OK;
 }
 

@@ -74,8 +74,9 @@ def test_host_side_checks_without_gpu():
         assert L.freeze_lookup_stats_attach(h, None) == binding.FREEZE_OK
         assert L.freeze_set_centring(h, 3) == binding.FREEZE_EINVAL and L.freeze_set_centring(None, 1) == binding.FREEZE_EINVAL
         assert L.freeze_set_centring(h, 0) == binding.FREEZE_OK and L.freeze_set_centring(h, 1) == binding.FREEZE_OK
-        assert L.freeze_profile_enable(h, 3) == binding.FREEZE_EINVAL
-        assert L.freeze_profile_enable(h, 2) == binding.FREEZE_OK and L.freeze_profile_enable(h, 0) == binding.FREEZE_OK
+        assert L.freeze_profile_enable(h, 4) == binding.FREEZE_EINVAL
+        assert L.freeze_profile_enable(h, 2) == binding.FREEZE_OK and L.freeze_profile_enable(h, 3) == binding.FREEZE_OK
+        assert L.freeze_profile_enable(h, 0) == binding.FREEZE_OK
     finally:
         assert L.freeze_destroy(h) == binding.FREEZE_OK
     assert L.freeze_destroy(None) == binding.FREEZE_EINVAL

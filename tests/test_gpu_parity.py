@@ -457,6 +457,13 @@ def test_empty_batch_and_stage_timing():
         binding.freeze_profile_enable(fc.ctx, False)
         fc.lookup(0, q, 3, 2)
         assert binding.freeze_profile_read(fc.ctx)[1] == 0
+        # the sampled mode brackets the distance pass of every eighth look-up, the first included
+        binding.freeze_profile_enable(fc.ctx, 3)
+        for _ in range(17):
+            fc.lookup(0, q, 3, 2)
+        calls = binding.freeze_profile_read_calls(fc.ctx)
+        assert len(calls) == 3 and all(c[0] == 0.0 and c[1] > 0.0 and c[2] == 0.0 for c in calls)
+        binding.freeze_profile_enable(fc.ctx, False)
     finally:
         fc.close()
 
