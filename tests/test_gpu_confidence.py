@@ -87,6 +87,8 @@ def test_config1_confidence_full_batch():
     (3000, 2048, 100, 10, 0, torch.bfloat16),  # keys-out kernel
     (1500, 192, 9, 33, 0, torch.bfloat16),     # k > 24
     (300, 64, 1, 1, 0, torch.float32),         # k = 1: confidence = 1 / distance
+    (1200, 4096, 300, 10, 0, torch.bfloat16),  # long activations: the two-step re-scoring in front of the rule
+    (900, 4104, 40, 20, 0, torch.float32),     # ... width 32, keys-out kernel, fp32 cache
 ])
 def test_confidence_shapes_random_labels(n, d, b, k, r, dtype):
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
