@@ -266,6 +266,28 @@ def test_two_step_rescoring_on_dense_data(n, d, b, k, offset, dtype):
     assert c.sum() == b, c
 
 
+@pytest.mark.parametrize("frac,scale,dtype", [
+    (0.01, 100.0, torch.bfloat16),    # five channels in 512 a hundred times larger than the rest
+    (0.004, 300.0, torch.float32),    # two channels three hundred times larger: they carry nearly all of every distance
+])
+def test_outlier_channels(frac, scale, dtype):
+    """Activations with a few channels far larger than the others (common in trained networks): the
+    distances are dominated by those channels, the bf16 keys resolve the rest poorly, and more
+    queries need the wider re-scoring; the results stay the oracle's."""
+    n, d, b, k = 4000, 512, 300, 10
+    wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=n, batch=b)
+    spec = type(wl.layers[0])(n, d, 10, 0.8, relu=True, store_bf16=(dtype == torch.bfloat16))
+    data = synth.make_workload(type(wl)(wl.name, (spec,), b, k, (8,), 0, 31337))
+    L = data.layers[0]
+    g = torch.Generator().manual_seed(5)
+    cols = torch.randperm(d, generator=g)[: max(1, int(d * frac))]
+    ent = L.entries.float().clone()
+    q = data.queries[0].clone()
+    ent[:, cols] *= scale
+    q[:, cols] *= scale
+    check_case(ent.to(L.entries.dtype), L.labels, q, 10, k, 8)
+
+
 def test_certificate_verdicts_on_clustered_data():
     # the paper's kind of input: nearly every query is confirmed after the first re-scoring
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=20000, d_div=4, batch=2000)
