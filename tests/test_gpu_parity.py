@@ -288,6 +288,38 @@ def test_outlier_channels(frac, scale, dtype):
     check_case(ent.to(L.entries.dtype), L.labels, q, 10, k, 8)
 
 
+@pytest.mark.parametrize("kind,dtype", [
+    ("student_t2", torch.bfloat16),       # heavy tails: a few huge coordinates per row
+    ("sparse", torch.bfloat16),           # 95 % zeros
+    ("scale_1e6", torch.float32),         # large magnitudes (squares of 1e12 per coordinate)
+    ("scale_1e-6", torch.bfloat16),       # small magnitudes
+    ("binary", torch.float32),            # 0 / 1 entries: integer distances, many exact ties at the k-th place
+    ("bytes", torch.bfloat16),            # integers 0 .. 255 (exact in bf16)
+])
+def test_value_distributions(kind, dtype):
+    """Inputs unlike the benchmark's Gaussian clusters; every one must still give the oracle's answer
+    (ties at the k-th place go by the entry index, which the certificate leaves to the wider re-scoring)."""
+    g = torch.Generator().manual_seed(7)
+    n, d, b, k = 6000, 768, 400, 10
+    lab = torch.randint(0, 10, (n,), generator=g, dtype=torch.int32)
+    cent = torch.randn(10, d, generator=g)
+    ce, cq = cent[lab.long()], cent[torch.randint(0, 10, (b,), generator=g)]
+    if kind == "student_t2":
+        t = torch.distributions.StudentT(2.0)
+        torch.manual_seed(11)
+        e, q = ce + t.sample((n, d)), cq + t.sample((b, d))
+    elif kind == "sparse":
+        e, q = torch.relu(ce + torch.randn(n, d, generator=g) - 1.8), torch.relu(cq + torch.randn(b, d, generator=g) - 1.8)
+    elif kind in ("scale_1e6", "scale_1e-6"):
+        f = 1e6 if kind == "scale_1e6" else 1e-6
+        e, q = (ce + 0.8 * torch.randn(n, d, generator=g)) * f, (cq + 0.8 * torch.randn(b, d, generator=g)) * f
+    elif kind == "binary":
+        e, q = (torch.rand(n, d, generator=g) < 0.3).float(), (torch.rand(b, d, generator=g) < 0.3).float()
+    else:
+        e, q = torch.randint(0, 256, (n, d), generator=g).float(), torch.randint(0, 256, (b, d), generator=g).float()
+    check_case(e.to(dtype), lab, q, 10, k, 8)
+
+
 def test_certificate_verdicts_on_clustered_data():
     # the paper's kind of input: nearly every query is confirmed after the first re-scoring
     wl = synth.scaled(synth.WORKLOADS["c2_batched"], n=20000, d_div=4, batch=2000)
